@@ -1,0 +1,165 @@
+/*
+ * ppsd.h -- C ABI of the MI355X (gfx950) library for pipeline-parallel early-exit
+ * self-speculative decoding, batch 1, one GPU.
+ *
+ * The method (paper Sec. 3.1, 4.1, 4.2 and Alg. 1): the first E layers of a
+ * decoder-only transformer plus an early-exit head draft token t+1 while layers
+ * E+1..N plus the LM head verify token t, reusing the draft pass's hidden state
+ * and KV cache.  The verifier's token is compared with the draft for the same
+ * position; on a mismatch the draft and everything computed from it (its KV rows,
+ * its hidden state, the next draft) are dropped and drafting restarts from the
+ * verifier's token.  With greedy (argmax) heads the committed stream equals vanilla
+ * greedy autoregressive decoding of the full model (Sec. 5.1, "Evaluation Metrics").
+ *
+ * Conventions
+ *   - Every function returns 0 on success or a negative PPSD_E* code; it never
+ *     throws.  ppsd_last_error() returns a thread-local message for the last
+ *     failure on the calling thread.
+ *   - Pointers marked DEVICE are HIP device pointers on the current device;
+ *     pointers marked HOST are ordinary host pointers.  The caller owns all of
+ *     them.  Device memory handed over in ppsd_buffers is BORROWED: it must stay
+ *     alive and unmodified (weights) / untouched (workspace) until ppsd_free().
+ *   - The library allocates no device memory.  It owns the host-side context, a
+ *     few HIP events, captured graphs and one small pinned host block.
+ *   - Calls on one context must not overlap.  The library synchronises the two
+ *     streams it was given before returning from prefill/decode.
+ *   - Matrices are row-major [out_features, in_features] in the storage dtype;
+ *     norm gains are fp32.  Residual stream, accumulators, softmax and logits
+ *     are fp32.
+ */
+#ifndef PPSD_H
+#define PPSD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PPSD_OK         0
+#define PPSD_EARG      (-1)  /* bad argument or unsupported configuration */
+#define PPSD_ESTATE    (-2)  /* call out of order (e.g. decode before prefill) */
+#define PPSD_ECAPACITY (-3)  /* sequence would exceed max_seq, or workspace too small */
+#define PPSD_EHIP      (-4)  /* a HIP call failed; message holds hipGetErrorString */
+
+#define PPSD_FP32 0
+#define PPSD_BF16 1
+
+/* Scheduling of one decode step (Sec. 4.1-4.2).  All modes run the same kernels. */
+#define PPSD_MODE_VANILLA    0  /* autoregressive: all N layers + LM head per token, no draft */
+#define PPSD_MODE_SERIAL     1  /* draft stage then verify stage on one stream */
+#define PPSD_MODE_OVERLAP    2  /* draft stage and verify stage on two streams (verify-while-draft) */
+
+typedef struct ppsd_ctx ppsd_ctx;
+
+typedef struct {
+  int32_t n_layers;        /* N (paper) */
+  int32_t exit_layer;      /* E: the draft model is layers 1..E; 1 <= E < N */
+  int32_t d_model;
+  int32_t n_heads;         /* query heads */
+  int32_t n_kv_heads;      /* n_heads / n_kv_heads in {1,2,4,8} */
+  int32_t head_dim;        /* 64 or 128 */
+  int32_t d_ffn;
+  int32_t vocab;
+  int32_t dtype;           /* PPSD_FP32 / PPSD_BF16: storage of weights and KV cache */
+  int32_t max_seq;         /* capacity in positions (prompt + generated + 1 speculative) */
+  int32_t kv_page_tokens;  /* positions per KV page: 8, 16, 32 or 64 */
+  int32_t mode;            /* PPSD_MODE_* */
+  float   rope_base;       /* rotary base; pair (i, i+hd/2) turns by pos * base^(-2i/hd) */
+  float   rms_eps;
+  int32_t debug_logits;    /* >0: keep the LM-head logits behind the first debug_logits committed
+                              tokens (token #0 = the one prefill returns) for ppsd_read_logits */
+  int32_t use_graph;       /* 1: replay one captured HIP graph per step; 0: launch kernels directly */
+  int32_t time_kernels;    /* 1: profiling mode -- direct launches on one stream with a HIP event
+                              pair around every kernel, totals via ppsd_kernel_times (slow) */
+  int32_t reserved[7];     /* must be zero */
+} ppsd_config;
+
+/* DEVICE pointers, BORROWED.  Per-layer entries are HOST arrays of n_layers DEVICE pointers. */
+typedef struct {
+  const void *embed;        /* [vocab, d_model] storage dtype */
+  const void *final_norm;   /* [d_model] fp32 */
+  const void *lm_head;      /* [vocab, d_model] */
+  const void *exit_norm;    /* [d_model] fp32: gain of the early-exit norm head (Sec. 3.1) */
+  const void *exit_head;    /* [vocab, d_model] */
+  const void *const *attn_norm;  /* [d_model] fp32 each */
+  const void *const *wqkv;       /* [(n_heads + 2 n_kv_heads) * head_dim, d_model]: q heads, k heads, v heads */
+  const void *const *wo;         /* [d_model, n_heads * head_dim] */
+  const void *const *mlp_norm;   /* [d_model] fp32 each */
+  const void *const *wgu;        /* [2 d_ffn, d_model]: gate rows then up rows */
+  const void *const *wdown;      /* [d_model, d_ffn] */
+  void  *workspace;              /* >= ppsd_workspace_bytes(cfg) bytes, 256-byte aligned: KV pages,
+                                    activations, device-side decode state.  Contents are the library's. */
+  size_t workspace_bytes;
+  void  *stream_draft;           /* hipStream_t (not the legacy default stream) */
+  void  *stream_verify;          /* hipStream_t, distinct from stream_draft, same (default) priority */
+  const int32_t *kv_page_table;  /* HOST, optional: permutation of 0..n_pages-1 mapping logical KV page
+                                    -> physical page; NULL = identity.  n_pages = ceil(max_seq / kv_page_tokens) */
+} ppsd_buffers;
+
+/* Counters since the last ppsd_prefill (paper metrics: AR = accepted / drafts_compared, Sec. 5.1). */
+typedef struct {
+  int64_t committed;         /* tokens returned by ppsd_decode */
+  int64_t drafts_compared;   /* drafts that met their verifier token */
+  int64_t accepted;
+  int64_t rejected;
+  int64_t steps_overlapped;  /* steps that ran both stages */
+  int64_t steps_draft_only;  /* pipeline-refill steps: draft stage only, nothing committed */
+  int64_t kv_rollbacks;      /* rejected drafts whose KV rows (layers 1..E) were dropped */
+  int64_t steps_launched;    /* steps the host enqueued, including ones that found nothing to do */
+  double  device_ms;         /* HIP-event time spent inside ppsd_decode */
+} ppsd_stats_t;
+
+#define PPSD_N_KERNEL_KINDS 7   /* qkv, attention, o_proj, gate_up, down, head, commit */
+typedef struct {
+  double  total_us[PPSD_N_KERNEL_KINDS];  /* sum of event-measured durations of ACTIVE launches */
+  int64_t launches[PPSD_N_KERNEL_KINDS];
+} ppsd_kernel_times_t;
+
+/* Bytes of workspace a context with this configuration needs.  0 if cfg is invalid. */
+size_t ppsd_workspace_bytes(const ppsd_config *cfg);
+
+/* Validates cfg, records the borrowed pointers, builds the rotary table (computed in double on
+ * the host) and the KV page table, zeroes the device state.  *out receives the context. */
+int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *bufs, ppsd_ctx **out);
+
+/* Resets the sequence, runs the full model over prompt (HOST, n_prompt >= 1 ids in [0, vocab)),
+ * fills the KV cache of all layers for positions 0..n_prompt-1 and writes generated token #0 (the
+ * full model's greedy token after the prompt) to *first_token (HOST).  The pipeline is left empty:
+ * the first decode step is a draft-only step.  PPSD_ECAPACITY if n_prompt + 2 > max_seq. */
+int ppsd_prefill(ppsd_ctx *ctx, const int32_t *prompt, int32_t n_prompt, int32_t *first_token);
+
+/* Commits exactly n_tokens further tokens into out_tokens (HOST) and sets *n_written = n_tokens.
+ * One step drafts with layers 1..E + exit head and verifies with layers E+1..N + LM head
+ * (Sec. 4.2); accept/reject and KV rollback happen on the device (Alg. 1).  Resumable: a second
+ * call continues the same sequence, keeping an in-flight draft.  PPSD_ESTATE before prefill;
+ * PPSD_ECAPACITY if the sequence plus one speculative position would pass max_seq. */
+int ppsd_decode(ppsd_ctx *ctx, int32_t n_tokens, int32_t *out_tokens, int32_t *n_written);
+
+/* Copies the counters (HOST out). */
+int ppsd_stats(const ppsd_ctx *ctx, ppsd_stats_t *out);
+
+/* Debug/parity: logits behind committed tokens first..first+count-1 (token #0 = prefill's) into
+ * out (HOST, count * vocab floats).  Needs debug_logits >= first + count. */
+int ppsd_read_logits(ppsd_ctx *ctx, int32_t first, int32_t count, float *out);
+
+/* Debug/parity: for committed tokens first..first+count-1, the draft that was compared with it,
+ * or -1 if the token was committed without a draft (token #0, vanilla mode). HOST out. */
+int ppsd_read_drafts(ppsd_ctx *ctx, int32_t first, int32_t count, int32_t *out);
+
+/* Profiling mode only (time_kernels = 1): accumulated per-kind kernel durations. */
+int ppsd_kernel_times(const ppsd_ctx *ctx, ppsd_kernel_times_t *out);
+
+/* Measurement support: times `iters` launches of a pure streaming-read kernel over a DEVICE
+ * buffer of `bytes` bytes on `stream` (hipStream_t) and writes the average ms per launch.
+ * Gives the HBM read rate a kernel on this chip can actually reach. */
+int ppsd_hbm_read_probe(const void *buf, size_t bytes, void *stream, int32_t iters, float *avg_ms);
+
+void ppsd_free(ppsd_ctx *ctx);
+const char *ppsd_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PPSD_H */

@@ -1,0 +1,39 @@
+"""Compiles the HIP library for gfx950 in-tree (paper_2509_19368_amd/libppsd.so)."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libppsd.so")
+SOURCES = [os.path.join(HERE, "csrc", "ppsd_api.hip")]
+HEADERS = [os.path.join(HERE, "csrc", "ppsd_device.h"), os.path.join(HERE, "csrc", "ppsd_kernels.h"),
+           os.path.join(os.path.dirname(HERE), "include", "ppsd.h")]
+
+HIPCC_FLAGS = [
+    "-O3", "--offload-arch=gfx950", "-std=c++17", "-shared", "-fPIC",
+    # keep the compiler from forming packed-fp32 instructions from scalar float code
+    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+]
+
+
+def build_library(verbose: bool = False) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, *HIPCC_FLAGS, "-o", LIB_PATH, *SOURCES]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + res.stdout + res.stderr)
+    if verbose:
+        print(" ".join(cmd))
+    return LIB_PATH
+
+
+def is_stale() -> bool:
+    if not os.path.exists(LIB_PATH):
+        return True
+    t = os.path.getmtime(LIB_PATH)
+    return any(os.path.getmtime(p) > t for p in SOURCES + HEADERS)
+
+
+if __name__ == "__main__":
+    print(build_library(verbose=True))

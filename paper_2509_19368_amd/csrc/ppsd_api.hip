@@ -1,0 +1,640 @@
+// Host side of the C ABI declared in include/ppsd.h: context, workspace layout, the one-GPU
+// step scheduler (draft stage and verify stage on two streams, one commit kernel per step,
+// optionally replayed from a captured HIP graph) and the decode loop.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/ppsd.h"
+#include "ppsd_kernels.h"
+
+using namespace ppsd;
+
+namespace {
+
+thread_local std::string g_err;
+
+int fail(int code, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  g_err = buf;
+  return code;
+}
+
+#define HIP_TRY(expr)                                                                     \
+  do {                                                                                    \
+    hipError_t e_ = (expr);                                                               \
+    if (e_ != hipSuccess) return fail(PPSD_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+// rows per wave of the row-streaming kernels
+constexpr int kQkvPairs = 2;
+constexpr int kGuPairs = 2;
+constexpr int kProjRows = 4;
+constexpr int kHeadRows = 4;
+
+enum Kind { kKQkv = 0, kKAttn, kKOproj, kKGateUp, kKDown, kKHead, kKCommit };
+
+struct Layout {
+  size_t state, prompt, out_tokens, drafts, page_table, rope_cos, rope_sin, xbuf;
+  size_t q[2], a[2], mbuf[2], partials[2], counters[2], cand_lm, cand_exit, sink, logits, kv;
+  size_t total;
+  int n_pages, n_splits, head_blocks;
+};
+
+bool valid_config(const ppsd_config *c, const char **why) {
+#define REJECT(cond, msg) if (cond) { *why = msg; return false; }
+  REJECT(!c, "null config");
+  REJECT(c->n_layers < 2 || c->exit_layer < 1 || c->exit_layer >= c->n_layers, "need 1 <= exit_layer < n_layers");
+  REJECT(c->head_dim != 64 && c->head_dim != 128, "head_dim must be 64 or 128");
+  REJECT(c->n_heads < 1 || c->n_kv_heads < 1 || c->n_heads % c->n_kv_heads, "n_heads must be a multiple of n_kv_heads");
+  const int g = c->n_kv_heads ? c->n_heads / c->n_kv_heads : 0;
+  REJECT(g != 1 && g != 2 && g != 4, "n_heads / n_kv_heads must be 1, 2 or 4");
+  REJECT(c->dtype != PPSD_FP32 && c->dtype != PPSD_BF16, "dtype must be PPSD_FP32 or PPSD_BF16");
+  const int vec = c->dtype == PPSD_FP32 ? 4 : 8;
+  REJECT(c->d_model < vec || c->d_model % vec, "d_model must be a multiple of the 16-byte vector width");
+  REJECT(c->d_ffn < vec || c->d_ffn % vec, "d_ffn must be a multiple of the 16-byte vector width");
+  REJECT(c->vocab < 2, "vocab too small");
+  REJECT(c->max_seq < 3, "max_seq too small");
+  REJECT(c->kv_page_tokens != 8 && c->kv_page_tokens != 16 && c->kv_page_tokens != 32 && c->kv_page_tokens != 64,
+         "kv_page_tokens must be 8, 16, 32 or 64");
+  REJECT(c->mode < 0 || c->mode > 2, "mode must be 0, 1 or 2");
+  REJECT(!(c->rope_base > 1.0f) || !(c->rms_eps >= 0.0f), "bad rope_base / rms_eps");
+  REJECT(c->debug_logits < 0, "debug_logits < 0");
+  REJECT((size_t)c->d_ffn * 4 > 64 * 1024 || (size_t)c->d_model * 4 > 64 * 1024 ||
+         (size_t)c->n_heads * c->head_dim * 4 > 64 * 1024, "activation vector exceeds 64 KiB of LDS");
+  for (int k = 0; k < 7; ++k) REJECT(c->reserved[k] != 0, "reserved fields must be zero");
+#undef REJECT
+  return true;
+}
+
+Layout make_layout(const ppsd_config *c) {
+  Layout L{};
+  const size_t es = c->dtype == PPSD_FP32 ? 4 : 2;
+  L.n_pages = (c->max_seq + c->kv_page_tokens - 1) / c->kv_page_tokens;
+  int ns = (c->max_seq + 63) / 64;
+  L.n_splits = ns < 1 ? 1 : (ns > 32 ? 32 : ns);
+  L.head_blocks = (c->vocab + kHeadRows * kWavesPerBlock - 1) / (kHeadRows * kWavesPerBlock);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+  L.state = take(sizeof(DevState));
+  L.prompt = take(4ull * c->max_seq);
+  L.out_tokens = take(4ull * c->max_seq);
+  L.drafts = take(4ull * (c->max_seq + 1));
+  L.page_table = take(4ull * L.n_pages);
+  L.rope_cos = take(4ull * c->max_seq * (c->head_dim / 2));
+  L.rope_sin = take(4ull * c->max_seq * (c->head_dim / 2));
+  L.xbuf = take(4ull * 4 * c->d_model);
+  const size_t nq = (size_t)c->n_heads * c->head_dim;
+  for (int s = 0; s < 2; ++s) {
+    L.q[s] = take(4 * nq);
+    L.a[s] = take(4 * nq);
+    L.mbuf[s] = take(4ull * c->d_ffn);
+    L.partials[s] = take(4ull * c->n_heads * L.n_splits * (c->head_dim + 2));
+    L.counters[s] = take(4ull * c->n_kv_heads);
+  }
+  L.cand_lm = take(8ull * L.head_blocks);
+  L.cand_exit = take(8ull * L.head_blocks);
+  L.sink = take(256);
+  L.logits = take(4ull * c->debug_logits * c->vocab);
+  L.kv = take((size_t)c->n_layers * L.n_pages * c->n_kv_heads * 2 * c->kv_page_tokens * c->head_dim * es);
+  L.total = off;
+  return L;
+}
+
+}  // namespace
+
+struct ppsd_ctx {
+  ppsd_config cfg;
+  Layout lay;
+  Common cm;
+  const void *embed, *final_norm, *lm_head, *exit_norm, *exit_head;
+  std::vector<const void *> attn_norm, wqkv, wo, mlp_norm, wgu, wdown;
+  char *ws;
+  hipStream_t sA, sB;
+  hipEvent_t ev_fork, ev_join, ev_t0, ev_t1;
+  hipGraphExec_t g_step = nullptr;      // decode step in cfg.mode
+  hipGraphExec_t g_prefill = nullptr;   // one prompt position, no head
+  DevState *h_state = nullptr;          // pinned
+  bool prefilled = false;
+  int host_len = 0;                     // prompt length + tokens committed so far (token #0 included)
+  int64_t steps_launched = 0;
+  double device_ms = 0.0;
+  // profiling mode
+  std::vector<hipEvent_t> tk_events;
+  std::vector<int> tk_kinds;
+  size_t tk_used = 0;
+  ppsd_kernel_times_t ktimes{};
+};
+
+namespace {
+
+template <typename T> T *at(ppsd_ctx *x, size_t off) { return reinterpret_cast<T *>(x->ws + off); }
+
+// Launch helper: in profiling mode brackets the kernel with an event pair.
+struct Launcher {
+  ppsd_ctx *x;
+  hipStream_t s;
+  bool timed;
+  hipError_t err = hipSuccess;
+
+  void before(int kind) {
+    if (!timed || err != hipSuccess) return;
+    if (x->tk_used + 2 > x->tk_events.size()) {
+      for (int k = 0; k < 2; ++k) {
+        hipEvent_t e;
+        err = hipEventCreate(&e);
+        if (err != hipSuccess) return;
+        x->tk_events.push_back(e);
+      }
+    }
+    x->tk_kinds.resize(x->tk_events.size() / 2);
+    x->tk_kinds[x->tk_used / 2] = kind;
+    err = hipEventRecord(x->tk_events[x->tk_used], s);
+  }
+  void after() {
+    if (err == hipSuccess) err = hipGetLastError();
+    if (!timed || err != hipSuccess) return;
+    err = hipEventRecord(x->tk_events[x->tk_used + 1], s);
+    x->tk_used += 2;
+  }
+};
+
+template <typename WT>
+void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int xout_last_sel, bool from_embed) {
+  ppsd_ctx *x = L.x;
+  const ppsd_config &c = x->cfg;
+  const Common &cm = x->cm;
+  const int d = c.d_model, f = c.d_ffn, nq = c.n_heads * c.head_dim;
+  float *q = at<float>(x, x->lay.q[stage]);
+  float *a = at<float>(x, x->lay.a[stage]);
+  float *mb = at<float>(x, x->lay.mbuf[stage]);
+  // residual slot used inside the layer after the first residual add
+  const int xwork = (role == kVerify) ? kXVerify : kXDraft;
+
+  const int total_pairs = (c.n_heads + 2 * c.n_kv_heads) * (c.head_dim / 2);
+  const int qkv_blocks = (total_pairs + kQkvPairs * kWavesPerBlock - 1) / (kQkvPairs * kWavesPerBlock);
+  L.before(kKQkv);
+  hipLaunchKernelGGL((k_qkv<WT, kQkvPairs>), dim3(qkv_blocks), dim3(kBlock), (size_t)d * 4, L.s, cm, role, layer,
+                     xin_sel, from_embed ? 1 : 0, (const WT *)x->embed, (const float *)x->attn_norm[layer],
+                     (const WT *)x->wqkv[layer], q);
+  L.after();
+
+  const dim3 agrid(c.n_kv_heads, x->lay.n_splits);
+  float *part = at<float>(x, x->lay.partials[stage]);
+  int *cnt = at<int>(x, x->lay.counters[stage]);
+  const int G = c.n_heads / c.n_kv_heads;
+  L.before(kKAttn);
+#define ATTN(HD, GG) hipLaunchKernelGGL((k_attn<WT, HD, GG>), agrid, dim3(kBlock), 0, L.s, cm, role, layer, \
+                                        (const float *)q, a, part, cnt)
+  if (c.head_dim == 64) { if (G == 1) ATTN(64, 1); else if (G == 2) ATTN(64, 2); else ATTN(64, 4); }
+  else { if (G == 1) ATTN(128, 1); else if (G == 2) ATTN(128, 2); else ATTN(128, 4); }
+#undef ATTN
+  L.after();
+
+  const int oproj_blocks = (d + kProjRows * kWavesPerBlock - 1) / (kProjRows * kWavesPerBlock);
+  L.before(kKOproj);
+  hipLaunchKernelGGL((k_proj_resid<WT, kProjRows>), dim3(oproj_blocks), dim3(kBlock), (size_t)nq * 4, L.s, cm, role,
+                     (const float *)a, nq, (const WT *)x->wo[layer], d, xin_sel, xwork);
+  L.after();
+
+  const int gu_blocks = (f + kGuPairs * kWavesPerBlock - 1) / (kGuPairs * kWavesPerBlock);
+  L.before(kKGateUp);
+  hipLaunchKernelGGL((k_gate_up<WT, kGuPairs>), dim3(gu_blocks), dim3(kBlock), (size_t)d * 4, L.s, cm, role, xwork,
+                     (const float *)x->mlp_norm[layer], (const WT *)x->wgu[layer], mb);
+  L.after();
+
+  L.before(kKDown);
+  hipLaunchKernelGGL((k_proj_resid<WT, kProjRows>), dim3(oproj_blocks), dim3(kBlock), (size_t)f * 4, L.s, cm, role,
+                     (const float *)mb, f, (const WT *)x->wdown[layer], d, xwork, xout_last_sel);
+  L.after();
+}
+
+template <typename WT>
+void launch_head(Launcher &L, int role, int xin_sel, bool is_lm) {
+  ppsd_ctx *x = L.x;
+  const ppsd_config &c = x->cfg;
+  float2 *cand = at<float2>(x, is_lm ? x->lay.cand_lm : x->lay.cand_exit);
+  float *logits = c.debug_logits > 0 ? at<float>(x, x->lay.logits) : nullptr;
+  L.before(kKHead);
+  hipLaunchKernelGGL((k_head<WT, kHeadRows>), dim3(x->lay.head_blocks), dim3(kBlock), (size_t)c.d_model * 4, L.s,
+                     x->cm, role, xin_sel, (const float *)(is_lm ? x->final_norm : x->exit_norm),
+                     (const WT *)(is_lm ? x->lm_head : x->exit_head), cand, logits, is_lm ? 1 : 0);
+  L.after();
+}
+
+void launch_commit(Launcher &L, int kind) {
+  ppsd_ctx *x = L.x;
+  L.before(kKCommit);
+  hipLaunchKernelGGL(k_commit, dim3(1), dim3(kBlock), 0, L.s, x->cm, kind, at<const float2>(x, x->lay.cand_lm),
+                     at<const float2>(x, x->lay.cand_exit), at<int32_t>(x, x->lay.out_tokens),
+                     at<int32_t>(x, x->lay.drafts));
+  L.after();
+}
+
+// A stage = a run of layers [lo, hi) for one role.  The first layer reads xin_first (or the
+// embedding); the last layer's down-projection writes xout_last.
+template <typename WT>
+void launch_stage(Launcher &L, int role, int lo, int hi, int stage, int xin_first, bool from_embed, int xout_last) {
+  const int xwork = (role == kVerify) ? kXVerify : kXDraft;
+  for (int l = lo; l < hi; ++l)
+    launch_layer<WT>(L, role, l, stage, l == lo ? xin_first : xwork, l == hi - 1 ? xout_last : xwork,
+                     from_embed && l == lo);
+}
+
+// One decode step in the given mode.  With two_streams the verify stage goes to stream B between
+// a fork event and a join event (also valid under stream capture).
+template <typename WT>
+hipError_t enqueue_step(ppsd_ctx *x, int mode, bool two_streams, bool timed) {
+  const ppsd_config &c = x->cfg;
+  Launcher A{x, x->sA, timed};
+  if (mode == PPSD_MODE_VANILLA) {
+    launch_stage<WT>(A, kVanilla, 0, c.n_layers, 0, kXDraft, true, kXDraft);
+    launch_head<WT>(A, kVanilla, kXDraft, true);
+    launch_commit(A, 0);
+    return A.err;
+  }
+  Launcher B{x, two_streams ? x->sB : x->sA, timed};
+  if (two_streams) {
+    hipError_t e = hipEventRecord(x->ev_fork, x->sA);
+    if (e != hipSuccess) return e;
+    e = hipStreamWaitEvent(x->sB, x->ev_fork, 0);
+    if (e != hipSuccess) return e;
+  }
+  // draft stage: layers 1..E + exit head; its last layer writes the other hExit buffer
+  launch_stage<WT>(A, kDraft, 0, c.exit_layer, 0, kXDraft, true, kHExitNext);
+  launch_head<WT>(A, kDraft, kHExitNext, false);
+  // verify stage: layers E+1..N + LM head on the hidden state kept from the previous step
+  launch_stage<WT>(B, kVerify, c.exit_layer, c.n_layers, 1, kHExitCur, false, kXVerify);
+  launch_head<WT>(B, kVerify, kXVerify, true);
+  if (B.err != hipSuccess) return B.err;
+  if (two_streams) {
+    hipError_t e = hipEventRecord(x->ev_join, x->sB);
+    if (e != hipSuccess) return e;
+    e = hipStreamWaitEvent(x->sA, x->ev_join, 0);
+    if (e != hipSuccess) return e;
+  }
+  launch_commit(A, 1);
+  return A.err;
+}
+
+template <typename WT>
+hipError_t enqueue_prefill_pos(ppsd_ctx *x, bool last, bool timed) {
+  Launcher A{x, x->sA, timed};
+  launch_stage<WT>(A, kPrefill, 0, x->cfg.n_layers, 0, kXDraft, true, kXDraft);
+  if (last) launch_head<WT>(A, kPrefill, kXDraft, true);
+  launch_commit(A, last ? 3 : 2);
+  return A.err;
+}
+
+hipError_t enqueue_step_any(ppsd_ctx *x, int mode, bool two_streams, bool timed) {
+  return x->cfg.dtype == PPSD_FP32 ? enqueue_step<float>(x, mode, two_streams, timed)
+                                   : enqueue_step<bf16_t>(x, mode, two_streams, timed);
+}
+hipError_t enqueue_prefill_any(ppsd_ctx *x, bool last, bool timed) {
+  return x->cfg.dtype == PPSD_FP32 ? enqueue_prefill_pos<float>(x, last, timed)
+                                   : enqueue_prefill_pos<bf16_t>(x, last, timed);
+}
+
+template <typename F>
+int capture(ppsd_ctx *x, hipGraphExec_t *out, F &&body) {
+  hipGraph_t g = nullptr;
+  HIP_TRY(hipStreamBeginCapture(x->sA, hipStreamCaptureModeRelaxed));
+  hipError_t e = body();
+  hipError_t e2 = hipStreamEndCapture(x->sA, &g);
+  if (e != hipSuccess) { if (g) (void)hipGraphDestroy(g); return fail(PPSD_EHIP, "capture body: %s", hipGetErrorString(e)); }
+  if (e2 != hipSuccess) return fail(PPSD_EHIP, "hipStreamEndCapture: %s", hipGetErrorString(e2));
+  hipError_t e3 = hipGraphInstantiate(out, g, nullptr, nullptr, 0);
+  (void)hipGraphDestroy(g);
+  if (e3 != hipSuccess) return fail(PPSD_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(e3));
+  return PPSD_OK;
+}
+
+// Drains the event pairs recorded in profiling mode into the per-kind totals.  A launch whose
+// stage was idle lasts a few microseconds and would distort the averages; those are skipped by
+// the caller passing which kinds were active (all launches in serial profiling steps are
+// counted only if the step's stage ran, see decode loop).
+int drain_kernel_events(ppsd_ctx *x, const std::vector<char> *active_mask) {
+  for (size_t k = 0; k + 1 < x->tk_used; k += 2) {
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, x->tk_events[k], x->tk_events[k + 1]));
+    if (active_mask && !(*active_mask)[k / 2]) continue;
+    const int kind = x->tk_kinds[k / 2];
+    x->ktimes.total_us[kind] += 1000.0 * ms;
+    x->ktimes.launches[kind] += 1;
+  }
+  x->tk_used = 0;
+  return PPSD_OK;
+}
+
+int read_state(ppsd_ctx *x) {
+  HIP_TRY(hipMemcpyAsync(x->h_state, at<DevState>(x, x->lay.state), sizeof(DevState), hipMemcpyDeviceToHost, x->sA));
+  HIP_TRY(hipStreamSynchronize(x->sA));
+  return PPSD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *ppsd_last_error(void) { return g_err.c_str(); }
+
+size_t ppsd_workspace_bytes(const ppsd_config *cfg) {
+  const char *why = "";
+  if (!valid_config(cfg, &why)) { fail(PPSD_EARG, "invalid config: %s", why); return 0; }
+  return make_layout(cfg).total;
+}
+
+int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *b, ppsd_ctx **out) {
+  const char *why = "";
+  if (!out) return fail(PPSD_EARG, "out is null");
+  *out = nullptr;
+  if (!valid_config(cfg, &why)) return fail(PPSD_EARG, "invalid config: %s", why);
+  if (!b) return fail(PPSD_EARG, "buffers is null");
+  if (!b->embed || !b->final_norm || !b->lm_head || !b->exit_norm || !b->exit_head || !b->attn_norm || !b->wqkv ||
+      !b->wo || !b->mlp_norm || !b->wgu || !b->wdown || !b->workspace)
+    return fail(PPSD_EARG, "a weight or workspace pointer is null");
+  if (!b->stream_draft || !b->stream_verify || b->stream_draft == b->stream_verify)
+    return fail(PPSD_EARG, "two distinct non-default streams are required");
+  const Layout lay = make_layout(cfg);
+  if (b->workspace_bytes < lay.total)
+    return fail(PPSD_ECAPACITY, "workspace has %zu bytes, %zu needed", b->workspace_bytes, lay.total);
+  if ((uintptr_t)b->workspace % kAlign) return fail(PPSD_EARG, "workspace must be 256-byte aligned");
+  for (int l = 0; l < cfg->n_layers; ++l) {
+    const void *ps[6] = {b->attn_norm[l], b->wqkv[l], b->wo[l], b->mlp_norm[l], b->wgu[l], b->wdown[l]};
+    for (const void *p : ps) {
+      if (!p) return fail(PPSD_EARG, "layer %d has a null weight pointer", l);
+      if ((uintptr_t)p % 16) return fail(PPSD_EARG, "layer %d has a weight pointer that is not 16-byte aligned", l);
+    }
+  }
+  const void *gl[5] = {b->embed, b->final_norm, b->lm_head, b->exit_norm, b->exit_head};
+  for (const void *p : gl)
+    if ((uintptr_t)p % 16) return fail(PPSD_EARG, "a global weight pointer is not 16-byte aligned");
+  std::vector<int32_t> table(lay.n_pages);
+  {
+    std::vector<char> seen(lay.n_pages, 0);
+    for (int p = 0; p < lay.n_pages; ++p) {
+      const int32_t v = b->kv_page_table ? b->kv_page_table[p] : p;
+      if (v < 0 || v >= lay.n_pages || seen[v]) return fail(PPSD_EARG, "kv_page_table is not a permutation");
+      seen[v] = 1;
+      table[p] = v;
+    }
+  }
+
+  ppsd_ctx *x = new (std::nothrow) ppsd_ctx();
+  if (!x) return fail(PPSD_EARG, "out of host memory");
+  x->cfg = *cfg;
+  x->lay = lay;
+  x->ws = (char *)b->workspace;
+  x->embed = b->embed; x->final_norm = b->final_norm; x->lm_head = b->lm_head;
+  x->exit_norm = b->exit_norm; x->exit_head = b->exit_head;
+  x->attn_norm.assign(b->attn_norm, b->attn_norm + cfg->n_layers);
+  x->wqkv.assign(b->wqkv, b->wqkv + cfg->n_layers);
+  x->wo.assign(b->wo, b->wo + cfg->n_layers);
+  x->mlp_norm.assign(b->mlp_norm, b->mlp_norm + cfg->n_layers);
+  x->wgu.assign(b->wgu, b->wgu + cfg->n_layers);
+  x->wdown.assign(b->wdown, b->wdown + cfg->n_layers);
+  x->sA = (hipStream_t)b->stream_draft;
+  x->sB = (hipStream_t)b->stream_verify;
+
+  Common &cm = x->cm;
+  cm.st = at<DevState>(x, lay.state);
+  cm.prompt = at<int32_t>(x, lay.prompt);
+  cm.xbuf = at<float>(x, lay.xbuf);
+  cm.rope_cos = at<float>(x, lay.rope_cos);
+  cm.rope_sin = at<float>(x, lay.rope_sin);
+  cm.page_table = at<int32_t>(x, lay.page_table);
+  cm.kv_pool = x->ws + lay.kv;
+  Dims &m = cm.dm;
+  m.d = cfg->d_model; m.n_h = cfg->n_heads; m.n_kv = cfg->n_kv_heads; m.hd = cfg->head_dim; m.f = cfg->d_ffn;
+  m.V = cfg->vocab; m.L = cfg->n_layers; m.E = cfg->exit_layer; m.max_seq = cfg->max_seq;
+  m.page_tokens = cfg->kv_page_tokens; m.n_pages = lay.n_pages; m.n_splits = lay.n_splits;
+  m.debug_rows = cfg->debug_logits; m.head_blocks = lay.head_blocks;
+  m.eps = cfg->rms_eps; m.qscale = (float)(1.0 / std::sqrt((double)cfg->head_dim));
+
+  auto cleanup = [&](int rc) { ppsd_free(x); return rc; };
+#define HIP_TRY_X(expr)                                                                                   \
+  do {                                                                                                    \
+    hipError_t e_ = (expr);                                                                               \
+    if (e_ != hipSuccess) return cleanup(fail(PPSD_EHIP, "%s: %s", #expr, hipGetErrorString(e_)));        \
+  } while (0)
+  HIP_TRY_X(hipEventCreateWithFlags(&x->ev_fork, hipEventDisableTiming));
+  HIP_TRY_X(hipEventCreateWithFlags(&x->ev_join, hipEventDisableTiming));
+  HIP_TRY_X(hipEventCreate(&x->ev_t0));
+  HIP_TRY_X(hipEventCreate(&x->ev_t1));
+  HIP_TRY_X(hipHostMalloc((void **)&x->h_state, sizeof(DevState), hipHostMallocDefault));
+
+  // everything before the KV pool starts from zero (state, counters, candidates, logs)
+  HIP_TRY_X(hipMemsetAsync(x->ws, 0, lay.kv, x->sA));
+  HIP_TRY_X(hipMemcpyAsync(at<int32_t>(x, lay.page_table), table.data(), 4ull * lay.n_pages, hipMemcpyHostToDevice, x->sA));
+  {
+    // rotary table in double on the host: angle = pos * base^(-2i/hd)
+    const int half = cfg->head_dim / 2;
+    std::vector<float> cs((size_t)cfg->max_seq * half), sn((size_t)cfg->max_seq * half);
+    for (int i = 0; i < half; ++i) {
+      const double theta = std::pow((double)cfg->rope_base, -2.0 * i / cfg->head_dim);
+      for (int p = 0; p < cfg->max_seq; ++p) {
+        const double ang = (double)p * theta;
+        cs[(size_t)p * half + i] = (float)std::cos(ang);
+        sn[(size_t)p * half + i] = (float)std::sin(ang);
+      }
+    }
+    HIP_TRY_X(hipMemcpyAsync(at<float>(x, lay.rope_cos), cs.data(), cs.size() * 4, hipMemcpyHostToDevice, x->sA));
+    HIP_TRY_X(hipMemcpyAsync(at<float>(x, lay.rope_sin), sn.data(), sn.size() * 4, hipMemcpyHostToDevice, x->sA));
+    HIP_TRY_X(hipStreamSynchronize(x->sA));   // host vectors go out of scope
+  }
+
+  if (cfg->use_graph && !cfg->time_kernels) {
+    int rc = capture(x, &x->g_step, [&] { return enqueue_step_any(x, cfg->mode, cfg->mode == PPSD_MODE_OVERLAP, false); });
+    if (rc != PPSD_OK) return cleanup(rc);
+    rc = capture(x, &x->g_prefill, [&] { return enqueue_prefill_any(x, false, false); });
+    if (rc != PPSD_OK) return cleanup(rc);
+  }
+#undef HIP_TRY_X
+  *out = x;
+  return PPSD_OK;
+}
+
+void ppsd_free(ppsd_ctx *x) {
+  if (!x) return;
+  if (x->sA) (void)hipStreamSynchronize(x->sA);
+  if (x->sB) (void)hipStreamSynchronize(x->sB);
+  if (x->g_step) (void)hipGraphExecDestroy(x->g_step);
+  if (x->g_prefill) (void)hipGraphExecDestroy(x->g_prefill);
+  if (x->ev_fork) (void)hipEventDestroy(x->ev_fork);
+  if (x->ev_join) (void)hipEventDestroy(x->ev_join);
+  if (x->ev_t0) (void)hipEventDestroy(x->ev_t0);
+  if (x->ev_t1) (void)hipEventDestroy(x->ev_t1);
+  for (hipEvent_t e : x->tk_events) (void)hipEventDestroy(e);
+  if (x->h_state) (void)hipHostFree(x->h_state);
+  delete x;
+}
+
+int ppsd_prefill(ppsd_ctx *x, const int32_t *prompt, int32_t n_prompt, int32_t *first_token) {
+  if (!x || !prompt || !first_token) return fail(PPSD_EARG, "null argument");
+  if (n_prompt < 1) return fail(PPSD_EARG, "n_prompt must be >= 1");
+  if (n_prompt + 2 > x->cfg.max_seq)
+    return fail(PPSD_ECAPACITY, "prompt of %d tokens does not fit max_seq %d", n_prompt, x->cfg.max_seq);
+  for (int i = 0; i < n_prompt; ++i)
+    if (prompt[i] < 0 || prompt[i] >= x->cfg.vocab) return fail(PPSD_EARG, "prompt[%d] = %d is outside the vocabulary", i, prompt[i]);
+  x->prefilled = false;
+  HIP_TRY(hipMemcpyAsync(at<int32_t>(x, x->lay.prompt), prompt, 4ull * n_prompt, hipMemcpyHostToDevice, x->sA));
+  hipLaunchKernelGGL(k_begin_prefill, dim3(1), dim3(64), 0, x->sA, at<DevState>(x, x->lay.state), n_prompt);
+  HIP_TRY(hipGetLastError());
+  for (int p = 0; p < n_prompt; ++p) {
+    const bool last = p == n_prompt - 1;
+    if (!last && x->g_prefill) HIP_TRY(hipGraphLaunch(x->g_prefill, x->sA));
+    else HIP_TRY(enqueue_prefill_any(x, last, false));
+  }
+  int rc = read_state(x);
+  if (rc != PPSD_OK) return rc;
+  if (x->h_state->prefill_pos != n_prompt || x->h_state->t != n_prompt)
+    return fail(PPSD_ESTATE, "prefill ended in an unexpected device state (pos %d, t %d)", x->h_state->prefill_pos, x->h_state->t);
+  *first_token = x->h_state->last_token;
+  x->prefilled = true;
+  x->host_len = n_prompt + 1;
+  x->steps_launched = 0;
+  x->device_ms = 0.0;
+  x->ktimes = ppsd_kernel_times_t{};
+  return PPSD_OK;
+}
+
+int ppsd_decode(ppsd_ctx *x, int32_t n_tokens, int32_t *out_tokens, int32_t *n_written) {
+  if (!x || !n_written || (n_tokens > 0 && !out_tokens)) return fail(PPSD_EARG, "null argument");
+  *n_written = 0;
+  if (n_tokens < 0) return fail(PPSD_EARG, "n_tokens < 0");
+  if (!x->prefilled) return fail(PPSD_ESTATE, "ppsd_decode before ppsd_prefill");
+  if (n_tokens == 0) return PPSD_OK;
+  // positions 0..host_len-1 are committed; committing n more needs rows up to host_len+n-1 plus
+  // one speculative row written by the draft stage
+  if ((int64_t)x->host_len + n_tokens + 1 > x->cfg.max_seq)
+    return fail(PPSD_ECAPACITY, "%d committed + %d new + 1 speculative position exceed max_seq %d", x->host_len, n_tokens,
+                x->cfg.max_seq);
+  const ppsd_config &c = x->cfg;
+  const bool timed = c.time_kernels != 0;
+  const bool two = c.mode == PPSD_MODE_OVERLAP && !timed;
+  hipLaunchKernelGGL(k_begin_decode, dim3(1), dim3(64), 0, x->sA, at<DevState>(x, x->lay.state), n_tokens);
+  HIP_TRY(hipGetLastError());
+  HIP_TRY(hipEventRecord(x->ev_t0, x->sA));
+  int remaining = n_tokens;
+  int guard = 0;
+  while (remaining > 0) {
+    if (timed) {
+      // one step at a time so idle launches can be told apart from active ones
+      int rc = read_state(x);
+      if (rc != PPSD_OK) return rc;
+      const int was_full = x->h_state->full;
+      HIP_TRY(enqueue_step_any(x, c.mode, false, true));
+      x->steps_launched += 1;
+      rc = read_state(x);
+      if (rc != PPSD_OK) return rc;
+      std::vector<char> mask(x->tk_used / 2, 1);
+      if (c.mode != PPSD_MODE_VANILLA && !was_full) {
+        // draft-only step: the verify stage's launches (after the draft stage's 5E+1) were idle
+        const size_t draft_launches = 5u * c.exit_layer + 1;
+        for (size_t k = draft_launches; k + 1 < mask.size(); ++k) mask[k] = 0;   // keep the commit
+      }
+      rc = drain_kernel_events(x, &mask);
+      if (rc != PPSD_OK) return rc;
+    } else {
+      for (int k = 0; k < remaining; ++k) {
+        if (x->g_step) HIP_TRY(hipGraphLaunch(x->g_step, x->sA));
+        else HIP_TRY(enqueue_step_any(x, c.mode, two, false));
+      }
+      x->steps_launched += remaining;
+      int rc = read_state(x);
+      if (rc != PPSD_OK) return rc;
+    }
+    remaining = n_tokens - x->h_state->n_out;
+    if (++guard > 4 * n_tokens + 16) return fail(PPSD_ESTATE, "decode made no progress (device state n_out %d)", x->h_state->n_out);
+  }
+  HIP_TRY(hipEventRecord(x->ev_t1, x->sA));
+  HIP_TRY(hipMemcpyAsync(out_tokens, at<int32_t>(x, x->lay.out_tokens), 4ull * n_tokens, hipMemcpyDeviceToHost, x->sA));
+  HIP_TRY(hipStreamSynchronize(x->sA));
+  HIP_TRY(hipStreamSynchronize(x->sB));
+  float ms = 0.f;
+  HIP_TRY(hipEventElapsedTime(&ms, x->ev_t0, x->ev_t1));
+  x->device_ms += ms;
+  x->host_len += n_tokens;
+  *n_written = n_tokens;
+  return PPSD_OK;
+}
+
+int ppsd_stats(const ppsd_ctx *cx, ppsd_stats_t *out) {
+  if (!cx || !out) return fail(PPSD_EARG, "null argument");
+  ppsd_ctx *x = const_cast<ppsd_ctx *>(cx);
+  int rc = read_state(x);
+  if (rc != PPSD_OK) return rc;
+  const int64_t *s = x->h_state->stats;
+  out->committed = s[0]; out->drafts_compared = s[1]; out->accepted = s[2]; out->rejected = s[3];
+  out->steps_overlapped = s[4]; out->steps_draft_only = s[5]; out->kv_rollbacks = s[6];
+  out->steps_launched = x->steps_launched;
+  out->device_ms = x->device_ms;
+  return PPSD_OK;
+}
+
+int ppsd_read_logits(ppsd_ctx *x, int32_t first, int32_t count, float *out) {
+  if (!x || !out) return fail(PPSD_EARG, "null argument");
+  if (first < 0 || count < 0 || first + count > x->cfg.debug_logits)
+    return fail(PPSD_EARG, "rows %d..%d are outside the %d kept logit rows", first, first + count - 1, x->cfg.debug_logits);
+  HIP_TRY(hipMemcpyAsync(out, at<float>(x, x->lay.logits) + (size_t)first * x->cfg.vocab, 4ull * count * x->cfg.vocab,
+                         hipMemcpyDeviceToHost, x->sA));
+  HIP_TRY(hipStreamSynchronize(x->sA));
+  return PPSD_OK;
+}
+
+int ppsd_read_drafts(ppsd_ctx *x, int32_t first, int32_t count, int32_t *out) {
+  if (!x || !out) return fail(PPSD_EARG, "null argument");
+  if (first < 0 || count < 0 || first + count > x->cfg.max_seq)
+    return fail(PPSD_EARG, "rows %d..%d are outside the draft log", first, first + count - 1);
+  HIP_TRY(hipMemcpyAsync(out, at<int32_t>(x, x->lay.drafts) + first, 4ull * count, hipMemcpyDeviceToHost, x->sA));
+  HIP_TRY(hipStreamSynchronize(x->sA));
+  return PPSD_OK;
+}
+
+int ppsd_kernel_times(const ppsd_ctx *x, ppsd_kernel_times_t *out) {
+  if (!x || !out) return fail(PPSD_EARG, "null argument");
+  if (!x->cfg.time_kernels) return fail(PPSD_ESTATE, "context was not created with time_kernels = 1");
+  *out = x->ktimes;
+  return PPSD_OK;
+}
+
+int ppsd_hbm_read_probe(const void *buf, size_t bytes, void *stream, int32_t iters, float *avg_ms) {
+  if (!buf || !avg_ms || iters < 1 || bytes < 16 || (uintptr_t)buf % 16) return fail(PPSD_EARG, "bad probe argument");
+  hipStream_t s = (hipStream_t)stream;
+  hipEvent_t e0, e1;
+  HIP_TRY(hipEventCreate(&e0));
+  HIP_TRY(hipEventCreate(&e1));
+  uint32_t *sink = nullptr;   // the probe never writes in practice, but needs a valid target
+  static uint32_t *s_sink = nullptr;
+  if (!s_sink) HIP_TRY(hipHostMalloc((void **)&s_sink, 64, hipHostMallocDefault));
+  sink = s_sink;
+  const size_t n_vec = bytes / 16;
+  const int blocks = 256 * 8;
+  hipLaunchKernelGGL(k_read_probe, dim3(blocks), dim3(kBlock), 0, s, (const uint4 *)buf, n_vec, sink);   // warm-up
+  HIP_TRY(hipEventRecord(e0, s));
+  for (int k = 0; k < iters; ++k) hipLaunchKernelGGL(k_read_probe, dim3(blocks), dim3(kBlock), 0, s, (const uint4 *)buf, n_vec, sink);
+  HIP_TRY(hipEventRecord(e1, s));
+  HIP_TRY(hipStreamSynchronize(s));
+  HIP_TRY(hipGetLastError());
+  float ms = 0.f;
+  HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  *avg_ms = ms / iters;
+  return PPSD_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,253 @@
+// Device-side definitions shared by the decode kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ppsd {
+
+typedef uint16_t bf16_t;   // raw bfloat16 bits
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;          // threads per workgroup in every kernel
+constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr float kNegBig = -1.0e30f;  // finite stand-in for -inf in the running softmax maximum
+
+// Stage roles: which part of the device state a kernel takes its input from.
+enum Role : int { kVanilla = 0, kDraft = 1, kVerify = 2, kPrefill = 3 };
+
+// Residual-stream slots inside xbuf (each d floats).
+enum XSel : int { kXDraft = 0, kXVerify = 1, kHExitCur = 2, kHExitNext = 3 };
+
+// Device-resident decode state.  Only the commit kernel writes it, once per step, after
+// both stages have finished; every other kernel of the step reads a stable copy.
+struct DevState {
+  int32_t t;            // position of the last committed token
+  int32_t last_token;   // y_t
+  int32_t full;         // 1: h_t^E and draft d_{t+1} are in hand (pipeline full)
+  int32_t draft;        // d_{t+1} when full
+  int32_t cur;          // which hExit buffer holds h_t^E when full
+  int32_t n_out;        // tokens written to out_tokens by the current decode call
+  int32_t target;       // the current decode call stops at n_out == target
+  int32_t gen_count;    // tokens committed since prefill, token #0 included
+  int32_t prefill_pos;  // next prompt position to process
+  int32_t prefill_len;
+  int32_t pad[6];
+  int64_t stats[8];     // committed, compared, accepted, rejected, overlapped, draft_only, rollbacks, spare
+};
+
+struct Dims {
+  int32_t d, n_h, n_kv, hd, f, V, L, E;
+  int32_t max_seq, page_tokens, n_pages, n_splits;
+  int32_t debug_rows, head_blocks;
+  float eps, qscale;     // qscale = 1/sqrt(hd)
+};
+
+// Everything a kernel needs besides its own operands; passed by value.
+struct Common {
+  DevState *st;
+  const int32_t *prompt;      // [max_seq] prompt ids (device)
+  float *xbuf;                // [4][d]
+  const float *rope_cos;      // [max_seq][hd/2]
+  const float *rope_sin;
+  const int32_t *page_table;  // [n_pages]
+  void *kv_pool;              // [L][n_pages][n_kv][2][page_tokens][hd] storage dtype
+  Dims dm;
+};
+
+struct StageIn {
+  int active;
+  int pos;
+  int tok;
+};
+
+// Step a0 of the decode path: which token/position each stage works on.
+__device__ __forceinline__ StageIn stage_in(const Common &c, int role) {
+  const DevState *st = c.st;
+  StageIn s;
+  const int running = st->n_out < st->target;
+  if (role == kPrefill) {
+    s.active = st->prefill_pos < st->prefill_len;
+    s.pos = st->prefill_pos;
+    s.tok = s.active ? c.prompt[s.pos] : 0;
+  } else if (role == kVanilla) {
+    s.active = running;
+    s.pos = st->t;
+    s.tok = st->last_token;
+  } else if (role == kDraft) {
+    s.active = running;
+    s.pos = st->full ? st->t + 1 : st->t;
+    s.tok = st->full ? st->draft : st->last_token;
+  } else {  // kVerify
+    s.active = running && st->full;
+    s.pos = st->t;
+    s.tok = -1;
+  }
+  return s;
+}
+
+__device__ __forceinline__ float *xslot(const Common &c, int sel) {
+  int slot = sel;
+  if (sel == kHExitCur) slot = 2 + (c.st->cur & 1);
+  else if (sel == kHExitNext) slot = 2 + ((c.st->cur & 1) ^ 1);
+  return c.xbuf + (size_t)slot * c.dm.d;
+}
+
+// 16-byte streaming load (weights and probe data are read once per step: keep them out of the
+// way of the small, reused activation vectors in the caches).
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ld16_stream(const void *p) {
+  const u32x4_t v = __builtin_nontemporal_load((const u32x4_t *)p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// ---------------------------------------------------------------- numeric helpers
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t hi16_in_low) {
+  return __uint_as_float(hi16_in_low << 16);
+}
+
+__device__ __forceinline__ bf16_t float_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40u);  // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename WT> struct Pack;   // one 16-byte load
+template <> struct Pack<float> {
+  static constexpr int N = 4;
+  static __device__ __forceinline__ void unpack(const uint4 &u, float (&f)[4]) {
+    f[0] = __uint_as_float(u.x); f[1] = __uint_as_float(u.y);
+    f[2] = __uint_as_float(u.z); f[3] = __uint_as_float(u.w);
+  }
+  static __device__ __forceinline__ float to_float(float v) { return v; }
+  static __device__ __forceinline__ float from_float(float v) { return v; }
+};
+template <> struct Pack<bf16_t> {
+  static constexpr int N = 8;
+  static __device__ __forceinline__ void unpack(const uint4 &u, float (&f)[8]) {
+    f[0] = __uint_as_float(u.x << 16); f[1] = __uint_as_float(u.x & 0xffff0000u);
+    f[2] = __uint_as_float(u.y << 16); f[3] = __uint_as_float(u.y & 0xffff0000u);
+    f[4] = __uint_as_float(u.z << 16); f[5] = __uint_as_float(u.z & 0xffff0000u);
+    f[6] = __uint_as_float(u.w << 16); f[7] = __uint_as_float(u.w & 0xffff0000u);
+  }
+  static __device__ __forceinline__ float to_float(bf16_t v) { return __uint_as_float((uint32_t)v << 16); }
+  static __device__ __forceinline__ bf16_t from_float(float v) { return float_to_bf16_rne(v); }
+};
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+// Sum over the workgroup; every thread gets the result.  red: >= kWavesPerBlock floats of LDS.
+__device__ __forceinline__ float block_sum(float v, float *red) {
+  v = wave_sum(v);
+  __syncthreads();   // red may still be read from a previous use
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float s = 0.f;
+#pragma unroll
+  for (int w = 0; w < kWavesPerBlock; ++w) s += red[w];
+  return s;
+}
+
+// (value, index) ordering for argmax: larger value wins, equal values -> lower index wins.
+__device__ __forceinline__ bool better(float v, int i, float bv, int bi) {
+  return (v > bv) || (v == bv && i < bi);
+}
+
+__device__ __forceinline__ void wave_argmax(float &v, int &i) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    float ov = __shfl_xor(v, o, kWave);
+    int oi = __shfl_xor(i, o, kWave);
+    if (better(ov, oi, v, i)) { v = ov; i = oi; }
+  }
+}
+
+// ---------------------------------------------------------------- weight-streaming dot products
+// acc[r] += sum_c W[rows[r]][c] * xs[c] over this lane's columns.  xs lives in LDS, C % N == 0,
+// every row pointer 16-byte aligned.  Lane l of the wave owns columns (it*64 + l)*N .. +N.
+template <typename WT, int R>
+__device__ __forceinline__ void stream_dot(const WT *const (&rows)[R], const float *xs, int C,
+                                           float (&acc)[R]) {
+  constexpr int N = Pack<WT>::N;
+  constexpr int kStride = kWave * N;
+  const int lane = threadIdx.x & 63;
+  const int full = C / kStride;
+  int c = lane * N;
+  int it = 0;
+  // two column blocks per trip: 2*R independent 16-byte loads in flight per lane
+  for (; it + 2 <= full; it += 2, c += 2 * kStride) {
+    uint4 u0[R], u1[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      u0[r] = ld16_stream(rows[r] + c);
+      u1[r] = ld16_stream(rows[r] + c + kStride);
+    }
+    float x0[N], x1[N];
+#pragma unroll
+    for (int k = 0; k < N; ++k) { x0[k] = xs[c + k]; x1[k] = xs[c + kStride + k]; }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      float w0[N], w1[N];
+      Pack<WT>::unpack(u0[r], w0);
+      Pack<WT>::unpack(u1[r], w1);
+#pragma unroll
+      for (int k = 0; k < N; ++k) acc[r] = fmaf(w0[k], x0[k], acc[r]);
+#pragma unroll
+      for (int k = 0; k < N; ++k) acc[r] = fmaf(w1[k], x1[k], acc[r]);
+    }
+  }
+  for (; it < full; ++it, c += kStride) {
+    uint4 u0[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) u0[r] = ld16_stream(rows[r] + c);
+    float x0[N];
+#pragma unroll
+    for (int k = 0; k < N; ++k) x0[k] = xs[c + k];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      float w0[N];
+      Pack<WT>::unpack(u0[r], w0);
+#pragma unroll
+      for (int k = 0; k < N; ++k) acc[r] = fmaf(w0[k], x0[k], acc[r]);
+    }
+  }
+  if (c < C) {   // ragged tail: only the low lanes have columns left
+    float x0[N];
+#pragma unroll
+    for (int k = 0; k < N; ++k) x0[k] = xs[c + k];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      uint4 u = ld16_stream(rows[r] + c);
+      float w0[N];
+      Pack<WT>::unpack(u, w0);
+#pragma unroll
+      for (int k = 0; k < N; ++k) acc[r] = fmaf(w0[k], x0[k], acc[r]);
+    }
+  }
+}
+
+// RMSNorm prologue (step a2): xs[i] = x[i] / sqrt(mean(x^2) + eps) * gain[i], staged in LDS.
+// x may come from the embedding row (storage dtype) or from a residual slot (fp32).
+// If copy_out != nullptr the un-normalised x is also written there (block 0 only passes it).
+template <typename WT>
+__device__ __forceinline__ void load_and_norm(const float *xf, const WT *xrow, const float *gain,
+                                              int d, float eps, float *xs, float *red, float *copy_out) {
+  float ss = 0.f;
+  for (int i = threadIdx.x; i < d; i += kBlock) {
+    float v = xrow ? Pack<WT>::to_float(xrow[i]) : xf[i];
+    xs[i] = v;
+    if (copy_out) copy_out[i] = v;
+    ss = fmaf(v, v, ss);
+  }
+  ss = block_sum(ss, red);
+  const float rs = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int i = threadIdx.x; i < d; i += kBlock) xs[i] = xs[i] * rs * gain[i];
+  __syncthreads();
+}
+
+}  // namespace ppsd

@@ -1,0 +1,475 @@
+// Decode-step kernels (steps a1..a10 of one PPSD step), gfx950, wave64.
+//
+// Every kernel is launched with kBlock threads and starts by resolving its stage's input
+// from the device state (stage_in); a stage with nothing to do returns at once, so the host
+// can enqueue steps without knowing accept/reject outcomes.
+#pragma once
+
+#include "ppsd_device.h"
+
+namespace ppsd {
+
+// KV pool addressing: [layer][physical page][kv head][K=0 / V=1][slot][hd]
+template <typename WT>
+__device__ __forceinline__ WT *kv_row(const Common &c, int layer, int pos, int kvh, int which) {
+  const Dims &m = c.dm;
+  const int page = c.page_table[pos / m.page_tokens];
+  const int slot = pos % m.page_tokens;
+  size_t idx = ((((size_t)layer * m.n_pages + page) * m.n_kv + kvh) * 2 + which) * m.page_tokens + slot;
+  return (WT *)c.kv_pool + idx * m.hd;
+}
+
+// ------------------------------------------------------------------------------------------
+// a1-a3: (embedding) + RMSNorm + QKV GEMV + rotary + KV append.
+// One wave computes PAIRS row pairs (i, i + hd/2) of one head, so the rotation partner is local.
+// grid = ceil(qkv_rows / 2 / (PAIRS * 4)).
+template <typename WT, int PAIRS>
+__global__ __launch_bounds__(kBlock) void k_qkv(Common c, int role, int layer, int xin_sel, int from_embed,
+                                                const WT *embed, const float *gain, const WT *wqkv,
+                                                float *qout) {
+  extern __shared__ float xs[];
+  __shared__ float red[kWavesPerBlock];
+  const StageIn si = stage_in(c, role);
+  if (!si.active) return;
+  const Dims &m = c.dm;
+  const int d = m.d;
+  {
+    const WT *xrow = from_embed ? embed + (size_t)si.tok * d : nullptr;
+    const float *xf = from_embed ? nullptr : xslot(c, xin_sel);
+    float *copy_out = (from_embed && blockIdx.x == 0) ? xslot(c, xin_sel) : nullptr;
+    load_and_norm<WT>(xf, xrow, gain, d, m.eps, xs, red, copy_out);
+  }
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int half = m.hd >> 1;
+  const int total_pairs = (m.n_h + 2 * m.n_kv) * half;
+  const int pair0 = (blockIdx.x * kWavesPerBlock + wave) * PAIRS;
+  if (pair0 >= total_pairs) return;
+
+  const WT *rows[2 * PAIRS];
+  int head[PAIRS], idx[PAIRS];
+#pragma unroll
+  for (int p = 0; p < PAIRS; ++p) {
+    int pr = min(pair0 + p, total_pairs - 1);
+    head[p] = pr / half;
+    idx[p] = pr - head[p] * half;
+    rows[2 * p] = wqkv + (size_t)(head[p] * m.hd + idx[p]) * d;
+    rows[2 * p + 1] = rows[2 * p] + (size_t)half * d;
+  }
+  float acc[2 * PAIRS];
+#pragma unroll
+  for (int r = 0; r < 2 * PAIRS; ++r) acc[r] = 0.f;
+  stream_dot<WT, 2 * PAIRS>(rows, xs, d, acc);
+#pragma unroll
+  for (int r = 0; r < 2 * PAIRS; ++r) acc[r] = wave_sum(acc[r]);
+
+  if (lane < PAIRS && pair0 + lane < total_pairs) {
+    float lo = 0.f, hi = 0.f;
+    int h = 0, i = 0;
+#pragma unroll
+    for (int p = 0; p < PAIRS; ++p)
+      if (lane == p) { lo = acc[2 * p]; hi = acc[2 * p + 1]; h = head[p]; i = idx[p]; }
+    if (h < m.n_h + m.n_kv) {   // q or k head: rotate pair by the position angle
+      const float cs = c.rope_cos[(size_t)si.pos * half + i];
+      const float sn = c.rope_sin[(size_t)si.pos * half + i];
+      const float rlo = lo * cs - hi * sn;
+      const float rhi = hi * cs + lo * sn;
+      lo = rlo; hi = rhi;
+    }
+    if (h < m.n_h) {
+      qout[h * m.hd + i] = lo;
+      qout[h * m.hd + i + half] = hi;
+    } else {
+      const int which = (h < m.n_h + m.n_kv) ? 0 : 1;
+      const int kvh = which ? h - m.n_h - m.n_kv : h - m.n_h;
+      WT *dst = kv_row<WT>(c, layer, si.pos, kvh, which);
+      dst[i] = Pack<WT>::from_float(lo);
+      dst[i + half] = Pack<WT>::from_float(hi);
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// a4: decode attention over the paged KV cache.
+// grid = (n_kv, n_splits).  A group of GS = HD / N lanes owns one position at a time (each lane
+// holds N consecutive dims of the K and V rows, loaded as one 16-byte vector); the G query heads
+// that share this KV head reuse the same K/V registers.  Every group keeps a running softmax
+// (max, sum, weighted V) and the groups are merged through LDS in a fixed order.  With several
+// splits the last workgroup to finish a KV head merges the splits, also in fixed order.
+template <typename WT, int HD, int G>
+__global__ __launch_bounds__(kBlock) void k_attn(Common c, int role, int layer, const float *q, float *aout,
+                                                 float *partials, int *counters) {
+  constexpr int N = Pack<WT>::N;
+  constexpr int GS = HD / N;               // lanes per position
+  constexpr int GPB = kBlock / GS;         // position groups per workgroup
+  constexpr int REC = HD + 2;              // m, l, acc[HD]
+  __shared__ float merge[GPB * G * REC];
+  __shared__ int s_last;
+  const StageIn si = stage_in(c, role);
+  if (!si.active) return;
+  const Dims &m = c.dm;
+  const int kvh = blockIdx.x, split = blockIdx.y, n_splits = gridDim.y;
+  const int len = si.pos + 1;
+  // split ranges are page aligned
+  int chunk = (len + n_splits - 1) / n_splits;
+  chunk = ((chunk + m.page_tokens - 1) / m.page_tokens) * m.page_tokens;
+  const int start = split * chunk;
+  const int end = min(len, start + chunk);
+
+  const int tid = threadIdx.x;
+  const int grp = tid / GS, j = tid % GS;
+
+  float qr[G][N];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int k = 0; k < N; ++k) qr[g][k] = q[(kvh * G + g) * HD + j * N + k] * m.qscale;
+
+  float mx[G], l[G], acc[G][N];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    mx[g] = kNegBig; l[g] = 0.f;
+#pragma unroll
+    for (int k = 0; k < N; ++k) acc[g][k] = 0.f;
+  }
+
+  constexpr int U = 4;   // positions in flight per group
+  for (int p0 = start + grp; p0 < end; p0 += U * GPB) {
+    uint4 ku[U], vu[U];
+    bool ok[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int p = p0 + u * GPB;
+      ok[u] = p < end;
+      const int pc = ok[u] ? p : p0;
+      const WT *kr = kv_row<WT>(c, layer, pc, kvh, 0) + j * N;
+      ku[u] = *(const uint4 *)kr;
+      vu[u] = *(const uint4 *)(kr + (size_t)m.page_tokens * HD);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float kf[N], vf[N];
+      Pack<WT>::unpack(ku[u], kf);
+      Pack<WT>::unpack(vu[u], vf);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float s = 0.f;
+#pragma unroll
+        for (int k = 0; k < N; ++k) s = fmaf(qr[g][k], kf[k], s);
+#pragma unroll
+        for (int o = GS / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, kWave);
+        if (ok[u]) {
+          const float mn = fmaxf(mx[g], s);
+          const float corr = __expf(mx[g] - mn);
+          const float pe = __expf(s - mn);
+          l[g] = l[g] * corr + pe;
+#pragma unroll
+          for (int k = 0; k < N; ++k) acc[g][k] = fmaf(pe, vf[k], acc[g][k] * corr);
+          mx[g] = mn;
+        }
+      }
+    }
+  }
+
+  // merge the position groups of this workgroup
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float *rec = merge + (grp * G + g) * REC;
+    if (j == 0) { rec[0] = mx[g]; rec[1] = l[g]; }
+#pragma unroll
+    for (int k = 0; k < N; ++k) rec[2 + j * N + k] = acc[g][k];
+  }
+  __syncthreads();
+  for (int o = tid; o < G * HD; o += kBlock) {
+    const int g = o / HD, dim = o % HD;
+    float M = kNegBig;
+    for (int r = 0; r < GPB; ++r) M = fmaxf(M, merge[(r * G + g) * REC]);
+    float L = 0.f, A = 0.f;
+    for (int r = 0; r < GPB; ++r) {
+      const float *rec = merge + (r * G + g) * REC;
+      const float w = __expf(rec[0] - M);
+      L = fmaf(rec[1], w, L);
+      A = fmaf(rec[2 + dim], w, A);
+    }
+    const int head = kvh * G + g;
+    if (n_splits == 1) {
+      aout[head * HD + dim] = A / L;
+    } else {
+      float *pr = partials + ((size_t)head * n_splits + split) * REC;
+      if (dim == 0) { pr[0] = M; pr[1] = L; }
+      pr[2 + dim] = A;
+    }
+  }
+  if (n_splits == 1) return;
+
+  // last workgroup of this KV head merges the splits
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    const int prev = atomicAdd(&counters[kvh], 1);
+    s_last = (prev == n_splits - 1);
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  for (int o = tid; o < G * HD; o += kBlock) {
+    const int g = o / HD, dim = o % HD;
+    const int head = kvh * G + g;
+    const float *pr = partials + (size_t)head * n_splits * REC;
+    float M = kNegBig;
+    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, __builtin_nontemporal_load(pr + s * REC));
+    float L = 0.f, A = 0.f;
+    for (int s = 0; s < n_splits; ++s) {
+      const float w = __expf(__builtin_nontemporal_load(pr + s * REC) - M);
+      L = fmaf(__builtin_nontemporal_load(pr + s * REC + 1), w, L);
+      A = fmaf(__builtin_nontemporal_load(pr + s * REC + 2 + dim), w, A);
+    }
+    aout[head * HD + dim] = A / L;
+  }
+  if (tid == 0) counters[kvh] = 0;   // ready for the next launch (stream order separates launches)
+}
+
+// ------------------------------------------------------------------------------------------
+// a5 / a7: out[r] = resid[r] + W[r,:] . vin   (o_proj and down_proj with the residual add fused).
+// grid = ceil(rows / (R * 4)); dynamic LDS = C floats.
+template <typename WT, int R>
+__global__ __launch_bounds__(kBlock) void k_proj_resid(Common c, int role, const float *vin, int C,
+                                                       const WT *W, int rows, int resid_sel, int out_sel) {
+  extern __shared__ float xs[];
+  const StageIn si = stage_in(c, role);
+  if (!si.active) return;
+  for (int i = threadIdx.x; i < C; i += kBlock) xs[i] = vin[i];
+  __syncthreads();
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r0 = (blockIdx.x * kWavesPerBlock + wave) * R;
+  if (r0 >= rows) return;
+  const WT *rp[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) rp[r] = W + (size_t)min(r0 + r, rows - 1) * C;
+  float acc[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) acc[r] = 0.f;
+  stream_dot<WT, R>(rp, xs, C, acc);
+#pragma unroll
+  for (int r = 0; r < R; ++r) acc[r] = wave_sum(acc[r]);
+  if (lane < R && r0 + lane < rows) {
+    float y = 0.f;
+#pragma unroll
+    for (int r = 0; r < R; ++r) if (lane == r) y = acc[r];
+    const float *resid = xslot(c, resid_sel);
+    float *out = xslot(c, out_sel);
+    out[r0 + lane] = resid[r0 + lane] + y;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// a2 + a6: RMSNorm + gate/up GEMV + SwiGLU: mout[i] = silu(Wg[i,:].xn) * (Wu[i,:].xn).
+// One wave computes PAIRS (gate_i, up_i) row pairs.  grid = ceil(f / (PAIRS * 4)).
+template <typename WT, int PAIRS>
+__global__ __launch_bounds__(kBlock) void k_gate_up(Common c, int role, int xin_sel, const float *gain,
+                                                    const WT *wgu, float *mout) {
+  extern __shared__ float xs[];
+  __shared__ float red[kWavesPerBlock];
+  const StageIn si = stage_in(c, role);
+  if (!si.active) return;
+  const Dims &m = c.dm;
+  const int d = m.d, f = m.f;
+  load_and_norm<WT>(xslot(c, xin_sel), nullptr, gain, d, m.eps, xs, red, nullptr);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int i0 = (blockIdx.x * kWavesPerBlock + wave) * PAIRS;
+  if (i0 >= f) return;
+  const WT *rows[2 * PAIRS];
+#pragma unroll
+  for (int p = 0; p < PAIRS; ++p) {
+    const int i = min(i0 + p, f - 1);
+    rows[2 * p] = wgu + (size_t)i * d;
+    rows[2 * p + 1] = wgu + (size_t)(f + i) * d;
+  }
+  float acc[2 * PAIRS];
+#pragma unroll
+  for (int r = 0; r < 2 * PAIRS; ++r) acc[r] = 0.f;
+  stream_dot<WT, 2 * PAIRS>(rows, xs, d, acc);
+#pragma unroll
+  for (int r = 0; r < 2 * PAIRS; ++r) acc[r] = wave_sum(acc[r]);
+  if (lane < PAIRS && i0 + lane < f) {
+    float g = 0.f, u = 0.f;
+#pragma unroll
+    for (int p = 0; p < PAIRS; ++p) if (lane == p) { g = acc[2 * p]; u = acc[2 * p + 1]; }
+    mout[i0 + lane] = g / (1.0f + __expf(-g)) * u;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// a8 / a9: head = RMSNorm + vocab projection + argmax (exit head and LM head share this kernel).
+// Each workgroup reduces its rows to one (value, index) candidate; the commit kernel finishes the
+// reduction.  logits_row != nullptr additionally stores the logits (parity harness).
+// grid = ceil(V / (R * 4)) = dm.head_blocks.
+template <typename WT, int R>
+__global__ __launch_bounds__(kBlock) void k_head(Common c, int role, int xin_sel, const float *gain,
+                                                 const WT *W, float2 *cand, float *logits_log, int is_lm) {
+  extern __shared__ float xs[];
+  __shared__ float red[kWavesPerBlock];
+  __shared__ float bv[kWavesPerBlock];
+  __shared__ int bi[kWavesPerBlock];
+  const StageIn si = stage_in(c, role);
+  if (!si.active) return;
+  const Dims &m = c.dm;
+  const int d = m.d, V = m.V;
+  load_and_norm<WT>(xslot(c, xin_sel), nullptr, gain, d, m.eps, xs, red, nullptr);
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r0 = (blockIdx.x * kWavesPerBlock + wave) * R;
+  float best = -INFINITY;
+  int besti = 0x7fffffff;
+  if (r0 < V) {
+    const WT *rp[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) rp[r] = W + (size_t)min(r0 + r, V - 1) * d;
+    float acc[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) acc[r] = 0.f;
+    stream_dot<WT, R>(rp, xs, d, acc);
+#pragma unroll
+    for (int r = 0; r < R; ++r) acc[r] = wave_sum(acc[r]);
+    // logits row for the parity harness: row index = number of tokens committed so far
+    float *lrow = nullptr;
+    if (logits_log && is_lm) {
+      const int row = (role == kPrefill) ? 0 : c.st->gen_count;
+      if (row < m.debug_rows) lrow = logits_log + (size_t)row * V;
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      if (r0 + r < V) {
+        if (better(acc[r], r0 + r, best, besti)) { best = acc[r]; besti = r0 + r; }
+        if (lrow && lane == 0) lrow[r0 + r] = acc[r];
+      }
+    }
+  }
+  if (lane == 0) { bv[wave] = best; bi[wave] = besti; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < kWavesPerBlock; ++w)
+      if (better(bv[w], bi[w], best, besti)) { best = bv[w]; besti = bi[w]; }
+    cand[blockIdx.x] = make_float2(best, __int_as_float(besti));
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// a10: finish both argmax reductions, compare draft with the verifier's token, commit, roll back.
+// One workgroup.  kind: 0 vanilla step, 1 PPSD step, 2 prefill position (no head), 3 last prefill
+// position (LM head ran).
+__device__ __forceinline__ int reduce_candidates(const float2 *cand, int n, float *sv, int *si_) {
+  float best = -INFINITY;
+  int besti = 0x7fffffff;
+  for (int k = threadIdx.x; k < n; k += kBlock) {
+    const float2 cnd = cand[k];
+    const int idx = __float_as_int(cnd.y);
+    if (better(cnd.x, idx, best, besti)) { best = cnd.x; besti = idx; }
+  }
+  wave_argmax(best, besti);
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = best; si_[threadIdx.x >> 6] = besti; }
+  __syncthreads();
+  best = sv[0]; besti = si_[0];
+#pragma unroll
+  for (int w = 1; w < kWavesPerBlock; ++w)
+    if (better(sv[w], si_[w], best, besti)) { best = sv[w]; besti = si_[w]; }
+  return besti;
+}
+
+__global__ __launch_bounds__(kBlock) void k_commit(Common c, int kind, const float2 *cand_lm,
+                                                   const float2 *cand_exit, int32_t *out_tokens,
+                                                   int32_t *drafts_log) {
+  __shared__ float sv[kWavesPerBlock];
+  __shared__ int si_[kWavesPerBlock];
+  DevState *st = c.st;
+  const int nb = c.dm.head_blocks;
+  if (kind == 2 || kind == 3) {   // prefill
+    if (!(st->prefill_pos < st->prefill_len)) return;
+    int tok = -1;
+    if (kind == 3) tok = reduce_candidates(cand_lm, nb, sv, si_);
+    if (threadIdx.x == 0) {
+      st->prefill_pos += 1;
+      if (kind == 3) {
+        st->t = st->prefill_len;
+        st->last_token = tok;
+        st->full = 0;
+        st->gen_count = 1;
+        drafts_log[0] = -1;
+      }
+    }
+    return;
+  }
+  if (!(st->n_out < st->target)) return;
+  const int full = st->full;
+  if (kind == 0) {   // vanilla: the LM head's token is the next token
+    const int v = reduce_candidates(cand_lm, nb, sv, si_);
+    if (threadIdx.x == 0) {
+      out_tokens[st->n_out] = v;
+      drafts_log[st->gen_count] = -1;
+      st->n_out += 1; st->gen_count += 1; st->t += 1; st->last_token = v;
+      st->stats[0] += 1;
+    }
+    return;
+  }
+  // PPSD step
+  const int d_next = reduce_candidates(cand_exit, nb, sv, si_);   // draft stage always ran
+  int v = -1;
+  if (full) v = reduce_candidates(cand_lm, nb, sv, si_);
+  if (threadIdx.x == 0) {
+    if (!full) {                 // pipeline refill: nothing to commit yet
+      st->draft = d_next;
+      st->full = 1;
+      st->cur ^= 1;              // the draft stage wrote hExit[cur ^ 1]
+      st->stats[5] += 1;
+    } else {
+      const int d = st->draft;
+      out_tokens[st->n_out] = v;
+      drafts_log[st->gen_count] = d;
+      st->n_out += 1; st->gen_count += 1;
+      st->stats[0] += 1; st->stats[1] += 1; st->stats[4] += 1;
+      if (v == d) {              // accept: h_{t+1}^E and d_{t+2} from this step stay valid
+        st->stats[2] += 1;
+        st->draft = d_next;
+        st->cur ^= 1;
+      } else {                   // reject: drop the draft's KV row (layers 1..E) by not advancing
+        st->stats[3] += 1;       // past it; the refill step rewrites position t+1
+        st->stats[6] += 1;
+        st->full = 0;
+      }
+      st->t += 1;
+      st->last_token = v;
+    }
+  }
+}
+
+// Host-requested state edits (tiny, one thread): new prefill / new decode target.
+__global__ void k_begin_prefill(DevState *st, int n_prompt) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    st->t = -1; st->last_token = -1; st->full = 0; st->draft = -1; st->cur = 0;
+    st->n_out = 0; st->target = 0; st->gen_count = 0;
+    st->prefill_pos = 0; st->prefill_len = n_prompt;
+    for (int k = 0; k < 8; ++k) st->stats[k] = 0;
+  }
+}
+
+__global__ void k_begin_decode(DevState *st, int n_tokens) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) { st->n_out = 0; st->target = n_tokens; }
+}
+
+// Streaming-read probe: each thread sums 16-byte loads over a grid-stride range.
+__global__ __launch_bounds__(kBlock) void k_read_probe(const uint4 *buf, size_t n_vec, uint32_t *sink) {
+  uint32_t acc = 0;
+  const size_t stride = (size_t)gridDim.x * kBlock;
+  size_t i = (size_t)blockIdx.x * kBlock + threadIdx.x;
+  for (; i + 3 * stride < n_vec; i += 4 * stride) {
+    uint4 a = ld16_stream(buf + i);
+    uint4 b = ld16_stream(buf + i + stride);
+    uint4 cc = ld16_stream(buf + i + 2 * stride);
+    uint4 dd = ld16_stream(buf + i + 3 * stride);
+    acc += a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ cc.x ^ cc.y ^ cc.z ^ cc.w ^ dd.x ^ dd.y ^ dd.z ^ dd.w;
+  }
+  for (; i < n_vec; i += stride) { uint4 a = ld16_stream(buf + i); acc += a.x ^ a.y ^ a.z ^ a.w; }
+  if (acc == 0x9e3779b9u) sink[0] = acc;   // practically never; keeps the loads alive
+}
+
+}  // namespace ppsd

@@ -1,0 +1,43 @@
+"""The C-ABI library loads without a GPU and exports every symbol include/ppsd.h declares."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    src = open(os.path.join(ROOT, "include", "ppsd.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(ppsd_[a-z_]+)\s*\(", src)))
+
+
+def test_header_declares_the_four_boundary_calls():
+    names = _declared_functions()
+    for n in ("ppsd_load_weights", "ppsd_prefill", "ppsd_decode", "ppsd_stats"):
+        assert n in names
+
+
+def test_library_exports_every_declared_symbol():
+    from paper_2509_19368_amd.build import LIB_PATH, build_library, is_stale
+    if is_stale():
+        build_library()
+    lib = ctypes.CDLL(LIB_PATH)
+    for n in _declared_functions():
+        assert hasattr(lib, n), n
+
+
+def test_config_validation_runs_on_the_host():
+    import paper_2509_19368_amd as P
+    import synth_inputs as S
+    from paper_2509_19368_amd.binding import make_config
+    cfg = make_config(S.WORKLOADS["C2"], 400, P.MODE_OVERLAP)
+    n = P.ppsd_workspace_bytes(cfg)
+    kv = 32 * 25 * 32 * 2 * 16 * 128 * 2          # layers * pages * kv heads * (K,V) * slots * hd * bytes
+    assert kv < n < kv + (8 << 20)
+    cfg.exit_layer = 32
+    try:
+        P.ppsd_workspace_bytes(cfg)
+        assert False
+    except P.PpsdError as e:
+        assert "exit_layer" in str(e)

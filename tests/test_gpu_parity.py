@@ -1,0 +1,198 @@
+"""GPU parity: the HIP library through its C ABI against the CPU oracle, element by element."""
+import pytest
+import torch
+
+import synth_inputs as S
+from oracle import decoder_fp64 as O
+from tests.parity_util import (REL_TOL_BF16, REL_TOL_FP32, check_against_teacher_forced_oracle, oracle_run,
+                               to_device)
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def P():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (torch.cuda.is_available() is False)")
+    import paper_2509_19368_amd as pkg
+    pkg.load_library()
+    return pkg
+
+
+def _gpu_run(P, w, W_gpu, prompt, n, mode, **kw):
+    ss = P.Session(w, W_gpu, max_seq=kw.pop("max_seq", len(prompt) + n + 2), mode=mode, debug_logits=n + 1, **kw)
+    t0 = ss.ppsd_prefill(prompt)
+    toks = [t0] + ss.ppsd_decode(n)
+    out = dict(tokens=toks, logits=ss.read_logits(0, n + 1), drafts=ss.read_drafts(0, n + 1), stats=ss.ppsd_stats())
+    ss.close()
+    return out
+
+
+SMALL = [
+    # ragged everything: vocab not a multiple of the head kernel's rows, d_ffn with a column tail
+    S.Workload("r32", n_layers=3, exit_layer=1, d_model=192, n_heads=4, n_kv_heads=2, head_dim=64, d_ffn=328,
+               vocab=1003, dtype="fp32", damp=0.2, seed=11, prompt_len=9, decode_len=40),
+    S.Workload("r16", n_layers=4, exit_layer=2, d_model=256, n_heads=4, n_kv_heads=1, head_dim=128, d_ffn=712,
+               vocab=777, dtype="bf16", damp=0.2, seed=12, prompt_len=21, decode_len=40),
+    S.Workload("m16", n_layers=3, exit_layer=2, d_model=128, n_heads=2, n_kv_heads=2, head_dim=64, d_ffn=264,
+               vocab=515, dtype="bf16", damp=0.3, seed=13, prompt_len=5, decode_len=30),
+    S.Workload("m32", n_layers=2, exit_layer=1, d_model=256, n_heads=2, n_kv_heads=2, head_dim=128, d_ffn=512,
+               vocab=640, dtype="fp32", damp=0.3, seed=14, prompt_len=1, decode_len=30),
+]
+
+
+def test_c1_all_modes_reproduce_the_oracle_stream(P):
+    w = S.WORKLOADS["C1"]
+    W = S.make_weights(w)
+    prompt = S.make_prompt(w)
+    dec, tr, sim = oracle_run(w, W, prompt, w.decode_len)
+    Wg = to_device(W, "cuda")
+    runs = {m: _gpu_run(P, w, Wg, prompt, w.decode_len, m) for m in (P.MODE_VANILLA, P.MODE_SERIAL, P.MODE_OVERLAP)}
+    for m, r in runs.items():
+        assert r["tokens"] == tr.tokens, f"mode {m}"
+        ref = torch.stack(tr.logits)
+        err = ((r["logits"].double() - ref).abs().max(dim=1).values / ref.abs().max(dim=1).values).max().item()
+        assert err <= REL_TOL_FP32, f"mode {m}: logits off by {err:.2e}"
+    # the three schedules run the same kernels in the same order per token: bitwise equal logits
+    assert torch.equal(runs[P.MODE_VANILLA]["logits"], runs[P.MODE_SERIAL]["logits"])
+    assert torch.equal(runs[P.MODE_SERIAL]["logits"], runs[P.MODE_OVERLAP]["logits"])
+    for m in (P.MODE_SERIAL, P.MODE_OVERLAP):
+        st = runs[m]["stats"]
+        assert (st["committed"], st["accepted"], st["rejected"], st["steps_overlapped"], st["steps_draft_only"],
+                st["kv_rollbacks"], st["drafts_compared"]) == \
+               (sim.committed, sim.accepted, sim.rejected, sim.steps_overlapped, sim.steps_draft_only,
+                sim.kv_rollbacks, sim.drafts_compared)
+    v = runs[P.MODE_VANILLA]["stats"]
+    assert v["committed"] == w.decode_len and v["drafts_compared"] == 0
+    assert all(d == -1 for d in runs[P.MODE_VANILLA]["drafts"])
+
+
+def test_drafts_equal_the_exit_heads_greedy_token(P):
+    """Every compared draft is the exit head's argmax on the true prefix (oracle, fp64)."""
+    w = S.WORKLOADS["C1"]
+    W = S.make_weights(w)
+    prompt = S.make_prompt(w)
+    dec = O.Decoder(w, W)
+    r = _gpu_run(P, w, to_device(W, "cuda"), prompt, w.decode_len, P.MODE_OVERLAP)
+    seq = list(prompt) + r["tokens"]
+    ex = dec.exit_logits_full(seq[:-1])
+    assert r["drafts"][0] == -1
+    for k in range(1, len(r["tokens"])):
+        assert r["drafts"][k] == O.argmax_lowest(ex[len(prompt) + k - 1])
+    acc = sum(1 for k in range(1, len(r["tokens"])) if r["drafts"][k] == r["tokens"][k])
+    assert acc == r["stats"]["accepted"]
+
+
+@pytest.mark.parametrize("w", SMALL, ids=[w.name for w in SMALL])
+def test_small_ragged_shapes(P, w):
+    W = S.make_weights(w)
+    prompt = S.make_prompt(w)
+    dec = O.Decoder(w, W)
+    Wg = to_device(W, "cuda")
+    tol = REL_TOL_FP32 if w.dtype == "fp32" else REL_TOL_BF16
+    ref_logits = None
+    for mode in (P.MODE_VANILLA, P.MODE_SERIAL, P.MODE_OVERLAP):
+        r = _gpu_run(P, w, Wg, prompt, w.decode_len, mode)
+        worst, loose = check_against_teacher_forced_oracle(dec, prompt, r["tokens"], r["logits"], tol)
+        if w.dtype == "fp32":
+            assert r["tokens"] == O.greedy_decode(dec, prompt, w.decode_len + 1).tokens
+        if ref_logits is None:
+            ref_logits, ref_tokens = r["logits"], r["tokens"]
+        else:
+            assert r["tokens"] == ref_tokens and torch.equal(r["logits"], ref_logits)
+        if mode != P.MODE_VANILLA:
+            st = r["stats"]
+            assert st["accepted"] + st["rejected"] == w.decode_len == st["committed"]
+            assert st["steps_draft_only"] in (st["rejected"], st["rejected"] + 1)
+
+
+def test_alpha_one_and_alpha_zero_accounting(P):
+    w = S.WORKLOADS["C1"].replace(damp=0.0)
+    W = S.make_weights(w)
+    prompt = S.make_prompt(w)
+    r = _gpu_run(P, w, to_device(W, "cuda"), prompt, 32, P.MODE_OVERLAP)
+    st = r["stats"]
+    assert st["rejected"] == 0 and st["accepted"] == 32 and st["steps_draft_only"] == 1 and st["steps_overlapped"] == 32
+    W["exit_head"] = -W["lm_head"]
+    r = _gpu_run(P, w, to_device(W, "cuda"), prompt, 32, P.MODE_OVERLAP)
+    st = r["stats"]
+    assert st["accepted"] == 0 and st["rejected"] == 32 == st["kv_rollbacks"] and st["steps_draft_only"] == 32
+    assert r["tokens"] == O.greedy_decode(O.Decoder(w, W), prompt, 33).tokens
+
+
+def test_long_context_splits_and_shuffled_pages(P):
+    """Context of several hundred positions: several attention splits, pages in shuffled order."""
+    w = S.Workload("ctx", n_layers=2, exit_layer=1, d_model=128, n_heads=4, n_kv_heads=1, head_dim=64, d_ffn=256,
+                   vocab=300, dtype="fp32", damp=0.3, seed=21, prompt_len=333, decode_len=24)
+    W = S.make_weights(w)
+    prompt = S.make_prompt(w)
+    dec = O.Decoder(w, W)
+    want = O.greedy_decode(dec, prompt, w.decode_len + 1, keep_logits=True)
+    Wg = to_device(W, "cuda")
+    max_seq = 333 + 24 + 2
+    a = _gpu_run(P, w, Wg, prompt, w.decode_len, P.MODE_OVERLAP, max_seq=max_seq, kv_page_tokens=8)
+    n_pages = (max_seq + 7) // 8
+    b = _gpu_run(P, w, Wg, prompt, w.decode_len, P.MODE_OVERLAP, max_seq=max_seq, kv_page_tokens=8,
+                 page_table=S.page_permutation(5, n_pages))
+    c = _gpu_run(P, w, Wg, prompt, w.decode_len, P.MODE_VANILLA, max_seq=1024, kv_page_tokens=64)
+    assert a["tokens"] == want.tokens == b["tokens"] == c["tokens"]
+    assert torch.equal(a["logits"], b["logits"])
+    ref = torch.stack(want.logits)
+    for r in (a, c):
+        err = ((r["logits"].double() - ref).abs().max(dim=1).values / ref.abs().max(dim=1).values).max().item()
+        assert err <= REL_TOL_FP32
+
+
+def test_graph_replay_equals_direct_launch_and_decode_is_resumable(P):
+    w = S.WORKLOADS["C1"]
+    W = to_device(S.make_weights(w), "cuda")
+    prompt = S.make_prompt(w)
+    a = _gpu_run(P, w, W, prompt, 48, P.MODE_OVERLAP, use_graph=True)
+    b = _gpu_run(P, w, W, prompt, 48, P.MODE_OVERLAP, use_graph=False)
+    assert a["tokens"] == b["tokens"] and torch.equal(a["logits"], b["logits"]) and a["stats"]["accepted"] == b["stats"]["accepted"]
+    ss = P.Session(w, W, max_seq=16 + 48 + 2, mode=P.MODE_OVERLAP)
+    t0 = ss.ppsd_prefill(prompt)
+    toks = [t0] + ss.ppsd_decode(1) + ss.ppsd_decode(30) + ss.ppsd_decode(17)
+    assert toks == a["tokens"]
+    st = ss.ppsd_stats()
+    assert st["accepted"] == a["stats"]["accepted"] and st["steps_draft_only"] == a["stats"]["steps_draft_only"]
+    # a second prefill on the same context starts a fresh sequence
+    assert ss.ppsd_prefill(prompt) == t0 and ss.ppsd_decode(5) == a["tokens"][1:6]
+    ss.close()
+
+
+def test_error_paths_leave_the_context_usable(P):
+    w = S.WORKLOADS["C1"]
+    W = to_device(S.make_weights(w), "cuda")
+    prompt = S.make_prompt(w)
+    ss = P.Session(w, W, max_seq=16 + 8 + 2, mode=P.MODE_SERIAL)
+    with pytest.raises(P.PpsdError) as e:
+        ss.ppsd_decode(4)
+    assert e.value.code == -2
+    with pytest.raises(P.PpsdError) as e:
+        ss.ppsd_prefill(list(range(40)))
+    assert e.value.code == -3
+    with pytest.raises(P.PpsdError) as e:
+        ss.ppsd_prefill([5, w.vocab])
+    assert e.value.code == -1
+    t0 = ss.ppsd_prefill(prompt)
+    with pytest.raises(P.PpsdError) as e:
+        ss.ppsd_decode(9)
+    assert e.value.code == -3
+    got = ss.ppsd_decode(8)
+    assert [t0] + got == O.greedy_decode(O.Decoder(w, S.make_weights(w)), prompt, 9).tokens
+    ss.close()
+    bad = w.replace(head_dim=48)
+    with pytest.raises(P.PpsdError):
+        P.Session(bad, W, max_seq=32)
+
+
+def test_generator_is_bit_identical_on_cpu_and_gpu(P):
+    w = S.WORKLOADS["C1"]
+    a, b = S.make_weights(w), S.make_weights(w, device="cuda")
+    for k, v in a.items():
+        for x, y in zip(v if isinstance(v, list) else [v], b[k] if isinstance(v, list) else [b[k]]):
+            assert torch.equal(x, y.cpu()), k
+    x = S.bell_tensor(2509, 16, 3_000_000, 0.02, "cpu", torch.bfloat16)
+    y = S.bell_tensor(2509, 16, 3_000_000, 0.02, "cuda", torch.bfloat16)
+    assert torch.equal(x, y.cpu())
