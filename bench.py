@@ -1,0 +1,206 @@
+#!/usr/bin/env python3
+"""Benchmark of the PPSD decode hot path on one MI355X.
+
+One "step" = one generation: prefill of the workload's prompt (untimed; the paper's speed metric
+is decode-phase tokens/s) followed by the timed ppsd_decode of the workload's decode length.
+Prints ONE JSON line.  value = committed tokens/s of PPSD (overlapped draft/verify stages);
+the same line carries vanilla GPU decode, the acceptance rate, the HBM-roofline fraction of the
+dominant kernel (live HIP-event timing) and the CPU oracle timed on this host.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def algorithmic_bytes(w, mean_ctx: float):
+    """Weights once + KV once per committed token (vanilla), plus PPSD's own extras."""
+    layer = w.layer_weight_bytes()
+    head = w.head_weight_bytes()
+    kv = w.kv_bytes_per_position() * mean_ctx
+    kv_draft = w.kv_bytes_per_position(w.exit_layer) * mean_ctx
+    embed_row = w.d_model * w.elem_bytes
+    vanilla = w.n_layers * layer + head + kv + embed_row
+    accept_step = vanilla + head                                   # + exit head
+    reject_extra = w.exit_layer * layer + head + kv_draft + embed_row   # the wasted draft pass
+    return dict(vanilla=vanilla, accept_step=accept_step, reject_extra=reject_extra, layer=layer, head=head)
+
+
+def kernel_bytes(w, mean_ctx: float):
+    """Algorithmic bytes per launch of each kernel kind (weights + vectors in/out)."""
+    B, d, f = w.elem_bytes, w.d_model, w.d_ffn
+    nq = w.n_heads * w.head_dim
+    return {
+        "qkv": w.qkv_rows * d * B + 4 * d + 4 * nq + 2 * w.n_kv_heads * w.head_dim * B,
+        "attention": 2 * w.n_kv_heads * w.head_dim * B * mean_ctx + 8 * nq,
+        "o_proj": d * nq * B + 4 * nq + 8 * d,
+        "gate_up": 2 * f * d * B + 4 * d + 4 * f,
+        "down": d * f * B + 4 * f + 8 * d,
+        "head": w.vocab * d * B + 4 * d,
+    }
+
+
+def run_generations(ss, prompt, n_decode, steps, warmup, torch):
+    times = []
+    stats = None
+    toks = None
+    for it in range(warmup + steps):
+        first = ss.ppsd_prefill(prompt)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        out = ss.ppsd_decode(n_decode)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        if it >= warmup:
+            times.append(dt)
+        stats = ss.ppsd_stats()
+        toks = [first] + out
+    return times, stats, toks
+
+
+def cpu_oracle_baseline(w, W_gpu, prompt, torch, budget_s=25.0):
+    """The CPU oracle as it stands, on a bounded sample of the same workload."""
+    from oracle import decoder_fp64 as O
+    W = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in W_gpu.items()}
+    dec = O.Decoder(w, W)
+    t0 = time.perf_counter()
+    O.greedy_decode(dec, prompt[:2], 1)                      # 2 positions: sizes the sample
+    per_pos = (time.perf_counter() - t0) / 2
+    n_pos = int(max(2, min(24, budget_s / max(per_pos, 1e-6))))
+    t0 = time.perf_counter()
+    O.greedy_decode(dec, prompt[:n_pos], 1)                  # n_pos positions through the full model
+    dt = time.perf_counter() - t0
+    return dict(value=n_pos / dt, unit="tokens/s", cores=torch.get_num_threads(), kind="oracle",
+                sample=f"fp64 oracle (KV-cache greedy decode), full {w.name} model, the first {n_pos} positions "
+                       f"of the workload's prompt, one position at a time; tokens/s = positions / wall time "
+                       f"({dt:.1f} s)")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--workload", default="C2")
+    ap.add_argument("--damp", type=float, default=None, help="override the workload's damp")
+    ap.add_argument("--exit-layer", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-timing", action="store_true")
+    ap.add_argument("--modes", default="vanilla,serial,overlap")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the two pipeline stages share one MI355X); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth_inputs as S
+    import paper_2509_19368_amd as P
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    P.load_library()
+
+    w = S.WORKLOADS[args.workload]
+    if args.damp is not None:
+        w = w.replace(damp=args.damp)
+    if args.exit_layer is not None:
+        w = w.replace(exit_layer=args.exit_layer)
+    t0 = time.perf_counter()
+    W = S.make_weights(w, device="cuda")
+    torch.cuda.synchronize()
+    gen_s = time.perf_counter() - t0
+    prompt = S.make_prompt(w)
+    n = w.decode_len
+    max_seq = w.prompt_len + n + 2
+    mean_ctx = w.prompt_len + 1 + n / 2.0
+    ab = algorithmic_bytes(w, mean_ctx)
+
+    res = {}
+    streams = {}
+    for name, mode in (("vanilla", P.MODE_VANILLA), ("serial", P.MODE_SERIAL), ("overlap", P.MODE_OVERLAP)):
+        if name not in args.modes.split(","):
+            continue
+        ss = P.Session(w, W, max_seq=max_seq, mode=mode)
+        times, st, toks = run_generations(ss, prompt, n, args.steps, args.warmup, torch)
+        ss.close()
+        total = sum(times)
+        res[name] = dict(tokens_per_s=args.steps * n / total, ms_per_generation=1e3 * total / args.steps,
+                         ms_per_token=1e3 * total / (args.steps * n), stats=st)
+        streams[name] = toks
+    if len(streams) > 1:
+        first = next(iter(streams.values()))
+        if any(s != first for s in streams.values()):
+            print("bench.py: modes disagree on the token stream", file=sys.stderr)
+            sys.exit(1)
+
+    main_mode = "overlap" if "overlap" in res else next(iter(res))
+    r = res[main_mode]
+    st = r["stats"]
+    alpha = st["accepted"] / st["drafts_compared"] if st["drafts_compared"] else None
+
+    # live per-kernel timing (HIP events around every launch, serial single-stream pass)
+    roofline = None
+    ktimes = None
+    if not args.no_kernel_timing:
+        ss = P.Session(w, W, max_seq=max_seq, mode=P.MODE_VANILLA, use_graph=False, time_kernels=True)
+        ss.ppsd_prefill(prompt)
+        ss.ppsd_decode(min(n, 32))
+        kt = ss.kernel_times()
+        ss.close()
+        ctx_t = w.prompt_len + 1 + min(n, 32) / 2.0
+        kb = kernel_bytes(w, ctx_t)
+        ktimes = {}
+        for k, v in kt.items():
+            if v["launches"] and k in kb:
+                us = v["total_us"] / v["launches"]
+                ktimes[k] = dict(avg_us=us, launches=v["launches"], bytes=kb[k], gbps=kb[k] / us / 1e3)
+        dom = max((k for k in ktimes), key=lambda k: ktimes[k]["avg_us"] * ktimes[k]["launches"])
+        roofline = dict(bound="hbm", kernel=dom, achieved=ktimes[dom]["gbps"], peak=HBM_PEAK_GBPS, unit="GB/s",
+                        frac=ktimes[dom]["gbps"] / HBM_PEAK_GBPS, traffic=None,
+                        avg_launch_us=ktimes[dom]["avg_us"], bytes_per_launch=ktimes[dom]["bytes"])
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_oracle_baseline(w, W, prompt, torch)
+
+    out = {
+        "metric": "committed tokens/sec at batch 1 (PPSD decode, draft and verify stages overlapped on one GPU)",
+        "value": r["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": r["ms_per_generation"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.n_layers}-layer d={w.d_model} decoder ({w.dtype}), exit layer "
+                               f"{w.exit_layer}, prompt {w.prompt_len}, decode {n} tokens, batch 1, damp {w.damp}, "
+                               f"exit head {w.exit_head}",
+                   "mode": main_mode, "tokens_per_step": n},
+        "acceptance_rate": alpha,
+        "ms_per_token": r["ms_per_token"],
+        "modes": {k: {"tokens_per_s": v["tokens_per_s"], "ms_per_token": v["ms_per_token"],
+                      "steps_draft_only": v["stats"]["steps_draft_only"], "accepted": v["stats"]["accepted"],
+                      "rejected": v["stats"]["rejected"], "device_ms": v["stats"]["device_ms"]}
+                  for k, v in res.items()},
+        "speedup_vs_vanilla_gpu": (r["tokens_per_s"] / res["vanilla"]["tokens_per_s"]) if "vanilla" in res else None,
+        "bytes_per_token": {"vanilla": ab["vanilla"], "ppsd_accept_step": ab["accept_step"],
+                            "ppsd_extra_per_reject": ab["reject_extra"]},
+        "hbm_frac_per_committed_token": r["tokens_per_s"] * ab["vanilla"] / (HBM_PEAK_GBPS * 1e9),
+        "hbm_frac_vanilla": (res["vanilla"]["tokens_per_s"] * ab["vanilla"] / (HBM_PEAK_GBPS * 1e9))
+        if "vanilla" in res else None,
+        "hbm_frac_per_moved_byte": (r["tokens_per_s"] * (ab["accept_step"] + (1 - alpha) * ab["reject_extra"])
+                                    / (HBM_PEAK_GBPS * 1e9)) if alpha is not None else None,
+        "roofline": roofline, "kernels": ktimes, "cpu_baseline": cpu,
+        "weight_generation_s": gen_s,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
