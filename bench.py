@@ -96,6 +96,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--modes", default="vanilla,serial,overlap")
+    ap.add_argument("--engine", default="persistent", choices=["streams", "persistent"])
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the two pipeline stages share one MI355X); "
@@ -125,12 +126,13 @@ def main():
     mean_ctx = w.prompt_len + 1 + n / 2.0
     ab = algorithmic_bytes(w, mean_ctx)
 
+    engine = P.ENGINE_PERSISTENT if args.engine == "persistent" else P.ENGINE_STREAMS
     res = {}
     streams = {}
     for name, mode in (("vanilla", P.MODE_VANILLA), ("serial", P.MODE_SERIAL), ("overlap", P.MODE_OVERLAP)):
         if name not in args.modes.split(","):
             continue
-        ss = P.Session(w, W, max_seq=max_seq, mode=mode)
+        ss = P.Session(w, W, max_seq=max_seq, mode=mode, engine=engine)
         times, st, toks = run_generations(ss, prompt, n, args.steps, args.warmup, torch)
         ss.close()
         total = sum(times)
@@ -151,7 +153,16 @@ def main():
     # live per-kernel timing (HIP events around every launch, serial single-stream pass)
     roofline = None
     ktimes = None
-    if not args.no_kernel_timing:
+    if not args.no_kernel_timing and engine == P.ENGINE_PERSISTENT:
+        # the whole decode call is ONE kernel launch; its duration comes from the HIP event pair the
+        # library records on the launching stream around it (ppsd_stats.device_ms of the last call)
+        moved = n * ab["accept_step"] + st["rejected"] * ab["reject_extra"] if main_mode != "vanilla" else n * ab["vanilla"]
+        dur_ms = st["device_ms"]
+        gbps = moved / dur_ms / 1e6
+        roofline = dict(bound="hbm", kernel=f"k_mega ({main_mode} decode of {n} tokens in one launch)", achieved=gbps,
+                        peak=HBM_PEAK_GBPS, unit="GB/s", frac=gbps / HBM_PEAK_GBPS, traffic=None,
+                        avg_launch_us=dur_ms * 1e3, bytes_per_launch=moved)
+    elif not args.no_kernel_timing:
         ss = P.Session(w, W, max_seq=max_seq, mode=P.MODE_VANILLA, use_graph=False, time_kernels=True)
         ss.ppsd_prefill(prompt)
         ss.ppsd_decode(min(n, 32))
@@ -181,7 +192,7 @@ def main():
         "config": {"workload": f"{w.name}: {w.n_layers}-layer d={w.d_model} decoder ({w.dtype}), exit layer "
                                f"{w.exit_layer}, prompt {w.prompt_len}, decode {n} tokens, batch 1, damp {w.damp}, "
                                f"exit head {w.exit_head}",
-                   "mode": main_mode, "tokens_per_step": n},
+                   "mode": main_mode, "engine": args.engine, "tokens_per_step": n},
         "acceptance_rate": alpha,
         "ms_per_token": r["ms_per_token"],
         "modes": {k: {"tokens_per_s": v["tokens_per_s"], "ms_per_token": v["ms_per_token"],

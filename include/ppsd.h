@@ -51,6 +51,15 @@ extern "C" {
 #define PPSD_MODE_SERIAL     1  /* draft stage then verify stage on one stream */
 #define PPSD_MODE_OVERLAP    2  /* draft stage and verify stage on two streams (verify-while-draft) */
 
+/* Execution engines.  Both run every step of the path in this library's HIP kernels and give
+ * the same tokens; logits agree to fp32 rounding (the RMSNorm sums are grouped differently). */
+#define PPSD_ENGINE_STREAMS    0  /* one kernel per operation; the stages on the two caller streams,
+                                     one captured HIP graph per step if use_graph */
+#define PPSD_ENGINE_PERSISTENT 1  /* one cooperative persistent kernel per prefill/decode call: grid
+                                     barriers between operations, the two stages zipped phase by phase
+                                     (PPSD_MODE_OVERLAP) or back to back (PPSD_MODE_SERIAL), weight
+                                     loads software-pipelined across barriers.  Uses stream_draft only. */
+
 typedef struct ppsd_ctx ppsd_ctx;
 
 typedef struct {
@@ -73,7 +82,8 @@ typedef struct {
   int32_t use_graph;       /* 1: replay one captured HIP graph per step; 0: launch kernels directly */
   int32_t time_kernels;    /* 1: profiling mode -- direct launches on one stream with a HIP event
                               pair around every kernel, totals via ppsd_kernel_times (slow) */
-  int32_t reserved[7];     /* must be zero */
+  int32_t engine;          /* PPSD_ENGINE_*: how a step is executed on the GPU */
+  int32_t reserved[6];     /* must be zero */
 } ppsd_config;
 
 /* DEVICE pointers, BORROWED.  Per-layer entries are HOST arrays of n_layers DEVICE pointers. */
@@ -150,6 +160,14 @@ int ppsd_read_drafts(ppsd_ctx *ctx, int32_t first, int32_t count, int32_t *out);
 
 /* Profiling mode only (time_kernels = 1): accumulated per-kind kernel durations. */
 int ppsd_kernel_times(const ppsd_ctx *ctx, ppsd_kernel_times_t *out);
+
+/* Measurement support, persistent engine: ask the next ppsd_decode calls to record, for decode step
+ * `step` of each call (step < 0 switches it off), the timeline of workgroup `workgroup`: per phase
+ * four 100 MHz timestamps (barrier passed, inputs staged, own weight tasks done, arrived at the next
+ * barrier).  ppsd_trace_read copies 4 * n_phases values (HOST out); phases a step skipped hold stale
+ * values. */
+int ppsd_trace_request(ppsd_ctx *ctx, int32_t step, int32_t workgroup);
+int ppsd_trace_read(ppsd_ctx *ctx, int32_t n_phases, uint64_t *out);
 
 /* Measurement support: times `iters` launches of a pure streaming-read kernel over a DEVICE
  * buffer of `bytes` bytes on `stream` (hipStream_t) and writes the average ms per launch.

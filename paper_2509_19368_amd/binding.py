@@ -14,6 +14,7 @@ import torch
 from .build import LIB_PATH
 
 MODE_VANILLA, MODE_SERIAL, MODE_OVERLAP = 0, 1, 2
+ENGINE_STREAMS, ENGINE_PERSISTENT = 0, 1
 KERNEL_KINDS = ("qkv", "attention", "o_proj", "gate_up", "down", "head", "commit")
 
 
@@ -27,7 +28,8 @@ class ppsd_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "exit_layer", "d_model", "n_heads", "n_kv_heads", "head_dim",
                                           "d_ffn", "vocab", "dtype", "max_seq", "kv_page_tokens", "mode")] + \
                [("rope_base", C.c_float), ("rms_eps", C.c_float), ("debug_logits", C.c_int32),
-                ("use_graph", C.c_int32), ("time_kernels", C.c_int32), ("reserved", C.c_int32 * 7)]
+                ("use_graph", C.c_int32), ("time_kernels", C.c_int32), ("engine", C.c_int32),
+                ("reserved", C.c_int32 * 6)]
 
 
 class ppsd_buffers(C.Structure):
@@ -73,6 +75,8 @@ def load_library():
     lib.ppsd_read_logits.restype, lib.ppsd_read_logits.argtypes = i32, [vp, i32, i32, C.POINTER(C.c_float)]
     lib.ppsd_read_drafts.restype, lib.ppsd_read_drafts.argtypes = i32, [vp, i32, i32, C.POINTER(i32)]
     lib.ppsd_kernel_times.restype, lib.ppsd_kernel_times.argtypes = i32, [vp, C.POINTER(ppsd_kernel_times_t)]
+    lib.ppsd_trace_request.restype, lib.ppsd_trace_request.argtypes = i32, [vp, i32, i32]
+    lib.ppsd_trace_read.restype, lib.ppsd_trace_read.argtypes = i32, [vp, i32, C.POINTER(C.c_uint64)]
     lib.ppsd_hbm_read_probe.restype = i32
     lib.ppsd_hbm_read_probe.argtypes = [vp, C.c_size_t, vp, i32, C.POINTER(C.c_float)]
     lib.ppsd_free.restype, lib.ppsd_free.argtypes = None, [vp]
@@ -87,7 +91,7 @@ def _check(rc: int):
 
 
 def make_config(shape, max_seq: int, mode: int, kv_page_tokens: int = 16, debug_logits: int = 0,
-                use_graph: bool = True, time_kernels: bool = False) -> ppsd_config:
+                use_graph: bool = True, time_kernels: bool = False, engine: int = ENGINE_STREAMS) -> ppsd_config:
     cfg = ppsd_config()
     for n in ("n_layers", "exit_layer", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab"):
         setattr(cfg, n, int(getattr(shape, n)))
@@ -95,6 +99,7 @@ def make_config(shape, max_seq: int, mode: int, kv_page_tokens: int = 16, debug_
     cfg.max_seq, cfg.kv_page_tokens, cfg.mode = int(max_seq), int(kv_page_tokens), int(mode)
     cfg.rope_base, cfg.rms_eps = float(shape.rope_base), float(shape.rms_eps)
     cfg.debug_logits, cfg.use_graph, cfg.time_kernels = int(debug_logits), int(use_graph), int(time_kernels)
+    cfg.engine = int(engine)
     return cfg
 
 
@@ -123,11 +128,11 @@ class Session:
 
     def __init__(self, shape, weights: dict, max_seq: int, mode: int = MODE_OVERLAP, kv_page_tokens: int = 16,
                  debug_logits: int = 0, use_graph: bool = True, time_kernels: bool = False,
-                 page_table: Optional[Sequence[int]] = None):
+                 page_table: Optional[Sequence[int]] = None, engine: int = ENGINE_STREAMS):
         self.lib = load_library()
         self.shape = shape
         self.weights = weights
-        self.cfg = make_config(shape, max_seq, mode, kv_page_tokens, debug_logits, use_graph, time_kernels)
+        self.cfg = make_config(shape, max_seq, mode, kv_page_tokens, debug_logits, use_graph, time_kernels, engine)
         nbytes = ppsd_workspace_bytes(self.cfg)
         dev = weights["embed"].device
         if dev.type != "cuda":
@@ -193,6 +198,14 @@ class Session:
         kt = ppsd_kernel_times_t()
         _check(self.lib.ppsd_kernel_times(self._ctx, C.byref(kt)))
         return {k: {"total_us": kt.total_us[i], "launches": kt.launches[i]} for i, k in enumerate(KERNEL_KINDS)}
+
+    def trace_request(self, step: int, workgroup: int = 0):
+        _check(self.lib.ppsd_trace_request(self._ctx, step, workgroup))
+
+    def trace_read(self, n_phases: int) -> List[List[int]]:
+        out = (C.c_uint64 * (4 * n_phases))()
+        _check(self.lib.ppsd_trace_read(self._ctx, n_phases, out))
+        return [list(out[4 * p: 4 * p + 4]) for p in range(n_phases)]
 
     def close(self):
         if getattr(self, "_ctx", None) and self._ctx.value:

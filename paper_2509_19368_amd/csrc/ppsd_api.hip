@@ -12,7 +12,7 @@
 #include <vector>
 
 #include "../../include/ppsd.h"
-#include "ppsd_kernels.h"
+#include "ppsd_mega.h"
 
 using namespace ppsd;
 
@@ -44,12 +44,16 @@ constexpr int kQkvPairs = 2;
 constexpr int kGuPairs = 2;
 constexpr int kProjRows = 4;
 constexpr int kHeadRows = 4;
+constexpr int kConsumerMergeSplits = 8;   // up to this many attention splits are merged by o_proj's prologue
+constexpr int kMaxSplits = 32;         // attention splits along the sequence (both engines)
+constexpr int kMaxWorkgroups = 1024;   // persistent engine: one head candidate per workgroup
 
 enum Kind { kKQkv = 0, kKAttn, kKOproj, kKGateUp, kKDown, kKHead, kKCommit };
 
 struct Layout {
   size_t state, prompt, out_tokens, drafts, page_table, rope_cos, rope_sin, xbuf;
   size_t q[2], a[2], mbuf[2], partials[2], counters[2], cand_lm, cand_exit, sink, logits, kv;
+  size_t layer_ptrs, bar, abort_flag, trace;
   size_t total;
   int n_pages, n_splits, head_blocks;
 };
@@ -75,7 +79,9 @@ bool valid_config(const ppsd_config *c, const char **why) {
   REJECT(c->debug_logits < 0, "debug_logits < 0");
   REJECT((size_t)c->d_ffn * 4 > 64 * 1024 || (size_t)c->d_model * 4 > 64 * 1024 ||
          (size_t)c->n_heads * c->head_dim * 4 > 64 * 1024, "activation vector exceeds 64 KiB of LDS");
-  for (int k = 0; k < 7; ++k) REJECT(c->reserved[k] != 0, "reserved fields must be zero");
+  REJECT(c->engine != PPSD_ENGINE_STREAMS && c->engine != PPSD_ENGINE_PERSISTENT, "engine must be 0 or 1");
+  REJECT(c->engine == PPSD_ENGINE_PERSISTENT && c->time_kernels, "time_kernels needs the per-operation engine");
+  for (int k = 0; k < 6; ++k) REJECT(c->reserved[k] != 0, "reserved fields must be zero");
 #undef REJECT
   return true;
 }
@@ -84,8 +90,8 @@ Layout make_layout(const ppsd_config *c) {
   Layout L{};
   const size_t es = c->dtype == PPSD_FP32 ? 4 : 2;
   L.n_pages = (c->max_seq + c->kv_page_tokens - 1) / c->kv_page_tokens;
-  int ns = (c->max_seq + 63) / 64;
-  L.n_splits = ns < 1 ? 1 : (ns > 32 ? 32 : ns);
+  int ns = (c->max_seq + 127) / 128;
+  L.n_splits = ns < 1 ? 1 : (ns > kMaxSplits ? kMaxSplits : ns);
   L.head_blocks = (c->vocab + kHeadRows * kWavesPerBlock - 1) / (kHeadRows * kWavesPerBlock);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
@@ -102,11 +108,16 @@ Layout make_layout(const ppsd_config *c) {
     L.q[s] = take(4 * nq);
     L.a[s] = take(4 * nq);
     L.mbuf[s] = take(4ull * c->d_ffn);
-    L.partials[s] = take(4ull * c->n_heads * L.n_splits * (c->head_dim + 2));
+    L.partials[s] = take(4ull * c->n_heads * kMaxSplits * (c->head_dim + 2));
     L.counters[s] = take(4ull * c->n_kv_heads);
   }
-  L.cand_lm = take(8ull * L.head_blocks);
-  L.cand_exit = take(8ull * L.head_blocks);
+  const size_t n_cand = L.head_blocks > kMaxWorkgroups ? L.head_blocks : kMaxWorkgroups;
+  L.cand_lm = take(8ull * n_cand);
+  L.cand_exit = take(8ull * n_cand);
+  L.layer_ptrs = take(sizeof(LayerPtrs) * (size_t)c->n_layers);
+  L.bar = take(256);
+  L.abort_flag = take(256);
+  L.trace = take(8ull * kTraceSlots * kTracePhases);
   L.sink = take(256);
   L.logits = take(4ull * c->debug_logits * c->vocab);
   L.kv = take((size_t)c->n_layers * L.n_pages * c->n_kv_heads * 2 * c->kv_page_tokens * c->head_dim * es);
@@ -128,6 +139,12 @@ struct ppsd_ctx {
   hipGraphExec_t g_step = nullptr;      // decode step in cfg.mode
   hipGraphExec_t g_prefill = nullptr;   // one prompt position, no head
   DevState *h_state = nullptr;          // pinned
+  // persistent engine
+  int n_wg = 0;
+  int mega_splits = 1;
+  int xs_stride = 0;
+  size_t mega_lds = 0;
+  int trace_step = -1, trace_wg = 0;
   bool prefilled = false;
   int host_len = 0;                     // prompt length + tokens committed so far (token #0 included)
   int64_t steps_launched = 0;
@@ -197,8 +214,10 @@ void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int 
   int *cnt = at<int>(x, x->lay.counters[stage]);
   const int G = c.n_heads / c.n_kv_heads;
   L.before(kKAttn);
+  // few splits: the o_proj prologue merges them; many: the last attention workgroup of a head does
+  const int defer = x->lay.n_splits <= kConsumerMergeSplits ? 1 : 0;
 #define ATTN(HD, GG) hipLaunchKernelGGL((k_attn<WT, HD, GG>), agrid, dim3(kBlock), 0, L.s, cm, role, layer, \
-                                        (const float *)q, a, part, cnt)
+                                        (const float *)q, a, part, cnt, defer)
   if (c.head_dim == 64) { if (G == 1) ATTN(64, 1); else if (G == 2) ATTN(64, 2); else ATTN(64, 4); }
   else { if (G == 1) ATTN(128, 1); else if (G == 2) ATTN(128, 2); else ATTN(128, 4); }
 #undef ATTN
@@ -207,7 +226,8 @@ void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int 
   const int oproj_blocks = (d + kProjRows * kWavesPerBlock - 1) / (kProjRows * kWavesPerBlock);
   L.before(kKOproj);
   hipLaunchKernelGGL((k_proj_resid<WT, kProjRows>), dim3(oproj_blocks), dim3(kBlock), (size_t)nq * 4, L.s, cm, role,
-                     (const float *)a, nq, (const WT *)x->wo[layer], d, xin_sel, xwork);
+                     defer ? (const float *)part : (const float *)a, nq, (const WT *)x->wo[layer], d, xin_sel, xwork,
+                     defer ? c.head_dim : 0, x->lay.n_splits);
   L.after();
 
   const int gu_blocks = (f + kGuPairs * kWavesPerBlock - 1) / (kGuPairs * kWavesPerBlock);
@@ -218,7 +238,7 @@ void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int 
 
   L.before(kKDown);
   hipLaunchKernelGGL((k_proj_resid<WT, kProjRows>), dim3(oproj_blocks), dim3(kBlock), (size_t)f * 4, L.s, cm, role,
-                     (const float *)mb, f, (const WT *)x->wdown[layer], d, xwork, xout_last_sel);
+                     (const float *)mb, f, (const WT *)x->wdown[layer], d, xwork, xout_last_sel, 0, 1);
   L.after();
 }
 
@@ -339,6 +359,107 @@ int drain_kernel_events(ppsd_ctx *x, const std::vector<char> *active_mask) {
   return PPSD_OK;
 }
 
+// ---------------------------------------------------------------- persistent engine
+MegaArgs mega_args(ppsd_ctx *x, bool prefill, int max_steps) {
+  const ppsd_config &c = x->cfg;
+  MegaArgs A{};
+  A.cm = x->cm;
+  A.layers = at<const LayerPtrs>(x, x->lay.layer_ptrs);
+  A.embed = x->embed; A.final_norm = (const float *)x->final_norm; A.lm_head = x->lm_head;
+  A.exit_norm = (const float *)x->exit_norm; A.exit_head = x->exit_head;
+  for (int s = 0; s < 2; ++s) {
+    A.q[s] = at<float>(x, x->lay.q[s]); A.a[s] = at<float>(x, x->lay.a[s]); A.m[s] = at<float>(x, x->lay.mbuf[s]);
+    A.partials[s] = at<float>(x, x->lay.partials[s]); A.counters[s] = at<int>(x, x->lay.counters[s]);
+  }
+  A.cand_lm = at<float2>(x, x->lay.cand_lm); A.cand_exit = at<float2>(x, x->lay.cand_exit);
+  A.logits = c.debug_logits > 0 ? at<float>(x, x->lay.logits) : nullptr;
+  A.out_tokens = at<int32_t>(x, x->lay.out_tokens); A.drafts = at<int32_t>(x, x->lay.drafts);
+  A.bar = at<unsigned>(x, x->lay.bar); A.abort_flag = at<int>(x, x->lay.abort_flag);
+  A.max_steps = max_steps; A.attn_splits = x->mega_splits; A.xs_stride = x->xs_stride;
+  A.trace = (!prefill && x->trace_step >= 0) ? at<unsigned long long>(x, x->lay.trace) : nullptr;
+  A.trace_step = x->trace_step; A.trace_wg = x->trace_wg;
+  auto whole = [&](int role, int head) {
+    return StageDesc{role, 0, c.n_layers, 0, kXDraft, 1, kXDraft, kXDraft, head, kXDraft};
+  };
+  if (prefill) {
+    A.n_stages = 1; A.zip = 0; A.commit_kind = 2; A.st[0] = whole(kPrefill, 3);
+  } else if (c.mode == PPSD_MODE_VANILLA) {
+    A.n_stages = 1; A.zip = 0; A.commit_kind = 0; A.st[0] = whole(kVanilla, 1);
+  } else {
+    A.n_stages = 2; A.zip = c.mode == PPSD_MODE_OVERLAP ? 1 : 0; A.commit_kind = 1;
+    A.st[0] = StageDesc{kDraft, 0, c.exit_layer, 0, kXDraft, 1, kXDraft, kHExitNext, 2, kHExitNext};
+    A.st[1] = StageDesc{kVerify, c.exit_layer, c.n_layers, 1, kHExitCur, 0, kXVerify, kXVerify, 1, kXVerify};
+  }
+  return A;
+}
+
+template <typename WT>
+const void *mega_fn_for(int hd, int g) {
+  if (hd == 64) return g == 1 ? (const void *)k_mega<WT, 64, 1> : g == 2 ? (const void *)k_mega<WT, 64, 2> : (const void *)k_mega<WT, 64, 4>;
+  return g == 1 ? (const void *)k_mega<WT, 128, 1> : g == 2 ? (const void *)k_mega<WT, 128, 2> : (const void *)k_mega<WT, 128, 4>;
+}
+
+const void *mega_fn(const ppsd_config &c) {
+  const int g = c.n_heads / c.n_kv_heads;
+  return c.dtype == PPSD_FP32 ? mega_fn_for<float>(c.head_dim, g) : mega_fn_for<bf16_t>(c.head_dim, g);
+}
+
+int mega_launch(ppsd_ctx *x, bool prefill, int max_steps) {
+  MegaArgs A = mega_args(x, prefill, max_steps);
+  HIP_TRY(hipMemsetAsync(A.bar, 0, 4, x->sA));
+  HIP_TRY(hipMemsetAsync(A.abort_flag, 0, 4, x->sA));
+  void *params[] = {&A};
+  const void *fn = mega_fn(x->cfg);
+  HIP_TRY(hipLaunchCooperativeKernel(fn, dim3(x->n_wg), dim3(kMBlock), params, (unsigned)x->mega_lds, x->sA));
+  return PPSD_OK;
+}
+
+int mega_check_abort(ppsd_ctx *x) {
+  int flag = 0;
+  HIP_TRY(hipMemcpyAsync(&flag, at<int>(x, x->lay.abort_flag), 4, hipMemcpyDeviceToHost, x->sA));
+  HIP_TRY(hipStreamSynchronize(x->sA));
+  if (flag) return fail(PPSD_EHIP, "persistent kernel gave up at a grid barrier (bounded wait expired)");
+  return PPSD_OK;
+}
+
+int mega_setup(ppsd_ctx *x) {
+  const ppsd_config &c = x->cfg;
+  int dev = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  hipDeviceProp_t prop;
+  HIP_TRY(hipGetDeviceProperties(&prop, dev));
+  if (!prop.cooperativeLaunch) return fail(PPSD_EARG, "device does not support cooperative launches");
+  if (c.d_model > 16 * kMBlock) return fail(PPSD_EARG, "persistent engine supports d_model <= %d", 16 * kMBlock);
+  const int nq = c.n_heads * c.head_dim;
+  int xs = c.d_model > nq ? c.d_model : nq;
+  if (c.d_ffn > xs) xs = c.d_ffn;
+  x->xs_stride = (xs + 63) / 64 * 64;
+  const int vec = c.dtype == PPSD_FP32 ? 4 : 8;
+  const int G = c.n_heads / c.n_kv_heads;
+  const size_t merge_floats = (size_t)(kMBlock / (c.head_dim / vec)) * G * (c.head_dim + 2);
+  size_t lds_floats = 2 * (size_t)x->xs_stride;
+  if (merge_floats > lds_floats) lds_floats = merge_floats;
+  x->mega_lds = lds_floats * 4;
+  if (x->mega_lds > 150 * 1024) return fail(PPSD_EARG, "persistent engine needs %zu bytes of LDS", x->mega_lds);
+  const void *fn = mega_fn(c);
+  HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)x->mega_lds));
+  int per_cu = 0;
+  HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kMBlock, x->mega_lds));
+  if (per_cu < 1) return fail(PPSD_EARG, "persistent kernel does not fit on a CU (LDS %zu bytes)", x->mega_lds);
+  x->n_wg = prop.multiProcessorCount;
+  if (x->n_wg > kMaxWorkgroups) x->n_wg = kMaxWorkgroups;
+  int sp = x->n_wg / (2 * c.n_kv_heads);
+  const int pages = x->lay.n_pages;
+  if (sp > pages) sp = pages;
+  x->mega_splits = sp < 1 ? 1 : (sp > kMaxSplits ? kMaxSplits : sp);
+  std::vector<LayerPtrs> lp(c.n_layers);
+  for (int l = 0; l < c.n_layers; ++l)
+    lp[l] = LayerPtrs{(const float *)x->attn_norm[l], x->wqkv[l], x->wo[l], (const float *)x->mlp_norm[l], x->wgu[l], x->wdown[l]};
+  HIP_TRY(hipMemcpyAsync(at<LayerPtrs>(x, x->lay.layer_ptrs), lp.data(), sizeof(LayerPtrs) * lp.size(), hipMemcpyHostToDevice, x->sA));
+  HIP_TRY(hipStreamSynchronize(x->sA));
+  return PPSD_OK;
+}
+
 int read_state(ppsd_ctx *x) {
   HIP_TRY(hipMemcpyAsync(x->h_state, at<DevState>(x, x->lay.state), sizeof(DevState), hipMemcpyDeviceToHost, x->sA));
   HIP_TRY(hipStreamSynchronize(x->sA));
@@ -456,7 +577,10 @@ int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *b, ppsd_ctx **
     HIP_TRY_X(hipStreamSynchronize(x->sA));   // host vectors go out of scope
   }
 
-  if (cfg->use_graph && !cfg->time_kernels) {
+  if (cfg->engine == PPSD_ENGINE_PERSISTENT) {
+    int rc = mega_setup(x);
+    if (rc != PPSD_OK) return cleanup(rc);
+  } else if (cfg->use_graph && !cfg->time_kernels) {
     int rc = capture(x, &x->g_step, [&] { return enqueue_step_any(x, cfg->mode, cfg->mode == PPSD_MODE_OVERLAP, false); });
     if (rc != PPSD_OK) return cleanup(rc);
     rc = capture(x, &x->g_prefill, [&] { return enqueue_prefill_any(x, false, false); });
@@ -493,12 +617,20 @@ int ppsd_prefill(ppsd_ctx *x, const int32_t *prompt, int32_t n_prompt, int32_t *
   HIP_TRY(hipMemcpyAsync(at<int32_t>(x, x->lay.prompt), prompt, 4ull * n_prompt, hipMemcpyHostToDevice, x->sA));
   hipLaunchKernelGGL(k_begin_prefill, dim3(1), dim3(64), 0, x->sA, at<DevState>(x, x->lay.state), n_prompt);
   HIP_TRY(hipGetLastError());
-  for (int p = 0; p < n_prompt; ++p) {
-    const bool last = p == n_prompt - 1;
-    if (!last && x->g_prefill) HIP_TRY(hipGraphLaunch(x->g_prefill, x->sA));
-    else HIP_TRY(enqueue_prefill_any(x, last, false));
+  int rc;
+  if (x->cfg.engine == PPSD_ENGINE_PERSISTENT) {
+    rc = mega_launch(x, true, n_prompt);
+    if (rc != PPSD_OK) return rc;
+    rc = mega_check_abort(x);
+    if (rc != PPSD_OK) return rc;
+  } else {
+    for (int p = 0; p < n_prompt; ++p) {
+      const bool last = p == n_prompt - 1;
+      if (!last && x->g_prefill) HIP_TRY(hipGraphLaunch(x->g_prefill, x->sA));
+      else HIP_TRY(enqueue_prefill_any(x, last, false));
+    }
   }
-  int rc = read_state(x);
+  rc = read_state(x);
   if (rc != PPSD_OK) return rc;
   if (x->h_state->prefill_pos != n_prompt || x->h_state->t != n_prompt)
     return fail(PPSD_ESTATE, "prefill ended in an unexpected device state (pos %d, t %d)", x->h_state->prefill_pos, x->h_state->t);
@@ -531,7 +663,17 @@ int ppsd_decode(ppsd_ctx *x, int32_t n_tokens, int32_t *out_tokens, int32_t *n_w
   int remaining = n_tokens;
   int guard = 0;
   while (remaining > 0) {
-    if (timed) {
+    if (c.engine == PPSD_ENGINE_PERSISTENT) {
+      // each step commits at most one token and at least every second step commits one
+      const int max_steps = 2 * remaining + 2;
+      int rc = mega_launch(x, false, max_steps);
+      if (rc != PPSD_OK) return rc;
+      x->steps_launched += 1;
+      rc = mega_check_abort(x);
+      if (rc != PPSD_OK) return rc;
+      rc = read_state(x);
+      if (rc != PPSD_OK) return rc;
+    } else if (timed) {
       // one step at a time so idle launches can be told apart from active ones
       int rc = read_state(x);
       if (rc != PPSD_OK) return rc;
@@ -608,6 +750,22 @@ int ppsd_kernel_times(const ppsd_ctx *x, ppsd_kernel_times_t *out) {
   if (!x || !out) return fail(PPSD_EARG, "null argument");
   if (!x->cfg.time_kernels) return fail(PPSD_ESTATE, "context was not created with time_kernels = 1");
   *out = x->ktimes;
+  return PPSD_OK;
+}
+
+int ppsd_trace_request(ppsd_ctx *x, int32_t step, int32_t workgroup) {
+  if (!x) return fail(PPSD_EARG, "null argument");
+  if (x->cfg.engine != PPSD_ENGINE_PERSISTENT) return fail(PPSD_ESTATE, "the timeline exists for the persistent engine only");
+  x->trace_step = step;
+  x->trace_wg = workgroup;
+  return PPSD_OK;
+}
+
+int ppsd_trace_read(ppsd_ctx *x, int32_t n_phases, uint64_t *out) {
+  if (!x || !out) return fail(PPSD_EARG, "null argument");
+  if (n_phases < 0 || n_phases > kTracePhases) return fail(PPSD_EARG, "at most %d phases are recorded", kTracePhases);
+  HIP_TRY(hipMemcpyAsync(out, at<uint64_t>(x, x->lay.trace), 8ull * kTraceSlots * n_phases, hipMemcpyDeviceToHost, x->sA));
+  HIP_TRY(hipStreamSynchronize(x->sA));
   return PPSD_OK;
 }
 

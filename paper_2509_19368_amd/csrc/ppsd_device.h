@@ -11,6 +11,7 @@ typedef uint16_t bf16_t;   // raw bfloat16 bits
 constexpr int kWave = 64;
 constexpr int kBlock = 256;          // threads per workgroup in every kernel
 constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kTripBlocks = 4;       // column blocks per trip of the row-streaming kernels
 constexpr float kNegBig = -1.0e30f;  // finite stand-in for -inf in the running softmax maximum
 
 // Stage roles: which part of the device state a kernel takes its input from.
@@ -101,6 +102,24 @@ __device__ __forceinline__ uint4 ld16_stream(const void *p) {
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// Same, for a wave-uniform base pointer known to be global memory plus a per-lane byte offset:
+// compiles to a global (not flat) load with a scalar base.
+typedef const u32x4_t __attribute__((address_space(1))) *gptr16_t;
+__device__ __forceinline__ uint4 ld16_stream_global(const void *base, uint32_t byte_off) {
+  const u32x4_t v = __builtin_nontemporal_load((gptr16_t)((uintptr_t)base + byte_off));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// Values that are the same in every lane but arrive through vector loads: pin them to scalars.
+__device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+template <typename T>
+__device__ __forceinline__ T *uniform_ptr(T *p) {
+  const uintptr_t u = (uintptr_t)p;
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)u);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(u >> 32));
+  return (T *)(((uintptr_t)hi << 32) | lo);
+}
+
 // ---------------------------------------------------------------- numeric helpers
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t hi16_in_low) {
   return __uint_as_float(hi16_in_low << 16);
@@ -168,66 +187,72 @@ __device__ __forceinline__ void wave_argmax(float &v, int &i) {
 }
 
 // ---------------------------------------------------------------- weight-streaming dot products
-// acc[r] += sum_c W[rows[r]][c] * xs[c] over this lane's columns.  xs lives in LDS, C % N == 0,
-// every row pointer 16-byte aligned.  Lane l of the wave owns columns (it*64 + l)*N .. +N.
-template <typename WT, int R>
-__device__ __forceinline__ void stream_dot(const WT *const (&rows)[R], const float *xs, int C,
-                                           float (&acc)[R]) {
+// A wave streams R rows at a time, KB column blocks per trip (R*KB independent 16-byte loads in
+// flight per lane).  Lane l owns columns (blk*64 + l)*N .. +N of every row; a lane past the end of
+// a ragged last block re-reads the row's last 16 bytes and its products are skipped.  The first
+// trip is issued by the caller BEFORE its prologue (state is known, input vector not yet staged):
+// the weights a wave reads never depend on activations, so the prologue's latency chain runs under
+// the first loads.  Per row the FMA chain runs in increasing column order; the reduction order is
+// fixed (no atomics), which keeps every scheduling mode bitwise identical.
+template <typename WT, int R, int KB>
+struct Trip {
+  uint4 u[R * KB];
+};
+
+template <typename WT>
+__device__ __forceinline__ int col_blocks(int C) { return (C + kWave * Pack<WT>::N - 1) / (kWave * Pack<WT>::N); }
+
+template <typename WT, int R, int KB>
+__device__ __forceinline__ void trip_load(Trip<WT, R, KB> &t, const WT *const (&rows)[R], int cb, int nblk, int C) {
   constexpr int N = Pack<WT>::N;
   constexpr int kStride = kWave * N;
   const int lane = threadIdx.x & 63;
-  const int full = C / kStride;
-  int c = lane * N;
-  int it = 0;
-  // two column blocks per trip: 2*R independent 16-byte loads in flight per lane
-  for (; it + 2 <= full; it += 2, c += 2 * kStride) {
-    uint4 u0[R], u1[R];
+  const int last = C - N;
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      u0[r] = ld16_stream(rows[r] + c);
-      u1[r] = ld16_stream(rows[r] + c + kStride);
-    }
-    float x0[N], x1[N];
+  for (int k = 0; k < KB; ++k) {
+    if (cb + k < nblk) {   // wave-uniform
+      const int c = min((cb + k) * kStride + lane * N, last);
 #pragma unroll
-    for (int k = 0; k < N; ++k) { x0[k] = xs[c + k]; x1[k] = xs[c + kStride + k]; }
+      for (int r = 0; r < R; ++r) t.u[r * KB + k] = ld16_stream(rows[r] + c);
+    } else {
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      float w0[N], w1[N];
-      Pack<WT>::unpack(u0[r], w0);
-      Pack<WT>::unpack(u1[r], w1);
-#pragma unroll
-      for (int k = 0; k < N; ++k) acc[r] = fmaf(w0[k], x0[k], acc[r]);
-#pragma unroll
-      for (int k = 0; k < N; ++k) acc[r] = fmaf(w1[k], x1[k], acc[r]);
+      for (int r = 0; r < R; ++r) t.u[r * KB + k] = make_uint4(0u, 0u, 0u, 0u);
     }
   }
-  for (; it < full; ++it, c += kStride) {
-    uint4 u0[R];
+}
+
+template <typename WT, int R, int KB>
+__device__ __forceinline__ void trip_consume(const Trip<WT, R, KB> &t, const float *xs, int cb, int C,
+                                             float (&acc)[R]) {
+  constexpr int N = Pack<WT>::N;
+  constexpr int kStride = kWave * N;
+  const int lane = threadIdx.x & 63;
 #pragma unroll
-    for (int r = 0; r < R; ++r) u0[r] = ld16_stream(rows[r] + c);
-    float x0[N];
+  for (int k = 0; k < KB; ++k) {
+    const int c = (cb + k) * kStride + lane * N;
+    if (c < C) {
+      float x[N];
 #pragma unroll
-    for (int k = 0; k < N; ++k) x0[k] = xs[c + k];
+      for (int e = 0; e < N; ++e) x[e] = xs[c + e];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      float w0[N];
-      Pack<WT>::unpack(u0[r], w0);
+      for (int r = 0; r < R; ++r) {
+        float w[N];
+        Pack<WT>::unpack(t.u[r * KB + k], w);
 #pragma unroll
-      for (int k = 0; k < N; ++k) acc[r] = fmaf(w0[k], x0[k], acc[r]);
+        for (int e = 0; e < N; ++e) acc[r] = fmaf(w[e], x[e], acc[r]);
+      }
     }
   }
-  if (c < C) {   // ragged tail: only the low lanes have columns left
-    float x0[N];
-#pragma unroll
-    for (int k = 0; k < N; ++k) x0[k] = xs[c + k];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      uint4 u = ld16_stream(rows[r] + c);
-      float w0[N];
-      Pack<WT>::unpack(u, w0);
-#pragma unroll
-      for (int k = 0; k < N; ++k) acc[r] = fmaf(w0[k], x0[k], acc[r]);
-    }
+}
+
+// acc[r] += W[rows[r], :] . xs, given the first trip already in flight in t.
+template <typename WT, int R, int KB>
+__device__ __forceinline__ void stream_rows(Trip<WT, R, KB> &t, const WT *const (&rows)[R], const float *xs, int C,
+                                            float (&acc)[R]) {
+  const int nblk = col_blocks<WT>(C);
+  for (int cb = 0; cb < nblk; cb += KB) {
+    trip_consume<WT, R, KB>(t, xs, cb, C, acc);
+    if (cb + KB < nblk) trip_load<WT, R, KB>(t, rows, cb + KB, nblk, C);
   }
 }
 

@@ -29,23 +29,18 @@ __global__ __launch_bounds__(kBlock) void k_qkv(Common c, int role, int layer, i
                                                 float *qout) {
   extern __shared__ float xs[];
   __shared__ float red[kWavesPerBlock];
+  constexpr int R = 2 * PAIRS, KB = kTripBlocks;
   const StageIn si = stage_in(c, role);
   if (!si.active) return;
   const Dims &m = c.dm;
   const int d = m.d;
-  {
-    const WT *xrow = from_embed ? embed + (size_t)si.tok * d : nullptr;
-    const float *xf = from_embed ? nullptr : xslot(c, xin_sel);
-    float *copy_out = (from_embed && blockIdx.x == 0) ? xslot(c, xin_sel) : nullptr;
-    load_and_norm<WT>(xf, xrow, gain, d, m.eps, xs, red, copy_out);
-  }
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int half = m.hd >> 1;
   const int total_pairs = (m.n_h + 2 * m.n_kv) * half;
   const int pair0 = (blockIdx.x * kWavesPerBlock + wave) * PAIRS;
-  if (pair0 >= total_pairs) return;
+  const bool has_rows = pair0 < total_pairs;
 
-  const WT *rows[2 * PAIRS];
+  const WT *rows[R];
   int head[PAIRS], idx[PAIRS];
 #pragma unroll
   for (int p = 0; p < PAIRS; ++p) {
@@ -55,12 +50,21 @@ __global__ __launch_bounds__(kBlock) void k_qkv(Common c, int role, int layer, i
     rows[2 * p] = wqkv + (size_t)(head[p] * m.hd + idx[p]) * d;
     rows[2 * p + 1] = rows[2 * p] + (size_t)half * d;
   }
-  float acc[2 * PAIRS];
+  Trip<WT, R, KB> trip;
+  if (has_rows) trip_load<WT, R, KB>(trip, rows, 0, col_blocks<WT>(d), d);   // in flight during the prologue
+  {
+    const WT *xrow = from_embed ? embed + (size_t)si.tok * d : nullptr;
+    const float *xf = from_embed ? nullptr : xslot(c, xin_sel);
+    float *copy_out = (from_embed && blockIdx.x == 0) ? xslot(c, xin_sel) : nullptr;
+    load_and_norm<WT>(xf, xrow, gain, d, m.eps, xs, red, copy_out);
+  }
+  if (!has_rows) return;
+  float acc[R];
 #pragma unroll
-  for (int r = 0; r < 2 * PAIRS; ++r) acc[r] = 0.f;
-  stream_dot<WT, 2 * PAIRS>(rows, xs, d, acc);
+  for (int r = 0; r < R; ++r) acc[r] = 0.f;
+  stream_rows<WT, R, KB>(trip, rows, xs, d, acc);
 #pragma unroll
-  for (int r = 0; r < 2 * PAIRS; ++r) acc[r] = wave_sum(acc[r]);
+  for (int r = 0; r < R; ++r) acc[r] = wave_sum(acc[r]);
 
   if (lane < PAIRS && pair0 + lane < total_pairs) {
     float lo = 0.f, hi = 0.f;
@@ -89,26 +93,23 @@ __global__ __launch_bounds__(kBlock) void k_qkv(Common c, int role, int layer, i
 }
 
 // ------------------------------------------------------------------------------------------
-// a4: decode attention over the paged KV cache.
-// grid = (n_kv, n_splits).  A group of GS = HD / N lanes owns one position at a time (each lane
-// holds N consecutive dims of the K and V rows, loaded as one 16-byte vector); the G query heads
-// that share this KV head reuse the same K/V registers.  Every group keeps a running softmax
-// (max, sum, weighted V) and the groups are merged through LDS in a fixed order.  With several
-// splits the last workgroup to finish a KV head merges the splits, also in fixed order.
-template <typename WT, int HD, int G>
-__global__ __launch_bounds__(kBlock) void k_attn(Common c, int role, int layer, const float *q, float *aout,
-                                                 float *partials, int *counters) {
+// a4: decode attention over the paged KV cache, one (KV head, split) unit per call.
+// A group of GS = HD / N lanes owns one position at a time (each lane holds N consecutive dims of
+// the K and V rows, loaded as one 16-byte vector); the G query heads that share this KV head reuse
+// the same K/V registers.  Every group keeps a running softmax (max, sum, weighted V) and the
+// groups are merged through LDS (`merge`, BLOCK/GS * G * (HD+2) floats) in a fixed order.  With
+// several splits the last workgroup to finish a KV head merges the splits, also in fixed order.
+// Must be called by all BLOCK threads of the workgroup; ends with the workgroup synchronised.
+template <typename WT, int HD, int G, int BLOCK>
+__device__ __forceinline__ void attn_unit(const Common &c, int layer, int pos, int kvh, int split, int n_splits,
+                                          const float *q, float *aout, float *partials, int *counters,
+                                          float *merge, int *s_last, bool defer_merge) {
   constexpr int N = Pack<WT>::N;
   constexpr int GS = HD / N;               // lanes per position
-  constexpr int GPB = kBlock / GS;         // position groups per workgroup
+  constexpr int GPB = BLOCK / GS;          // position groups per workgroup
   constexpr int REC = HD + 2;              // m, l, acc[HD]
-  __shared__ float merge[GPB * G * REC];
-  __shared__ int s_last;
-  const StageIn si = stage_in(c, role);
-  if (!si.active) return;
   const Dims &m = c.dm;
-  const int kvh = blockIdx.x, split = blockIdx.y, n_splits = gridDim.y;
-  const int len = si.pos + 1;
+  const int len = pos + 1;
   // split ranges are page aligned
   int chunk = (len + n_splits - 1) / n_splits;
   chunk = ((chunk + m.page_tokens - 1) / m.page_tokens) * m.page_tokens;
@@ -179,7 +180,7 @@ __global__ __launch_bounds__(kBlock) void k_attn(Common c, int role, int layer, 
     for (int k = 0; k < N; ++k) rec[2 + j * N + k] = acc[g][k];
   }
   __syncthreads();
-  for (int o = tid; o < G * HD; o += kBlock) {
+  for (int o = tid; o < G * HD; o += BLOCK) {
     const int g = o / HD, dim = o % HD;
     float M = kNegBig;
     for (int r = 0; r < GPB; ++r) M = fmaxf(M, merge[(r * G + g) * REC]);
@@ -191,7 +192,7 @@ __global__ __launch_bounds__(kBlock) void k_attn(Common c, int role, int layer, 
       A = fmaf(rec[2 + dim], w, A);
     }
     const int head = kvh * G + g;
-    if (n_splits == 1) {
+    if (n_splits == 1 && !defer_merge) {
       aout[head * HD + dim] = A / L;
     } else {
       float *pr = partials + ((size_t)head * n_splits + split) * REC;
@@ -199,56 +200,98 @@ __global__ __launch_bounds__(kBlock) void k_attn(Common c, int role, int layer, 
       pr[2 + dim] = A;
     }
   }
-  if (n_splits == 1) return;
-
-  // last workgroup of this KV head merges the splits
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    const int prev = atomicAdd(&counters[kvh], 1);
-    s_last = (prev == n_splits - 1);
-  }
-  __syncthreads();
-  if (!s_last) return;
-  __threadfence();
-  for (int o = tid; o < G * HD; o += kBlock) {
-    const int g = o / HD, dim = o % HD;
-    const int head = kvh * G + g;
-    const float *pr = partials + (size_t)head * n_splits * REC;
-    float M = kNegBig;
-    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, __builtin_nontemporal_load(pr + s * REC));
-    float L = 0.f, A = 0.f;
-    for (int s = 0; s < n_splits; ++s) {
-      const float w = __expf(__builtin_nontemporal_load(pr + s * REC) - M);
-      L = fmaf(__builtin_nontemporal_load(pr + s * REC + 1), w, L);
-      A = fmaf(__builtin_nontemporal_load(pr + s * REC + 2 + dim), w, A);
+  if (n_splits > 1 && !defer_merge) {
+    // last workgroup of this KV head merges the splits
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) {
+      const int prev = atomicAdd(&counters[kvh], 1);
+      *s_last = (prev == n_splits - 1);
     }
-    aout[head * HD + dim] = A / L;
+    __syncthreads();
+    if (*s_last) {
+      __threadfence();
+      for (int o = tid; o < G * HD; o += BLOCK) {
+        const int g = o / HD, dim = o % HD;
+        const int head = kvh * G + g;
+        const float *pr = partials + (size_t)head * n_splits * REC;
+        float M = kNegBig;
+        for (int s = 0; s < n_splits; ++s) M = fmaxf(M, __builtin_nontemporal_load(pr + s * REC));
+        float L = 0.f, A = 0.f;
+        for (int s = 0; s < n_splits; ++s) {
+          const float w = __expf(__builtin_nontemporal_load(pr + s * REC) - M);
+          L = fmaf(__builtin_nontemporal_load(pr + s * REC + 1), w, L);
+          A = fmaf(__builtin_nontemporal_load(pr + s * REC + 2 + dim), w, A);
+        }
+        aout[head * HD + dim] = A / L;
+      }
+      if (tid == 0) counters[kvh] = 0;   // ready for the next use (a later launch or a later phase)
+    }
   }
-  if (tid == 0) counters[kvh] = 0;   // ready for the next launch (stream order separates launches)
+  __syncthreads();   // merge / s_last may be reused by the caller
+}
+
+// grid = (n_kv, n_splits)
+template <typename WT, int HD, int G>
+__global__ __launch_bounds__(kBlock) void k_attn(Common c, int role, int layer, const float *q, float *aout,
+                                                 float *partials, int *counters, int defer_merge) {
+  constexpr int GPB = kBlock / (HD / Pack<WT>::N);
+  __shared__ float merge[GPB * G * (HD + 2)];
+  __shared__ int s_last;
+  const StageIn si = stage_in(c, role);
+  if (!si.active) return;
+  attn_unit<WT, HD, G, kBlock>(c, layer, si.pos, blockIdx.x, blockIdx.y, gridDim.y, q, aout, partials, counters,
+                               merge, &s_last, defer_merge != 0);
 }
 
 // ------------------------------------------------------------------------------------------
+// Merges the attention splits of one element (head, dim) from the per-split records
+// [head][split][m, l, acc[hd]] in split order: a = sum_s acc_s e^(m_s - M) / sum_s l_s e^(m_s - M).
+__device__ __forceinline__ float merge_splits(const float *partials, int head, int dim, int hd, int n_splits) {
+  const int rec = hd + 2;
+  const float *pr = partials + (size_t)head * n_splits * rec;
+  float M = kNegBig;
+  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, pr[s * rec]);
+  float L = 0.f, A = 0.f;
+  for (int s = 0; s < n_splits; ++s) {
+    const float w = __expf(pr[s * rec] - M);
+    L = fmaf(pr[s * rec + 1], w, L);
+    A = fmaf(pr[s * rec + 2 + dim], w, A);
+  }
+  return A / L;
+}
+
 // a5 / a7: out[r] = resid[r] + W[r,:] . vin   (o_proj and down_proj with the residual add fused).
+// With merge_hd > 0 the input is the attention output still in per-split form and is merged while
+// it is staged (merge_hd = head_dim, n_splits records per head).
 // grid = ceil(rows / (R * 4)); dynamic LDS = C floats.
 template <typename WT, int R>
 __global__ __launch_bounds__(kBlock) void k_proj_resid(Common c, int role, const float *vin, int C,
-                                                       const WT *W, int rows, int resid_sel, int out_sel) {
+                                                       const WT *W, int rows, int resid_sel, int out_sel,
+                                                       int merge_hd, int n_splits) {
   extern __shared__ float xs[];
+  constexpr int KB = kTripBlocks;
   const StageIn si = stage_in(c, role);
   if (!si.active) return;
-  for (int i = threadIdx.x; i < C; i += kBlock) xs[i] = vin[i];
-  __syncthreads();
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int r0 = (blockIdx.x * kWavesPerBlock + wave) * R;
-  if (r0 >= rows) return;
+  const bool has_rows = r0 < rows;
   const WT *rp[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) rp[r] = W + (size_t)min(r0 + r, rows - 1) * C;
+  Trip<WT, R, KB> trip;
+  if (has_rows) trip_load<WT, R, KB>(trip, rp, 0, col_blocks<WT>(C), C);
+  if (merge_hd > 0) {
+    for (int i = threadIdx.x; i < C; i += kBlock) xs[i] = merge_splits(vin, i / merge_hd, i % merge_hd, merge_hd, n_splits);
+  } else {
+    for (int i = threadIdx.x; i < C; i += kBlock) xs[i] = vin[i];
+  }
+  __syncthreads();
+  if (!has_rows) return;
   float acc[R];
 #pragma unroll
   for (int r = 0; r < R; ++r) acc[r] = 0.f;
-  stream_dot<WT, R>(rp, xs, C, acc);
+  stream_rows<WT, R, KB>(trip, rp, xs, C, acc);
 #pragma unroll
   for (int r = 0; r < R; ++r) acc[r] = wave_sum(acc[r]);
   if (lane < R && r0 + lane < rows) {
@@ -269,27 +312,31 @@ __global__ __launch_bounds__(kBlock) void k_gate_up(Common c, int role, int xin_
                                                     const WT *wgu, float *mout) {
   extern __shared__ float xs[];
   __shared__ float red[kWavesPerBlock];
+  constexpr int R = 2 * PAIRS, KB = kTripBlocks;
   const StageIn si = stage_in(c, role);
   if (!si.active) return;
   const Dims &m = c.dm;
   const int d = m.d, f = m.f;
-  load_and_norm<WT>(xslot(c, xin_sel), nullptr, gain, d, m.eps, xs, red, nullptr);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int i0 = (blockIdx.x * kWavesPerBlock + wave) * PAIRS;
-  if (i0 >= f) return;
-  const WT *rows[2 * PAIRS];
+  const bool has_rows = i0 < f;
+  const WT *rows[R];
 #pragma unroll
   for (int p = 0; p < PAIRS; ++p) {
     const int i = min(i0 + p, f - 1);
     rows[2 * p] = wgu + (size_t)i * d;
     rows[2 * p + 1] = wgu + (size_t)(f + i) * d;
   }
-  float acc[2 * PAIRS];
+  Trip<WT, R, KB> trip;
+  if (has_rows) trip_load<WT, R, KB>(trip, rows, 0, col_blocks<WT>(d), d);
+  load_and_norm<WT>(xslot(c, xin_sel), nullptr, gain, d, m.eps, xs, red, nullptr);
+  if (!has_rows) return;
+  float acc[R];
 #pragma unroll
-  for (int r = 0; r < 2 * PAIRS; ++r) acc[r] = 0.f;
-  stream_dot<WT, 2 * PAIRS>(rows, xs, d, acc);
+  for (int r = 0; r < R; ++r) acc[r] = 0.f;
+  stream_rows<WT, R, KB>(trip, rows, xs, d, acc);
 #pragma unroll
-  for (int r = 0; r < 2 * PAIRS; ++r) acc[r] = wave_sum(acc[r]);
+  for (int r = 0; r < R; ++r) acc[r] = wave_sum(acc[r]);
   if (lane < PAIRS && i0 + lane < f) {
     float g = 0.f, u = 0.f;
 #pragma unroll
@@ -310,23 +357,26 @@ __global__ __launch_bounds__(kBlock) void k_head(Common c, int role, int xin_sel
   __shared__ float red[kWavesPerBlock];
   __shared__ float bv[kWavesPerBlock];
   __shared__ int bi[kWavesPerBlock];
+  constexpr int KB = kTripBlocks;
   const StageIn si = stage_in(c, role);
   if (!si.active) return;
   const Dims &m = c.dm;
   const int d = m.d, V = m.V;
-  load_and_norm<WT>(xslot(c, xin_sel), nullptr, gain, d, m.eps, xs, red, nullptr);
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int r0 = (blockIdx.x * kWavesPerBlock + wave) * R;
+  const WT *rp[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) rp[r] = W + (size_t)min(r0 + r, V - 1) * d;
+  Trip<WT, R, KB> trip;
+  if (r0 < V) trip_load<WT, R, KB>(trip, rp, 0, col_blocks<WT>(d), d);
+  load_and_norm<WT>(xslot(c, xin_sel), nullptr, gain, d, m.eps, xs, red, nullptr);
   float best = -INFINITY;
   int besti = 0x7fffffff;
   if (r0 < V) {
-    const WT *rp[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) rp[r] = W + (size_t)min(r0 + r, V - 1) * d;
     float acc[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) acc[r] = 0.f;
-    stream_dot<WT, R>(rp, xs, d, acc);
+    stream_rows<WT, R, KB>(trip, rp, xs, d, acc);
 #pragma unroll
     for (int r = 0; r < R; ++r) acc[r] = wave_sum(acc[r]);
     // logits row for the parity harness: row index = number of tokens committed so far
@@ -357,10 +407,12 @@ __global__ __launch_bounds__(kBlock) void k_head(Common c, int role, int xin_sel
 // a10: finish both argmax reductions, compare draft with the verifier's token, commit, roll back.
 // One workgroup.  kind: 0 vanilla step, 1 PPSD step, 2 prefill position (no head), 3 last prefill
 // position (LM head ran).
+template <int BLOCK>
 __device__ __forceinline__ int reduce_candidates(const float2 *cand, int n, float *sv, int *si_) {
+  constexpr int NW = BLOCK / kWave;
   float best = -INFINITY;
   int besti = 0x7fffffff;
-  for (int k = threadIdx.x; k < n; k += kBlock) {
+  for (int k = threadIdx.x; k < n; k += BLOCK) {
     const float2 cnd = cand[k];
     const int idx = __float_as_int(cnd.y);
     if (better(cnd.x, idx, best, besti)) { best = cnd.x; besti = idx; }
@@ -371,22 +423,22 @@ __device__ __forceinline__ int reduce_candidates(const float2 *cand, int n, floa
   __syncthreads();
   best = sv[0]; besti = si_[0];
 #pragma unroll
-  for (int w = 1; w < kWavesPerBlock; ++w)
+  for (int w = 1; w < NW; ++w)
     if (better(sv[w], si_[w], best, besti)) { best = sv[w]; besti = si_[w]; }
   return besti;
 }
 
-__global__ __launch_bounds__(kBlock) void k_commit(Common c, int kind, const float2 *cand_lm,
-                                                   const float2 *cand_exit, int32_t *out_tokens,
-                                                   int32_t *drafts_log) {
-  __shared__ float sv[kWavesPerBlock];
-  __shared__ int si_[kWavesPerBlock];
+// Called by all BLOCK threads of ONE workgroup.  sv / si_: BLOCK/64 entries of LDS each.
+template <int BLOCK>
+__device__ __forceinline__ void commit_step(const Common &c, int kind, const float2 *cand_lm,
+                                            const float2 *cand_exit, int n_cand, int32_t *out_tokens,
+                                            int32_t *drafts_log, float *sv, int *si_) {
   DevState *st = c.st;
-  const int nb = c.dm.head_blocks;
+  const int nb = n_cand;
   if (kind == 2 || kind == 3) {   // prefill
     if (!(st->prefill_pos < st->prefill_len)) return;
     int tok = -1;
-    if (kind == 3) tok = reduce_candidates(cand_lm, nb, sv, si_);
+    if (kind == 3) tok = reduce_candidates<BLOCK>(cand_lm, nb, sv, si_);
     if (threadIdx.x == 0) {
       st->prefill_pos += 1;
       if (kind == 3) {
@@ -402,7 +454,7 @@ __global__ __launch_bounds__(kBlock) void k_commit(Common c, int kind, const flo
   if (!(st->n_out < st->target)) return;
   const int full = st->full;
   if (kind == 0) {   // vanilla: the LM head's token is the next token
-    const int v = reduce_candidates(cand_lm, nb, sv, si_);
+    const int v = reduce_candidates<BLOCK>(cand_lm, nb, sv, si_);
     if (threadIdx.x == 0) {
       out_tokens[st->n_out] = v;
       drafts_log[st->gen_count] = -1;
@@ -412,9 +464,9 @@ __global__ __launch_bounds__(kBlock) void k_commit(Common c, int kind, const flo
     return;
   }
   // PPSD step
-  const int d_next = reduce_candidates(cand_exit, nb, sv, si_);   // draft stage always ran
+  const int d_next = reduce_candidates<BLOCK>(cand_exit, nb, sv, si_);   // draft stage always ran
   int v = -1;
-  if (full) v = reduce_candidates(cand_lm, nb, sv, si_);
+  if (full) v = reduce_candidates<BLOCK>(cand_lm, nb, sv, si_);
   if (threadIdx.x == 0) {
     if (!full) {                 // pipeline refill: nothing to commit yet
       st->draft = d_next;
@@ -440,6 +492,14 @@ __global__ __launch_bounds__(kBlock) void k_commit(Common c, int kind, const flo
       st->last_token = v;
     }
   }
+}
+
+__global__ __launch_bounds__(kBlock) void k_commit(Common c, int kind, const float2 *cand_lm,
+                                                   const float2 *cand_exit, int32_t *out_tokens,
+                                                   int32_t *drafts_log) {
+  __shared__ float sv[kWavesPerBlock];
+  __shared__ int si_[kWavesPerBlock];
+  commit_step<kBlock>(c, kind, cand_lm, cand_exit, c.dm.head_blocks, out_tokens, drafts_log, sv, si_);
 }
 
 // Host-requested state edits (tiny, one thread): new prefill / new decode target.

@@ -41,13 +41,19 @@ SMALL = [
 ]
 
 
-def test_c1_all_modes_reproduce_the_oracle_stream(P):
+ENGINES = [0, 1]
+ENGINE_IDS = ["streams", "persistent"]
+
+
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
+def test_c1_all_modes_reproduce_the_oracle_stream(P, engine):
     w = S.WORKLOADS["C1"]
     W = S.make_weights(w)
     prompt = S.make_prompt(w)
     dec, tr, sim = oracle_run(w, W, prompt, w.decode_len)
     Wg = to_device(W, "cuda")
-    runs = {m: _gpu_run(P, w, Wg, prompt, w.decode_len, m) for m in (P.MODE_VANILLA, P.MODE_SERIAL, P.MODE_OVERLAP)}
+    runs = {m: _gpu_run(P, w, Wg, prompt, w.decode_len, m, engine=engine)
+            for m in (P.MODE_VANILLA, P.MODE_SERIAL, P.MODE_OVERLAP)}
     for m, r in runs.items():
         assert r["tokens"] == tr.tokens, f"mode {m}"
         ref = torch.stack(tr.logits)
@@ -83,8 +89,9 @@ def test_drafts_equal_the_exit_heads_greedy_token(P):
     assert acc == r["stats"]["accepted"]
 
 
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
 @pytest.mark.parametrize("w", SMALL, ids=[w.name for w in SMALL])
-def test_small_ragged_shapes(P, w):
+def test_small_ragged_shapes(P, w, engine):
     W = S.make_weights(w)
     prompt = S.make_prompt(w)
     dec = O.Decoder(w, W)
@@ -92,7 +99,7 @@ def test_small_ragged_shapes(P, w):
     tol = REL_TOL_FP32 if w.dtype == "fp32" else REL_TOL_BF16
     ref_logits = None
     for mode in (P.MODE_VANILLA, P.MODE_SERIAL, P.MODE_OVERLAP):
-        r = _gpu_run(P, w, Wg, prompt, w.decode_len, mode)
+        r = _gpu_run(P, w, Wg, prompt, w.decode_len, mode, engine=engine)
         worst, loose = check_against_teacher_forced_oracle(dec, prompt, r["tokens"], r["logits"], tol)
         if w.dtype == "fp32":
             assert r["tokens"] == O.greedy_decode(dec, prompt, w.decode_len + 1).tokens
@@ -106,21 +113,23 @@ def test_small_ragged_shapes(P, w):
             assert st["steps_draft_only"] in (st["rejected"], st["rejected"] + 1)
 
 
-def test_alpha_one_and_alpha_zero_accounting(P):
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
+def test_alpha_one_and_alpha_zero_accounting(P, engine):
     w = S.WORKLOADS["C1"].replace(damp=0.0)
     W = S.make_weights(w)
     prompt = S.make_prompt(w)
-    r = _gpu_run(P, w, to_device(W, "cuda"), prompt, 32, P.MODE_OVERLAP)
+    r = _gpu_run(P, w, to_device(W, "cuda"), prompt, 32, P.MODE_OVERLAP, engine=engine)
     st = r["stats"]
     assert st["rejected"] == 0 and st["accepted"] == 32 and st["steps_draft_only"] == 1 and st["steps_overlapped"] == 32
     W["exit_head"] = -W["lm_head"]
-    r = _gpu_run(P, w, to_device(W, "cuda"), prompt, 32, P.MODE_OVERLAP)
+    r = _gpu_run(P, w, to_device(W, "cuda"), prompt, 32, P.MODE_OVERLAP, engine=engine)
     st = r["stats"]
     assert st["accepted"] == 0 and st["rejected"] == 32 == st["kv_rollbacks"] and st["steps_draft_only"] == 32
     assert r["tokens"] == O.greedy_decode(O.Decoder(w, W), prompt, 33).tokens
 
 
-def test_long_context_splits_and_shuffled_pages(P):
+@pytest.mark.parametrize("engine", ENGINES, ids=ENGINE_IDS)
+def test_long_context_splits_and_shuffled_pages(P, engine):
     """Context of several hundred positions: several attention splits, pages in shuffled order."""
     w = S.Workload("ctx", n_layers=2, exit_layer=1, d_model=128, n_heads=4, n_kv_heads=1, head_dim=64, d_ffn=256,
                    vocab=300, dtype="fp32", damp=0.3, seed=21, prompt_len=333, decode_len=24)
@@ -130,11 +139,11 @@ def test_long_context_splits_and_shuffled_pages(P):
     want = O.greedy_decode(dec, prompt, w.decode_len + 1, keep_logits=True)
     Wg = to_device(W, "cuda")
     max_seq = 333 + 24 + 2
-    a = _gpu_run(P, w, Wg, prompt, w.decode_len, P.MODE_OVERLAP, max_seq=max_seq, kv_page_tokens=8)
+    a = _gpu_run(P, w, Wg, prompt, w.decode_len, P.MODE_OVERLAP, max_seq=max_seq, kv_page_tokens=8, engine=engine)
     n_pages = (max_seq + 7) // 8
     b = _gpu_run(P, w, Wg, prompt, w.decode_len, P.MODE_OVERLAP, max_seq=max_seq, kv_page_tokens=8,
-                 page_table=S.page_permutation(5, n_pages))
-    c = _gpu_run(P, w, Wg, prompt, w.decode_len, P.MODE_VANILLA, max_seq=1024, kv_page_tokens=64)
+                 page_table=S.page_permutation(5, n_pages), engine=engine)
+    c = _gpu_run(P, w, Wg, prompt, w.decode_len, P.MODE_VANILLA, max_seq=1024, kv_page_tokens=64, engine=engine)
     assert a["tokens"] == want.tokens == b["tokens"] == c["tokens"]
     assert torch.equal(a["logits"], b["logits"])
     ref = torch.stack(want.logits)
@@ -150,15 +159,16 @@ def test_graph_replay_equals_direct_launch_and_decode_is_resumable(P):
     a = _gpu_run(P, w, W, prompt, 48, P.MODE_OVERLAP, use_graph=True)
     b = _gpu_run(P, w, W, prompt, 48, P.MODE_OVERLAP, use_graph=False)
     assert a["tokens"] == b["tokens"] and torch.equal(a["logits"], b["logits"]) and a["stats"]["accepted"] == b["stats"]["accepted"]
-    ss = P.Session(w, W, max_seq=16 + 48 + 2, mode=P.MODE_OVERLAP)
-    t0 = ss.ppsd_prefill(prompt)
-    toks = [t0] + ss.ppsd_decode(1) + ss.ppsd_decode(30) + ss.ppsd_decode(17)
-    assert toks == a["tokens"]
-    st = ss.ppsd_stats()
-    assert st["accepted"] == a["stats"]["accepted"] and st["steps_draft_only"] == a["stats"]["steps_draft_only"]
-    # a second prefill on the same context starts a fresh sequence
-    assert ss.ppsd_prefill(prompt) == t0 and ss.ppsd_decode(5) == a["tokens"][1:6]
-    ss.close()
+    for engine in ENGINES:
+        ss = P.Session(w, W, max_seq=16 + 48 + 2, mode=P.MODE_OVERLAP, engine=engine)
+        t0 = ss.ppsd_prefill(prompt)
+        toks = [t0] + ss.ppsd_decode(1) + ss.ppsd_decode(30) + ss.ppsd_decode(17)
+        assert toks == a["tokens"]
+        st = ss.ppsd_stats()
+        assert st["accepted"] == a["stats"]["accepted"] and st["steps_draft_only"] == a["stats"]["steps_draft_only"]
+        # a second prefill on the same context starts a fresh sequence
+        assert ss.ppsd_prefill(prompt) == t0 and ss.ppsd_decode(5) == a["tokens"][1:6]
+        ss.close()
 
 
 def test_error_paths_leave_the_context_usable(P):
