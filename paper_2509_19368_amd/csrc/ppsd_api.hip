@@ -39,12 +39,8 @@ int fail(int code, const char *fmt, ...) {
 constexpr size_t kAlign = 256;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
-// rows per wave of the row-streaming kernels
-constexpr int kQkvPairs = 2;
-constexpr int kGuPairs = 2;
-constexpr int kProjRows = 4;
-constexpr int kHeadRows = 4;
-constexpr int kConsumerMergeSplits = 8;   // up to this many attention splits are merged by o_proj's prologue
+constexpr int kGemvWgsPerCu = 4;       // workgroups per CU of the weight-streaming kernels (measured best of 1..8)
+constexpr int kSplitPositions = 512;   // attention: one split per this many positions of capacity
 constexpr int kMaxSplits = 32;         // attention splits along the sequence (both engines)
 constexpr int kMaxWorkgroups = 1024;   // persistent engine: one head candidate per workgroup
 
@@ -79,6 +75,8 @@ bool valid_config(const ppsd_config *c, const char **why) {
   REJECT(c->debug_logits < 0, "debug_logits < 0");
   REJECT((size_t)c->d_ffn * 4 > 64 * 1024 || (size_t)c->d_model * 4 > 64 * 1024 ||
          (size_t)c->n_heads * c->head_dim * 4 > 64 * 1024, "activation vector exceeds 64 KiB of LDS");
+  REJECT(c->d_model > 16 * kGBlock, "d_model exceeds the staging capacity (8192)");
+  REJECT(c->d_ffn > 32 * kGBlock || c->n_heads * c->head_dim > 32 * kGBlock, "d_ffn / n_heads*head_dim exceed the staging capacity (16384)");
   REJECT(c->engine != PPSD_ENGINE_STREAMS && c->engine != PPSD_ENGINE_PERSISTENT, "engine must be 0 or 1");
   REJECT(c->engine == PPSD_ENGINE_PERSISTENT && c->time_kernels, "time_kernels needs the per-operation engine");
   for (int k = 0; k < 6; ++k) REJECT(c->reserved[k] != 0, "reserved fields must be zero");
@@ -90,9 +88,9 @@ Layout make_layout(const ppsd_config *c) {
   Layout L{};
   const size_t es = c->dtype == PPSD_FP32 ? 4 : 2;
   L.n_pages = (c->max_seq + c->kv_page_tokens - 1) / c->kv_page_tokens;
-  int ns = (c->max_seq + 127) / 128;
+  int ns = (c->max_seq + kSplitPositions - 1) / kSplitPositions;
   L.n_splits = ns < 1 ? 1 : (ns > kMaxSplits ? kMaxSplits : ns);
-  L.head_blocks = (c->vocab + kHeadRows * kWavesPerBlock - 1) / (kHeadRows * kWavesPerBlock);
+  L.head_blocks = kMaxWorkgroups;   // capacity of the candidate arrays; the live count is set at load
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
   L.state = take(sizeof(DevState));
@@ -111,7 +109,7 @@ Layout make_layout(const ppsd_config *c) {
     L.partials[s] = take(4ull * c->n_heads * kMaxSplits * (c->head_dim + 2));
     L.counters[s] = take(4ull * c->n_kv_heads);
   }
-  const size_t n_cand = L.head_blocks > kMaxWorkgroups ? L.head_blocks : kMaxWorkgroups;
+  const size_t n_cand = kMaxWorkgroups;
   L.cand_lm = take(8ull * n_cand);
   L.cand_exit = take(8ull * n_cand);
   L.layer_ptrs = take(sizeof(LayerPtrs) * (size_t)c->n_layers);
@@ -140,8 +138,16 @@ struct ppsd_ctx {
   hipGraphExec_t g_prefill = nullptr;   // one prompt position, no head
   DevState *h_state = nullptr;          // pinned
   // persistent engine
+  int n_cu = 0;                         // compute units of the device
   int n_wg = 0;
-  int mega_splits = 1;
+  // grid of a weight-streaming kernel with n_tasks row-pair tasks: one wave per task up to a few
+  // workgroups per CU, then the waves loop
+  int gemv_grid(int n_tasks) const {
+    const int want = (n_tasks + kGWaves - 1) / kGWaves;
+    int cap = kGemvWgsPerCu * n_cu;
+    if (cap > kMaxWorkgroups) cap = kMaxWorkgroups;
+    return want < cap ? want : cap;
+  }
   int xs_stride = 0;
   size_t mega_lds = 0;
   int trace_step = -1, trace_wg = 0;
@@ -202,9 +208,8 @@ void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int 
   const int xwork = (role == kVerify) ? kXVerify : kXDraft;
 
   const int total_pairs = (c.n_heads + 2 * c.n_kv_heads) * (c.head_dim / 2);
-  const int qkv_blocks = (total_pairs + kQkvPairs * kWavesPerBlock - 1) / (kQkvPairs * kWavesPerBlock);
   L.before(kKQkv);
-  hipLaunchKernelGGL((k_qkv<WT, kQkvPairs>), dim3(qkv_blocks), dim3(kBlock), (size_t)d * 4, L.s, cm, role, layer,
+  hipLaunchKernelGGL((k_qkv<WT>), dim3(x->gemv_grid(total_pairs)), dim3(kGBlock), (size_t)d * 4, L.s, cm, role, layer,
                      xin_sel, from_embed ? 1 : 0, (const WT *)x->embed, (const float *)x->attn_norm[layer],
                      (const WT *)x->wqkv[layer], q);
   L.after();
@@ -214,31 +219,27 @@ void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int 
   int *cnt = at<int>(x, x->lay.counters[stage]);
   const int G = c.n_heads / c.n_kv_heads;
   L.before(kKAttn);
-  // few splits: the o_proj prologue merges them; many: the last attention workgroup of a head does
-  const int defer = x->lay.n_splits <= kConsumerMergeSplits ? 1 : 0;
-#define ATTN(HD, GG) hipLaunchKernelGGL((k_attn<WT, HD, GG>), agrid, dim3(kBlock), 0, L.s, cm, role, layer, \
-                                        (const float *)q, a, part, cnt, defer)
+#define ATTN(HD, GG) hipLaunchKernelGGL((k_attn<WT, HD, GG>), agrid, dim3(kGBlock), 0, L.s, cm, role, layer, \
+                                        (const float *)q, a, part, cnt)
   if (c.head_dim == 64) { if (G == 1) ATTN(64, 1); else if (G == 2) ATTN(64, 2); else ATTN(64, 4); }
   else { if (G == 1) ATTN(128, 1); else if (G == 2) ATTN(128, 2); else ATTN(128, 4); }
 #undef ATTN
   L.after();
 
-  const int oproj_blocks = (d + kProjRows * kWavesPerBlock - 1) / (kProjRows * kWavesPerBlock);
+  const int proj_grid = x->gemv_grid((d + 1) / 2);
   L.before(kKOproj);
-  hipLaunchKernelGGL((k_proj_resid<WT, kProjRows>), dim3(oproj_blocks), dim3(kBlock), (size_t)nq * 4, L.s, cm, role,
-                     defer ? (const float *)part : (const float *)a, nq, (const WT *)x->wo[layer], d, xin_sel, xwork,
-                     defer ? c.head_dim : 0, x->lay.n_splits);
+  hipLaunchKernelGGL((k_proj_resid<WT>), dim3(proj_grid), dim3(kGBlock), (size_t)nq * 4, L.s, cm, role,
+                     (const float *)a, nq, (const WT *)x->wo[layer], d, xin_sel, xwork);
   L.after();
 
-  const int gu_blocks = (f + kGuPairs * kWavesPerBlock - 1) / (kGuPairs * kWavesPerBlock);
   L.before(kKGateUp);
-  hipLaunchKernelGGL((k_gate_up<WT, kGuPairs>), dim3(gu_blocks), dim3(kBlock), (size_t)d * 4, L.s, cm, role, xwork,
+  hipLaunchKernelGGL((k_gate_up<WT>), dim3(x->gemv_grid(f)), dim3(kGBlock), (size_t)d * 4, L.s, cm, role, xwork,
                      (const float *)x->mlp_norm[layer], (const WT *)x->wgu[layer], mb);
   L.after();
 
   L.before(kKDown);
-  hipLaunchKernelGGL((k_proj_resid<WT, kProjRows>), dim3(oproj_blocks), dim3(kBlock), (size_t)f * 4, L.s, cm, role,
-                     (const float *)mb, f, (const WT *)x->wdown[layer], d, xwork, xout_last_sel, 0, 1);
+  hipLaunchKernelGGL((k_proj_resid<WT>), dim3(proj_grid), dim3(kGBlock), (size_t)f * 4, L.s, cm, role,
+                     (const float *)mb, f, (const WT *)x->wdown[layer], d, xwork, xout_last_sel);
   L.after();
 }
 
@@ -249,7 +250,7 @@ void launch_head(Launcher &L, int role, int xin_sel, bool is_lm) {
   float2 *cand = at<float2>(x, is_lm ? x->lay.cand_lm : x->lay.cand_exit);
   float *logits = c.debug_logits > 0 ? at<float>(x, x->lay.logits) : nullptr;
   L.before(kKHead);
-  hipLaunchKernelGGL((k_head<WT, kHeadRows>), dim3(x->lay.head_blocks), dim3(kBlock), (size_t)c.d_model * 4, L.s,
+  hipLaunchKernelGGL((k_head<WT>), dim3(x->cm.dm.head_blocks), dim3(kGBlock), (size_t)c.d_model * 4, L.s,
                      x->cm, role, xin_sel, (const float *)(is_lm ? x->final_norm : x->exit_norm),
                      (const WT *)(is_lm ? x->lm_head : x->exit_head), cand, logits, is_lm ? 1 : 0);
   L.after();
@@ -375,7 +376,7 @@ MegaArgs mega_args(ppsd_ctx *x, bool prefill, int max_steps) {
   A.logits = c.debug_logits > 0 ? at<float>(x, x->lay.logits) : nullptr;
   A.out_tokens = at<int32_t>(x, x->lay.out_tokens); A.drafts = at<int32_t>(x, x->lay.drafts);
   A.bar = at<unsigned>(x, x->lay.bar); A.abort_flag = at<int>(x, x->lay.abort_flag);
-  A.max_steps = max_steps; A.attn_splits = x->mega_splits; A.xs_stride = x->xs_stride;
+  A.max_steps = max_steps; A.attn_splits = x->lay.n_splits; A.xs_stride = x->xs_stride;
   A.trace = (!prefill && x->trace_step >= 0) ? at<unsigned long long>(x, x->lay.trace) : nullptr;
   A.trace_step = x->trace_step; A.trace_wg = x->trace_wg;
   auto whole = [&](int role, int head) {
@@ -446,12 +447,7 @@ int mega_setup(ppsd_ctx *x) {
   int per_cu = 0;
   HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kMBlock, x->mega_lds));
   if (per_cu < 1) return fail(PPSD_EARG, "persistent kernel does not fit on a CU (LDS %zu bytes)", x->mega_lds);
-  x->n_wg = prop.multiProcessorCount;
-  if (x->n_wg > kMaxWorkgroups) x->n_wg = kMaxWorkgroups;
-  int sp = x->n_wg / (2 * c.n_kv_heads);
-  const int pages = x->lay.n_pages;
-  if (sp > pages) sp = pages;
-  x->mega_splits = sp < 1 ? 1 : (sp > kMaxSplits ? kMaxSplits : sp);
+  x->n_wg = x->n_cu > kMaxWorkgroups ? kMaxWorkgroups : x->n_cu;
   std::vector<LayerPtrs> lp(c.n_layers);
   for (int l = 0; l < c.n_layers; ++l)
     lp[l] = LayerPtrs{(const float *)x->attn_norm[l], x->wqkv[l], x->wo[l], (const float *)x->mlp_norm[l], x->wgu[l], x->wdown[l]};
@@ -542,10 +538,17 @@ int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *b, ppsd_ctx **
   m.d = cfg->d_model; m.n_h = cfg->n_heads; m.n_kv = cfg->n_kv_heads; m.hd = cfg->head_dim; m.f = cfg->d_ffn;
   m.V = cfg->vocab; m.L = cfg->n_layers; m.E = cfg->exit_layer; m.max_seq = cfg->max_seq;
   m.page_tokens = cfg->kv_page_tokens; m.n_pages = lay.n_pages; m.n_splits = lay.n_splits;
-  m.debug_rows = cfg->debug_logits; m.head_blocks = lay.head_blocks;
+  m.debug_rows = cfg->debug_logits; m.head_blocks = 0;   // set below, once the device is known
   m.eps = cfg->rms_eps; m.qscale = (float)(1.0 / std::sqrt((double)cfg->head_dim));
 
   auto cleanup = [&](int rc) { ppsd_free(x); return rc; };
+  {
+    int dev = 0, n_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+      return cleanup(fail(PPSD_EHIP, "cannot query the device's compute-unit count"));
+    x->n_cu = n_cu;
+    m.head_blocks = x->gemv_grid((cfg->vocab + 1) / 2);
+  }
 #define HIP_TRY_X(expr)                                                                                   \
   do {                                                                                                    \
     hipError_t e_ = (expr);                                                                               \

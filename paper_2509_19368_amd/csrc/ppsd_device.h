@@ -11,7 +11,12 @@ typedef uint16_t bf16_t;   // raw bfloat16 bits
 constexpr int kWave = 64;
 constexpr int kBlock = 256;          // threads per workgroup in every kernel
 constexpr int kWavesPerBlock = kBlock / kWave;
-constexpr int kTripBlocks = 4;       // column blocks per trip of the row-streaming kernels
+constexpr int kGBlock = 512;         // threads per workgroup of the weight-streaming kernels
+constexpr int kGWaves = kGBlock / kWave;
+constexpr int kTripRows = 2;         // rows a wave streams at a time (one rotation / gate-up pair)
+constexpr int kTripBlocks = 2;       // column blocks per trip: 4 independent 16-byte loads per lane.
+                                     // Measured on gfx950: many waves with a shallow queue each
+                                     // (2 x 2) stream faster than fewer waves with deep queues.
 constexpr float kNegBig = -1.0e30f;  // finite stand-in for -inf in the running softmax maximum
 
 // Stage roles: which part of the device state a kernel takes its input from.
@@ -245,34 +250,102 @@ __device__ __forceinline__ void trip_consume(const Trip<WT, R, KB> &t, const flo
   }
 }
 
-// acc[r] += W[rows[r], :] . xs, given the first trip already in flight in t.
-template <typename WT, int R, int KB>
-__device__ __forceinline__ void stream_rows(Trip<WT, R, KB> &t, const WT *const (&rows)[R], const float *xs, int C,
-                                            float (&acc)[R]) {
-  const int nblk = col_blocks<WT>(C);
-  for (int cb = 0; cb < nblk; cb += KB) {
-    trip_consume<WT, R, KB>(t, xs, cb, C, acc);
-    if (cb + KB < nblk) trip_load<WT, R, KB>(t, rows, cb + KB, nblk, C);
-  }
+// Sum over a workgroup of BLOCK threads; every thread gets the result.  red: BLOCK/64 floats of LDS.
+template <int BLOCK>
+__device__ __forceinline__ float wg_sum(float v, float *red) {
+  v = wave_sum(v);
+  __syncthreads();   // red may still be read from a previous use
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float s = 0.f;
+#pragma unroll
+  for (int w = 0; w < BLOCK / kWave; ++w) s += red[w];
+  return s;
 }
 
-// RMSNorm prologue (step a2): xs[i] = x[i] / sqrt(mean(x^2) + eps) * gain[i], staged in LDS.
-// x may come from the embedding row (storage dtype) or from a residual slot (fp32).
-// If copy_out != nullptr the un-normalised x is also written there (block 0 only passes it).
-template <typename WT>
-__device__ __forceinline__ void load_and_norm(const float *xf, const WT *xrow, const float *gain,
-                                              int d, float eps, float *xs, float *red, float *copy_out) {
-  float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += kBlock) {
-    float v = xrow ? Pack<WT>::to_float(xrow[i]) : xf[i];
-    xs[i] = v;
-    if (copy_out) copy_out[i] = v;
-    ss = fmaf(v, v, ss);
+// RMSNorm prologue (step a2) of a weight-streaming kernel: xs[i] = x[i] / sqrt(mean(x^2) + eps) * gain[i].
+// x comes from the embedding row (storage dtype) or from a residual slot (fp32).  The loads of x and
+// gain are issued first (the input vector is what the kernel waits for), then issue_weights() puts
+// the first weight trip in flight behind them, then the reduction runs.  d <= 16 * BLOCK.
+// If copy_out != nullptr the un-normalised x is also written there (one workgroup passes it).
+template <typename WT, int BLOCK, typename F>
+__device__ __forceinline__ void stage_norm(const float *xf, const WT *xrow, const float *gain, int d, float eps,
+                                           float *xs, float *red, float *copy_out, F &&issue_weights) {
+  constexpr int kPer = 16;
+  float xv[kPer], gv[kPer];
+#pragma unroll
+  for (int e = 0; e < kPer; ++e) {
+    const int i = threadIdx.x + e * BLOCK;
+    xv[e] = 0.f; gv[e] = 0.f;
+    if (i < d) {
+      xv[e] = xrow ? Pack<WT>::to_float(xrow[i]) : xf[i];
+      gv[e] = gain[i];
+    }
   }
-  ss = block_sum(ss, red);
+  issue_weights();
+  float ss = 0.f;
+#pragma unroll
+  for (int e = 0; e < kPer; ++e) {
+    const int i = threadIdx.x + e * BLOCK;
+    if (i < d) {
+      if (copy_out) copy_out[i] = xv[e];
+      ss = fmaf(xv[e], xv[e], ss);
+    }
+  }
+  ss = wg_sum<BLOCK>(ss, red);
   const float rs = 1.0f / sqrtf(ss / (float)d + eps);
-  for (int i = threadIdx.x; i < d; i += kBlock) xs[i] = xs[i] * rs * gain[i];
+#pragma unroll
+  for (int e = 0; e < kPer; ++e) {
+    const int i = threadIdx.x + e * BLOCK;
+    if (i < d) xs[i] = xv[e] * rs * gv[e];
+  }
   __syncthreads();
+}
+
+// Plain staging of an fp32 vector (attention output, SwiGLU output) into LDS.  C <= 32 * BLOCK.
+template <int BLOCK, typename F>
+__device__ __forceinline__ void stage_copy(const float *vin, int C, float *xs, F &&issue_weights) {
+  constexpr int kPer = 32;
+  float xv[kPer];
+#pragma unroll
+  for (int e = 0; e < kPer; ++e) {
+    const int i = threadIdx.x + e * BLOCK;
+    xv[e] = i < C ? vin[i] : 0.f;
+  }
+  issue_weights();
+#pragma unroll
+  for (int e = 0; e < kPer; ++e) {
+    const int i = threadIdx.x + e * BLOCK;
+    if (i < C) xs[i] = xv[e];
+  }
+  __syncthreads();
+}
+
+// A wave's share of a GEMV: tasks task, task + tw, ... of kTripRows rows each.  set_rows(t) points
+// rows[] at task t; the first trip of `task` is already in flight in trip.  After a task's last
+// trip is consumed the first trip of the wave's next task is issued before the reduction and the
+// epilogue epi(task, sum_row0, sum_row1) run.
+template <typename WT, typename RowsFn, typename EpiFn>
+__device__ __forceinline__ void gemv_tasks(Trip<WT, kTripRows, kTripBlocks> &trip, const WT *(&rows)[kTripRows],
+                                           int task, int n_tasks, int tw, int C, const float *xs,
+                                           RowsFn &&set_rows, EpiFn &&epi) {
+  const int nblk = col_blocks<WT>(C);
+  while (task < n_tasks) {
+    float acc[kTripRows] = {0.f, 0.f};
+    const int next = task + tw;
+    for (int cb = 0; cb < nblk; cb += kTripBlocks) {
+      trip_consume<WT, kTripRows, kTripBlocks>(trip, xs, cb, C, acc);
+      if (cb + kTripBlocks < nblk) {
+        trip_load<WT, kTripRows, kTripBlocks>(trip, rows, cb + kTripBlocks, nblk, C);
+      } else if (next < n_tasks) {
+        set_rows(next);
+        trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, nblk, C);
+      }
+    }
+    const float s0 = wave_sum(acc[0]), s1 = wave_sum(acc[1]);
+    epi(task, s0, s1);
+    task = next;
+  }
 }
 
 }  // namespace ppsd

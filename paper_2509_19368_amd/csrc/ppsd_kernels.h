@@ -1,8 +1,14 @@
 // Decode-step kernels (steps a1..a10 of one PPSD step), gfx950, wave64.
 //
-// Every kernel is launched with kBlock threads and starts by resolving its stage's input
-// from the device state (stage_in); a stage with nothing to do returns at once, so the host
-// can enqueue steps without knowing accept/reject outcomes.
+// Every kernel starts by resolving its stage's input from the device state (stage_in); a stage
+// with nothing to do returns at once, so the host can enqueue steps without knowing accept/reject
+// outcomes.
+//
+// The four weight-streaming kernels (k_qkv, k_proj_resid, k_gate_up, k_head) share one shape:
+// workgroups of kGBlock threads, a few per CU, each staging the input vector ONCE and every wave
+// looping over row-pair tasks with a stride of the whole grid (gemv_tasks).  Staging per small
+// workgroup was measured to cost ~8 us per kernel: a late workgroup's input loads queue behind
+// the weight loads already streaming through its CU.
 #pragma once
 
 #include "ppsd_device.h"
@@ -21,58 +27,41 @@ __device__ __forceinline__ WT *kv_row(const Common &c, int layer, int pos, int k
 
 // ------------------------------------------------------------------------------------------
 // a1-a3: (embedding) + RMSNorm + QKV GEMV + rotary + KV append.
-// One wave computes PAIRS row pairs (i, i + hd/2) of one head, so the rotation partner is local.
-// grid = ceil(qkv_rows / 2 / (PAIRS * 4)).
-template <typename WT, int PAIRS>
-__global__ __launch_bounds__(kBlock) void k_qkv(Common c, int role, int layer, int xin_sel, int from_embed,
-                                                const WT *embed, const float *gain, const WT *wqkv,
-                                                float *qout) {
+// A task is the row pair (i, i + hd/2) of one head, so the rotation partner is local to the wave.
+template <typename WT>
+__global__ __launch_bounds__(kGBlock) void k_qkv(Common c, int role, int layer, int xin_sel, int from_embed,
+                                                 const WT *embed, const float *gain, const WT *wqkv,
+                                                 float *qout) {
   extern __shared__ float xs[];
-  __shared__ float red[kWavesPerBlock];
-  constexpr int R = 2 * PAIRS, KB = kTripBlocks;
+  __shared__ float red[kGWaves];
   const StageIn si = stage_in(c, role);
   if (!si.active) return;
   const Dims &m = c.dm;
   const int d = m.d;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int half = m.hd >> 1;
-  const int total_pairs = (m.n_h + 2 * m.n_kv) * half;
-  const int pair0 = (blockIdx.x * kWavesPerBlock + wave) * PAIRS;
-  const bool has_rows = pair0 < total_pairs;
+  const int n_tasks = (m.n_h + 2 * m.n_kv) * half;
+  const int gw = blockIdx.x * kGWaves + wave, tw = gridDim.x * kGWaves;
 
-  const WT *rows[R];
-  int head[PAIRS], idx[PAIRS];
-#pragma unroll
-  for (int p = 0; p < PAIRS; ++p) {
-    int pr = min(pair0 + p, total_pairs - 1);
-    head[p] = pr / half;
-    idx[p] = pr - head[p] * half;
-    rows[2 * p] = wqkv + (size_t)(head[p] * m.hd + idx[p]) * d;
-    rows[2 * p + 1] = rows[2 * p] + (size_t)half * d;
-  }
-  Trip<WT, R, KB> trip;
-  if (has_rows) trip_load<WT, R, KB>(trip, rows, 0, col_blocks<WT>(d), d);   // in flight during the prologue
+  const WT *rows[kTripRows];
+  auto set_rows = [&](int task) {
+    const int head = task / half, i = task - head * half;
+    rows[0] = wqkv + (size_t)(head * m.hd + i) * d;
+    rows[1] = rows[0] + (size_t)half * d;
+  };
+  Trip<WT, kTripRows, kTripBlocks> trip;
   {
     const WT *xrow = from_embed ? embed + (size_t)si.tok * d : nullptr;
     const float *xf = from_embed ? nullptr : xslot(c, xin_sel);
     float *copy_out = (from_embed && blockIdx.x == 0) ? xslot(c, xin_sel) : nullptr;
-    load_and_norm<WT>(xf, xrow, gain, d, m.eps, xs, red, copy_out);
+    stage_norm<WT, kGBlock>(xf, xrow, gain, d, m.eps, xs, red, copy_out, [&] {
+      if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
+    });
   }
-  if (!has_rows) return;
-  float acc[R];
-#pragma unroll
-  for (int r = 0; r < R; ++r) acc[r] = 0.f;
-  stream_rows<WT, R, KB>(trip, rows, xs, d, acc);
-#pragma unroll
-  for (int r = 0; r < R; ++r) acc[r] = wave_sum(acc[r]);
-
-  if (lane < PAIRS && pair0 + lane < total_pairs) {
-    float lo = 0.f, hi = 0.f;
-    int h = 0, i = 0;
-#pragma unroll
-    for (int p = 0; p < PAIRS; ++p)
-      if (lane == p) { lo = acc[2 * p]; hi = acc[2 * p + 1]; h = head[p]; i = idx[p]; }
-    if (h < m.n_h + m.n_kv) {   // q or k head: rotate pair by the position angle
+  gemv_tasks<WT>(trip, rows, gw, n_tasks, tw, d, xs, set_rows, [&](int task, float lo, float hi) {
+    if (lane != 0) return;
+    const int h = task / half, i = task - h * half;
+    if (h < m.n_h + m.n_kv) {   // q or k head: rotate the pair by the position angle
       const float cs = c.rope_cos[(size_t)si.pos * half + i];
       const float sn = c.rope_sin[(size_t)si.pos * half + i];
       const float rlo = lo * cs - hi * sn;
@@ -89,7 +78,7 @@ __global__ __launch_bounds__(kBlock) void k_qkv(Common c, int role, int layer, i
       dst[i] = Pack<WT>::from_float(lo);
       dst[i + half] = Pack<WT>::from_float(hi);
     }
-  }
+  });
 }
 
 // ------------------------------------------------------------------------------------------
@@ -103,7 +92,7 @@ __global__ __launch_bounds__(kBlock) void k_qkv(Common c, int role, int layer, i
 template <typename WT, int HD, int G, int BLOCK>
 __device__ __forceinline__ void attn_unit(const Common &c, int layer, int pos, int kvh, int split, int n_splits,
                                           const float *q, float *aout, float *partials, int *counters,
-                                          float *merge, int *s_last, bool defer_merge) {
+                                          float *merge, int *s_last) {
   constexpr int N = Pack<WT>::N;
   constexpr int GS = HD / N;               // lanes per position
   constexpr int GPB = BLOCK / GS;          // position groups per workgroup
@@ -192,7 +181,7 @@ __device__ __forceinline__ void attn_unit(const Common &c, int layer, int pos, i
       A = fmaf(rec[2 + dim], w, A);
     }
     const int head = kvh * G + g;
-    if (n_splits == 1 && !defer_merge) {
+    if (n_splits == 1) {
       aout[head * HD + dim] = A / L;
     } else {
       float *pr = partials + ((size_t)head * n_splits + split) * REC;
@@ -200,7 +189,7 @@ __device__ __forceinline__ void attn_unit(const Common &c, int layer, int pos, i
       pr[2 + dim] = A;
     }
   }
-  if (n_splits > 1 && !defer_merge) {
+  if (n_splits > 1) {
     // last workgroup of this KV head merges the splits
     __threadfence();
     __syncthreads();
@@ -233,171 +222,121 @@ __device__ __forceinline__ void attn_unit(const Common &c, int layer, int pos, i
 
 // grid = (n_kv, n_splits)
 template <typename WT, int HD, int G>
-__global__ __launch_bounds__(kBlock) void k_attn(Common c, int role, int layer, const float *q, float *aout,
-                                                 float *partials, int *counters, int defer_merge) {
-  constexpr int GPB = kBlock / (HD / Pack<WT>::N);
+__global__ __launch_bounds__(kGBlock) void k_attn(Common c, int role, int layer, const float *q, float *aout,
+                                                  float *partials, int *counters) {
+  constexpr int GPB = kGBlock / (HD / Pack<WT>::N);
   __shared__ float merge[GPB * G * (HD + 2)];
   __shared__ int s_last;
   const StageIn si = stage_in(c, role);
   if (!si.active) return;
-  attn_unit<WT, HD, G, kBlock>(c, layer, si.pos, blockIdx.x, blockIdx.y, gridDim.y, q, aout, partials, counters,
-                               merge, &s_last, defer_merge != 0);
+  attn_unit<WT, HD, G, kGBlock>(c, layer, si.pos, blockIdx.x, blockIdx.y, gridDim.y, q, aout, partials, counters,
+                                merge, &s_last);
 }
 
 // ------------------------------------------------------------------------------------------
-// Merges the attention splits of one element (head, dim) from the per-split records
-// [head][split][m, l, acc[hd]] in split order: a = sum_s acc_s e^(m_s - M) / sum_s l_s e^(m_s - M).
-__device__ __forceinline__ float merge_splits(const float *partials, int head, int dim, int hd, int n_splits) {
-  const int rec = hd + 2;
-  const float *pr = partials + (size_t)head * n_splits * rec;
-  float M = kNegBig;
-  for (int s = 0; s < n_splits; ++s) M = fmaxf(M, pr[s * rec]);
-  float L = 0.f, A = 0.f;
-  for (int s = 0; s < n_splits; ++s) {
-    const float w = __expf(pr[s * rec] - M);
-    L = fmaf(pr[s * rec + 1], w, L);
-    A = fmaf(pr[s * rec + 2 + dim], w, A);
-  }
-  return A / L;
-}
-
 // a5 / a7: out[r] = resid[r] + W[r,:] . vin   (o_proj and down_proj with the residual add fused).
-// With merge_hd > 0 the input is the attention output still in per-split form and is merged while
-// it is staged (merge_hd = head_dim, n_splits records per head).
-// grid = ceil(rows / (R * 4)); dynamic LDS = C floats.
-template <typename WT, int R>
-__global__ __launch_bounds__(kBlock) void k_proj_resid(Common c, int role, const float *vin, int C,
-                                                       const WT *W, int rows, int resid_sel, int out_sel,
-                                                       int merge_hd, int n_splits) {
+// A task is two consecutive rows.  Dynamic LDS = C floats.
+template <typename WT>
+__global__ __launch_bounds__(kGBlock) void k_proj_resid(Common c, int role, const float *vin, int C,
+                                                        const WT *W, int n_rows, int resid_sel, int out_sel) {
   extern __shared__ float xs[];
-  constexpr int KB = kTripBlocks;
   const StageIn si = stage_in(c, role);
   if (!si.active) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int r0 = (blockIdx.x * kWavesPerBlock + wave) * R;
-  const bool has_rows = r0 < rows;
-  const WT *rp[R];
-#pragma unroll
-  for (int r = 0; r < R; ++r) rp[r] = W + (size_t)min(r0 + r, rows - 1) * C;
-  Trip<WT, R, KB> trip;
-  if (has_rows) trip_load<WT, R, KB>(trip, rp, 0, col_blocks<WT>(C), C);
-  if (merge_hd > 0) {
-    for (int i = threadIdx.x; i < C; i += kBlock) xs[i] = merge_splits(vin, i / merge_hd, i % merge_hd, merge_hd, n_splits);
-  } else {
-    for (int i = threadIdx.x; i < C; i += kBlock) xs[i] = vin[i];
-  }
-  __syncthreads();
-  if (!has_rows) return;
-  float acc[R];
-#pragma unroll
-  for (int r = 0; r < R; ++r) acc[r] = 0.f;
-  stream_rows<WT, R, KB>(trip, rp, xs, C, acc);
-#pragma unroll
-  for (int r = 0; r < R; ++r) acc[r] = wave_sum(acc[r]);
-  if (lane < R && r0 + lane < rows) {
-    float y = 0.f;
-#pragma unroll
-    for (int r = 0; r < R; ++r) if (lane == r) y = acc[r];
-    const float *resid = xslot(c, resid_sel);
-    float *out = xslot(c, out_sel);
-    out[r0 + lane] = resid[r0 + lane] + y;
-  }
+  const int n_tasks = (n_rows + 1) >> 1;
+  const int gw = blockIdx.x * kGWaves + wave, tw = gridDim.x * kGWaves;
+  const WT *rows[kTripRows];
+  auto set_rows = [&](int task) {
+    rows[0] = W + (size_t)(2 * task) * C;
+    rows[1] = W + (size_t)min(2 * task + 1, n_rows - 1) * C;
+  };
+  Trip<WT, kTripRows, kTripBlocks> trip;
+  stage_copy<kGBlock>(vin, C, xs, [&] {
+    if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(C), C); }
+  });
+  const float *resid = xslot(c, resid_sel);
+  float *out = xslot(c, out_sel);
+  gemv_tasks<WT>(trip, rows, gw, n_tasks, tw, C, xs, set_rows, [&](int task, float s0, float s1) {
+    const int r = 2 * task + lane;
+    if (lane < 2 && r < n_rows) out[r] = resid[r] + (lane == 0 ? s0 : s1);
+  });
 }
 
 // ------------------------------------------------------------------------------------------
 // a2 + a6: RMSNorm + gate/up GEMV + SwiGLU: mout[i] = silu(Wg[i,:].xn) * (Wu[i,:].xn).
-// One wave computes PAIRS (gate_i, up_i) row pairs.  grid = ceil(f / (PAIRS * 4)).
-template <typename WT, int PAIRS>
-__global__ __launch_bounds__(kBlock) void k_gate_up(Common c, int role, int xin_sel, const float *gain,
-                                                    const WT *wgu, float *mout) {
+// A task is the pair (gate row i, up row i).
+template <typename WT>
+__global__ __launch_bounds__(kGBlock) void k_gate_up(Common c, int role, int xin_sel, const float *gain,
+                                                     const WT *wgu, float *mout) {
   extern __shared__ float xs[];
-  __shared__ float red[kWavesPerBlock];
-  constexpr int R = 2 * PAIRS, KB = kTripBlocks;
+  __shared__ float red[kGWaves];
   const StageIn si = stage_in(c, role);
   if (!si.active) return;
   const Dims &m = c.dm;
   const int d = m.d, f = m.f;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int i0 = (blockIdx.x * kWavesPerBlock + wave) * PAIRS;
-  const bool has_rows = i0 < f;
-  const WT *rows[R];
-#pragma unroll
-  for (int p = 0; p < PAIRS; ++p) {
-    const int i = min(i0 + p, f - 1);
-    rows[2 * p] = wgu + (size_t)i * d;
-    rows[2 * p + 1] = wgu + (size_t)(f + i) * d;
-  }
-  Trip<WT, R, KB> trip;
-  if (has_rows) trip_load<WT, R, KB>(trip, rows, 0, col_blocks<WT>(d), d);
-  load_and_norm<WT>(xslot(c, xin_sel), nullptr, gain, d, m.eps, xs, red, nullptr);
-  if (!has_rows) return;
-  float acc[R];
-#pragma unroll
-  for (int r = 0; r < R; ++r) acc[r] = 0.f;
-  stream_rows<WT, R, KB>(trip, rows, xs, d, acc);
-#pragma unroll
-  for (int r = 0; r < R; ++r) acc[r] = wave_sum(acc[r]);
-  if (lane < PAIRS && i0 + lane < f) {
-    float g = 0.f, u = 0.f;
-#pragma unroll
-    for (int p = 0; p < PAIRS; ++p) if (lane == p) { g = acc[2 * p]; u = acc[2 * p + 1]; }
-    mout[i0 + lane] = g / (1.0f + __expf(-g)) * u;
-  }
+  const int gw = blockIdx.x * kGWaves + wave, tw = gridDim.x * kGWaves;
+  const WT *rows[kTripRows];
+  auto set_rows = [&](int task) {
+    rows[0] = wgu + (size_t)task * d;
+    rows[1] = wgu + (size_t)(f + task) * d;
+  };
+  Trip<WT, kTripRows, kTripBlocks> trip;
+  stage_norm<WT, kGBlock>(xslot(c, xin_sel), (const WT *)nullptr, gain, d, m.eps, xs, red, nullptr, [&] {
+    if (gw < f) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
+  });
+  gemv_tasks<WT>(trip, rows, gw, f, tw, d, xs, set_rows, [&](int task, float g, float u) {
+    if (lane == 0) mout[task] = g / (1.0f + __expf(-g)) * u;
+  });
 }
 
 // ------------------------------------------------------------------------------------------
 // a8 / a9: head = RMSNorm + vocab projection + argmax (exit head and LM head share this kernel).
-// Each workgroup reduces its rows to one (value, index) candidate; the commit kernel finishes the
-// reduction.  logits_row != nullptr additionally stores the logits (parity harness).
-// grid = ceil(V / (R * 4)) = dm.head_blocks.
-template <typename WT, int R>
-__global__ __launch_bounds__(kBlock) void k_head(Common c, int role, int xin_sel, const float *gain,
-                                                 const WT *W, float2 *cand, float *logits_log, int is_lm) {
+// A task is two consecutive vocabulary rows.  Each workgroup reduces its rows to one
+// (value, index) candidate in cand[blockIdx.x]; the commit kernel finishes the reduction over
+// gridDim.x candidates.  logits_log != nullptr additionally stores the logits (parity harness).
+template <typename WT>
+__global__ __launch_bounds__(kGBlock) void k_head(Common c, int role, int xin_sel, const float *gain,
+                                                  const WT *W, float2 *cand, float *logits_log, int is_lm) {
   extern __shared__ float xs[];
-  __shared__ float red[kWavesPerBlock];
-  __shared__ float bv[kWavesPerBlock];
-  __shared__ int bi[kWavesPerBlock];
-  constexpr int KB = kTripBlocks;
+  __shared__ float red[kGWaves];
+  __shared__ float bv[kGWaves];
+  __shared__ int bi[kGWaves];
   const StageIn si = stage_in(c, role);
   if (!si.active) return;
   const Dims &m = c.dm;
   const int d = m.d, V = m.V;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int r0 = (blockIdx.x * kWavesPerBlock + wave) * R;
-  const WT *rp[R];
-#pragma unroll
-  for (int r = 0; r < R; ++r) rp[r] = W + (size_t)min(r0 + r, V - 1) * d;
-  Trip<WT, R, KB> trip;
-  if (r0 < V) trip_load<WT, R, KB>(trip, rp, 0, col_blocks<WT>(d), d);
-  load_and_norm<WT>(xslot(c, xin_sel), nullptr, gain, d, m.eps, xs, red, nullptr);
+  const int n_tasks = (V + 1) >> 1;
+  const int gw = blockIdx.x * kGWaves + wave, tw = gridDim.x * kGWaves;
+  const WT *rows[kTripRows];
+  auto set_rows = [&](int task) {
+    rows[0] = W + (size_t)(2 * task) * d;
+    rows[1] = W + (size_t)min(2 * task + 1, V - 1) * d;
+  };
+  Trip<WT, kTripRows, kTripBlocks> trip;
+  stage_norm<WT, kGBlock>(xslot(c, xin_sel), (const WT *)nullptr, gain, d, m.eps, xs, red, nullptr, [&] {
+    if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
+  });
+  // logits row for the parity harness: row index = number of tokens committed so far
+  float *lrow = nullptr;
+  if (logits_log && is_lm) {
+    const int row = (role == kPrefill) ? 0 : c.st->gen_count;
+    if (row < m.debug_rows) lrow = logits_log + (size_t)row * V;
+  }
   float best = -INFINITY;
   int besti = 0x7fffffff;
-  if (r0 < V) {
-    float acc[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) acc[r] = 0.f;
-    stream_rows<WT, R, KB>(trip, rp, xs, d, acc);
-#pragma unroll
-    for (int r = 0; r < R; ++r) acc[r] = wave_sum(acc[r]);
-    // logits row for the parity harness: row index = number of tokens committed so far
-    float *lrow = nullptr;
-    if (logits_log && is_lm) {
-      const int row = (role == kPrefill) ? 0 : c.st->gen_count;
-      if (row < m.debug_rows) lrow = logits_log + (size_t)row * V;
-    }
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      if (r0 + r < V) {
-        if (better(acc[r], r0 + r, best, besti)) { best = acc[r]; besti = r0 + r; }
-        if (lrow && lane == 0) lrow[r0 + r] = acc[r];
-      }
-    }
-  }
+  gemv_tasks<WT>(trip, rows, gw, n_tasks, tw, d, xs, set_rows, [&](int task, float s0, float s1) {
+    const int r = 2 * task;
+    if (better(s0, r, best, besti)) { best = s0; besti = r; }
+    if (r + 1 < V && better(s1, r + 1, best, besti)) { best = s1; besti = r + 1; }
+    if (lrow && lane == 0) { lrow[r] = s0; if (r + 1 < V) lrow[r + 1] = s1; }
+  });
   if (lane == 0) { bv[wave] = best; bi[wave] = besti; }
   __syncthreads();
   if (threadIdx.x == 0) {
 #pragma unroll
-    for (int w = 1; w < kWavesPerBlock; ++w)
+    for (int w = 1; w < kGWaves; ++w)
       if (better(bv[w], bi[w], best, besti)) { best = bv[w]; besti = bi[w]; }
     cand[blockIdx.x] = make_float2(best, __int_as_float(besti));
   }

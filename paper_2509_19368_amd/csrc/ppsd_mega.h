@@ -481,7 +481,7 @@ __global__ __launch_bounds__(kMBlock) void k_mega(MegaArgs A) {
       for (int u = first; u < per; u += nwg) {
         const int kvh = u / A.attn_splits, split = u - kvh * A.attn_splits;
         attn_unit<WT, HD, G, kMBlock>(c, g.layer, run.pos, kvh, split, A.attn_splits, A.q[s.slot], A.a[s.slot],
-                                      A.partials[s.slot], A.counters[s.slot], lds, &s_last, false);
+                                      A.partials[s.slot], A.counters[s.slot], lds, &s_last);
       }
     };
 

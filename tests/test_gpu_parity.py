@@ -73,6 +73,17 @@ def test_c1_all_modes_reproduce_the_oracle_stream(P, engine):
     assert all(d == -1 for d in runs[P.MODE_VANILLA]["drafts"])
 
 
+def test_both_engines_give_bitwise_equal_logits(P):
+    """Per-operation kernels and the persistent kernel share the arithmetic order of every reduction."""
+    for w in (S.WORKLOADS["C1"], SMALL[1]):
+        W = to_device(S.make_weights(w), "cuda")
+        prompt = S.make_prompt(w)
+        a = _gpu_run(P, w, W, prompt, 24, P.MODE_OVERLAP, engine=0)
+        b = _gpu_run(P, w, W, prompt, 24, P.MODE_OVERLAP, engine=1)
+        assert a["tokens"] == b["tokens"] and a["drafts"] == b["drafts"]
+        assert torch.equal(a["logits"], b["logits"])
+
+
 def test_drafts_equal_the_exit_heads_greedy_token(P):
     """Every compared draft is the exit head's argmax on the true prefix (oracle, fp64)."""
     w = S.WORKLOADS["C1"]
