@@ -39,7 +39,9 @@ int fail(int code, const char *fmt, ...) {
 constexpr size_t kAlign = 256;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
-constexpr int kGemvWgsPerCu = 4;       // workgroups per CU of the weight-streaming kernels (measured best of 1..8)
+// workgroups per CU of the weight-streaming kernels (measured best of 1..8 on the 7B shapes)
+constexpr int kGemvWgsPerCu = 4;
+constexpr int kGateUpWgsPerCu = 2;
 constexpr int kSplitPositions = 512;   // attention: one split per this many positions of capacity
 constexpr int kMaxSplits = 32;         // attention splits along the sequence (both engines)
 constexpr int kMaxWorkgroups = 1024;   // persistent engine: one head candidate per workgroup
@@ -142,9 +144,9 @@ struct ppsd_ctx {
   int n_wg = 0;
   // grid of a weight-streaming kernel with n_tasks row-pair tasks: one wave per task up to a few
   // workgroups per CU, then the waves loop
-  int gemv_grid(int n_tasks) const {
+  int gemv_grid(int n_tasks, int wgs_per_cu = kGemvWgsPerCu) const {
     const int want = (n_tasks + kGWaves - 1) / kGWaves;
-    int cap = kGemvWgsPerCu * n_cu;
+    int cap = wgs_per_cu * n_cu;
     if (cap > kMaxWorkgroups) cap = kMaxWorkgroups;
     return want < cap ? want : cap;
   }
@@ -233,7 +235,7 @@ void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int 
   L.after();
 
   L.before(kKGateUp);
-  hipLaunchKernelGGL((k_gate_up<WT>), dim3(x->gemv_grid(f)), dim3(kGBlock), (size_t)d * 4, L.s, cm, role, xwork,
+  hipLaunchKernelGGL((k_gate_up<WT>), dim3(x->gemv_grid(f, kGateUpWgsPerCu)), dim3(kGBlock), (size_t)d * 4, L.s, cm, role, xwork,
                      (const float *)x->mlp_norm[layer], (const WT *)x->wgu[layer], mb);
   L.after();
 

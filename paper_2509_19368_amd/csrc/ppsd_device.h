@@ -263,63 +263,74 @@ __device__ __forceinline__ float wg_sum(float v, float *red) {
   return s;
 }
 
-// RMSNorm prologue (step a2) of a weight-streaming kernel: xs[i] = x[i] / sqrt(mean(x^2) + eps) * gain[i].
-// x comes from the embedding row (storage dtype) or from a residual slot (fp32).  The loads of x and
-// gain are issued first (the input vector is what the kernel waits for), then issue_weights() puts
-// the first weight trip in flight behind them, then the reduction runs.  d <= 16 * BLOCK.
-// If copy_out != nullptr the un-normalised x is also written there (one workgroup passes it).
-template <typename WT, int BLOCK, typename F>
-__device__ __forceinline__ void stage_norm(const float *xf, const WT *xrow, const float *gain, int d, float eps,
-                                           float *xs, float *red, float *copy_out, F &&issue_weights) {
-  constexpr int kPer = 16;
-  float xv[kPer], gv[kPer];
-#pragma unroll
-  for (int e = 0; e < kPer; ++e) {
-    const int i = threadIdx.x + e * BLOCK;
-    xv[e] = 0.f; gv[e] = 0.f;
-    if (i < d) {
-      xv[e] = xrow ? Pack<WT>::to_float(xrow[i]) : xf[i];
-      gv[e] = gain[i];
-    }
-  }
-  issue_weights();
-  float ss = 0.f;
-#pragma unroll
-  for (int e = 0; e < kPer; ++e) {
-    const int i = threadIdx.x + e * BLOCK;
-    if (i < d) {
-      if (copy_out) copy_out[i] = xv[e];
-      ss = fmaf(xv[e], xv[e], ss);
-    }
-  }
-  ss = wg_sum<BLOCK>(ss, red);
-  const float rs = 1.0f / sqrtf(ss / (float)d + eps);
-#pragma unroll
-  for (int e = 0; e < kPer; ++e) {
-    const int i = threadIdx.x + e * BLOCK;
-    if (i < d) xs[i] = xv[e] * rs * gv[e];
-  }
-  __syncthreads();
-}
+// Input staging of a weight-streaming kernel, split in two so that the loads of the input vector
+// can be in flight while the device state is still being read: *_issue puts the vector (and the
+// norm gain) into registers, *_finish reduces and writes LDS.  A residual slot that does not depend
+// on the state (the stage's working slot) is loaded before stage_in() resolves; the embedding row
+// and the hExit buffers are loaded after it.
+constexpr int kNormPer = 16;   // d <= kNormPer * BLOCK
+constexpr int kCopyPer = 32;   // C <= kCopyPer * BLOCK
 
-// Plain staging of an fp32 vector (attention output, SwiGLU output) into LDS.  C <= 32 * BLOCK.
-template <int BLOCK, typename F>
-__device__ __forceinline__ void stage_copy(const float *vin, int C, float *xs, F &&issue_weights) {
-  constexpr int kPer = 32;
-  float xv[kPer];
+template <typename WT, int BLOCK>
+struct NormStage {
+  float xv[kNormPer], gv[kNormPer];
+  // xrow (storage dtype) or xf (fp32): exactly one is non-null
+  __device__ __forceinline__ void issue(const float *xf, const WT *xrow, const float *gain, int d) {
 #pragma unroll
-  for (int e = 0; e < kPer; ++e) {
-    const int i = threadIdx.x + e * BLOCK;
-    xv[e] = i < C ? vin[i] : 0.f;
+    for (int e = 0; e < kNormPer; ++e) {
+      const int i = threadIdx.x + e * BLOCK;
+      xv[e] = 0.f; gv[e] = 0.f;
+      if (i < d) {
+        xv[e] = xrow ? Pack<WT>::to_float(xrow[i]) : xf[i];
+        gv[e] = gain[i];
+      }
+    }
   }
-  issue_weights();
+  // RMSNorm (step a2): xs[i] = x[i] / sqrt(mean(x^2) + eps) * gain[i].  If copy_out != nullptr the
+  // un-normalised x is also written there (one workgroup passes it).
+  __device__ __forceinline__ void finish(int d, float eps, float *xs, float *red, float *copy_out) {
+    float ss = 0.f;
 #pragma unroll
-  for (int e = 0; e < kPer; ++e) {
-    const int i = threadIdx.x + e * BLOCK;
-    if (i < C) xs[i] = xv[e];
+    for (int e = 0; e < kNormPer; ++e) {
+      const int i = threadIdx.x + e * BLOCK;
+      if (i < d) {
+        if (copy_out) copy_out[i] = xv[e];
+        ss = fmaf(xv[e], xv[e], ss);
+      }
+    }
+    ss = wg_sum<BLOCK>(ss, red);
+    const float rs = 1.0f / sqrtf(ss / (float)d + eps);
+#pragma unroll
+    for (int e = 0; e < kNormPer; ++e) {
+      const int i = threadIdx.x + e * BLOCK;
+      if (i < d) xs[i] = xv[e] * rs * gv[e];
+    }
+    __syncthreads();
   }
-  __syncthreads();
-}
+};
+
+template <int BLOCK>
+struct CopyStage {
+  float xv[kCopyPer];
+  __device__ __forceinline__ void issue(const float *vin, int C) {
+#pragma unroll
+    for (int e = 0; e < kCopyPer; ++e) {
+      const int i = threadIdx.x + e * BLOCK;
+      xv[e] = i < C ? vin[i] : 0.f;
+    }
+  }
+  __device__ __forceinline__ void finish(int C, float *xs) {
+#pragma unroll
+    for (int e = 0; e < kCopyPer; ++e) {
+      const int i = threadIdx.x + e * BLOCK;
+      if (i < C) xs[i] = xv[e];
+    }
+    __syncthreads();
+  }
+};
+
+// A residual selector whose address does not depend on the device state.
+__device__ __forceinline__ bool static_slot(int sel) { return sel == kXDraft || sel == kXVerify; }
 
 // A wave's share of a GEMV: tasks task, task + tw, ... of kTripRows rows each.  set_rows(t) points
 // rows[] at task t; the first trip of `task` is already in flight in trip.  After a task's last

@@ -16,10 +16,11 @@
 namespace ppsd {
 
 // KV pool addressing: [layer][physical page][kv head][K=0 / V=1][slot][hd]
+// ptab: the page table, in global memory or a copy in LDS.
 template <typename WT>
-__device__ __forceinline__ WT *kv_row(const Common &c, int layer, int pos, int kvh, int which) {
+__device__ __forceinline__ WT *kv_row(const Common &c, const int32_t *ptab, int layer, int pos, int kvh, int which) {
   const Dims &m = c.dm;
-  const int page = c.page_table[pos / m.page_tokens];
+  const int page = ptab[pos / m.page_tokens];
   const int slot = pos % m.page_tokens;
   size_t idx = ((((size_t)layer * m.n_pages + page) * m.n_kv + kvh) * 2 + which) * m.page_tokens + slot;
   return (WT *)c.kv_pool + idx * m.hd;
@@ -34,10 +35,13 @@ __global__ __launch_bounds__(kGBlock) void k_qkv(Common c, int role, int layer, 
                                                  float *qout) {
   extern __shared__ float xs[];
   __shared__ float red[kGWaves];
-  const StageIn si = stage_in(c, role);
-  if (!si.active) return;
   const Dims &m = c.dm;
   const int d = m.d;
+  NormStage<WT, kGBlock> in;
+  const bool early = !from_embed && static_slot(xin_sel);
+  if (early) in.issue(c.xbuf + (size_t)xin_sel * d, (const WT *)nullptr, gain, d);   // under the state read
+  const StageIn si = stage_in(c, role);
+  if (!si.active) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int half = m.hd >> 1;
   const int n_tasks = (m.n_h + 2 * m.n_kv) * half;
@@ -50,14 +54,12 @@ __global__ __launch_bounds__(kGBlock) void k_qkv(Common c, int role, int layer, 
     rows[1] = rows[0] + (size_t)half * d;
   };
   Trip<WT, kTripRows, kTripBlocks> trip;
-  {
+  if (!early) {
     const WT *xrow = from_embed ? embed + (size_t)si.tok * d : nullptr;
-    const float *xf = from_embed ? nullptr : xslot(c, xin_sel);
-    float *copy_out = (from_embed && blockIdx.x == 0) ? xslot(c, xin_sel) : nullptr;
-    stage_norm<WT, kGBlock>(xf, xrow, gain, d, m.eps, xs, red, copy_out, [&] {
-      if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
-    });
+    in.issue(from_embed ? nullptr : xslot(c, xin_sel), xrow, gain, d);
   }
+  if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
+  in.finish(d, m.eps, xs, red, (from_embed && blockIdx.x == 0) ? xslot(c, xin_sel) : nullptr);
   gemv_tasks<WT>(trip, rows, gw, n_tasks, tw, d, xs, set_rows, [&](int task, float lo, float hi) {
     if (lane != 0) return;
     const int h = task / half, i = task - h * half;
@@ -74,7 +76,7 @@ __global__ __launch_bounds__(kGBlock) void k_qkv(Common c, int role, int layer, 
     } else {
       const int which = (h < m.n_h + m.n_kv) ? 0 : 1;
       const int kvh = which ? h - m.n_h - m.n_kv : h - m.n_h;
-      WT *dst = kv_row<WT>(c, layer, si.pos, kvh, which);
+      WT *dst = kv_row<WT>(c, c.page_table, layer, si.pos, kvh, which);
       dst[i] = Pack<WT>::from_float(lo);
       dst[i + half] = Pack<WT>::from_float(hi);
     }
@@ -90,9 +92,9 @@ __global__ __launch_bounds__(kGBlock) void k_qkv(Common c, int role, int layer, 
 // several splits the last workgroup to finish a KV head merges the splits, also in fixed order.
 // Must be called by all BLOCK threads of the workgroup; ends with the workgroup synchronised.
 template <typename WT, int HD, int G, int BLOCK>
-__device__ __forceinline__ void attn_unit(const Common &c, int layer, int pos, int kvh, int split, int n_splits,
-                                          const float *q, float *aout, float *partials, int *counters,
-                                          float *merge, int *s_last) {
+__device__ __forceinline__ void attn_unit(const Common &c, const int32_t *ptab, int layer, int pos, int kvh,
+                                          int split, int n_splits, const float *q, float *aout, float *partials,
+                                          int *counters, float *merge, int *s_last) {
   constexpr int N = Pack<WT>::N;
   constexpr int GS = HD / N;               // lanes per position
   constexpr int GPB = BLOCK / GS;          // position groups per workgroup
@@ -131,7 +133,7 @@ __device__ __forceinline__ void attn_unit(const Common &c, int layer, int pos, i
       const int p = p0 + u * GPB;
       ok[u] = p < end;
       const int pc = ok[u] ? p : p0;
-      const WT *kr = kv_row<WT>(c, layer, pc, kvh, 0) + j * N;
+      const WT *kr = kv_row<WT>(c, ptab, layer, pc, kvh, 0) + j * N;
       ku[u] = *(const uint4 *)kr;
       vu[u] = *(const uint4 *)(kr + (size_t)m.page_tokens * HD);
     }
@@ -220,6 +222,8 @@ __device__ __forceinline__ void attn_unit(const Common &c, int layer, int pos, i
   __syncthreads();   // merge / s_last may be reused by the caller
 }
 
+constexpr int kAttnLdsPages = 2048;   // page-table entries the attention kernel keeps in LDS
+
 // grid = (n_kv, n_splits)
 template <typename WT, int HD, int G>
 __global__ __launch_bounds__(kGBlock) void k_attn(Common c, int role, int layer, const float *q, float *aout,
@@ -227,10 +231,16 @@ __global__ __launch_bounds__(kGBlock) void k_attn(Common c, int role, int layer,
   constexpr int GPB = kGBlock / (HD / Pack<WT>::N);
   __shared__ float merge[GPB * G * (HD + 2)];
   __shared__ int s_last;
+  __shared__ int32_t s_ptab[kAttnLdsPages];
+  // the page table does not depend on the state: copy it to LDS while the state is being read
+  const bool lds_pt = c.dm.n_pages <= kAttnLdsPages;
+  if (lds_pt)
+    for (int i = threadIdx.x; i < c.dm.n_pages; i += kGBlock) s_ptab[i] = c.page_table[i];
   const StageIn si = stage_in(c, role);
   if (!si.active) return;
-  attn_unit<WT, HD, G, kGBlock>(c, layer, si.pos, blockIdx.x, blockIdx.y, gridDim.y, q, aout, partials, counters,
-                                merge, &s_last);
+  __syncthreads();
+  attn_unit<WT, HD, G, kGBlock>(c, lds_pt ? s_ptab : c.page_table, layer, si.pos, blockIdx.x, blockIdx.y, gridDim.y,
+                                q, aout, partials, counters, merge, &s_last);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -240,6 +250,8 @@ template <typename WT>
 __global__ __launch_bounds__(kGBlock) void k_proj_resid(Common c, int role, const float *vin, int C,
                                                         const WT *W, int n_rows, int resid_sel, int out_sel) {
   extern __shared__ float xs[];
+  CopyStage<kGBlock> in;
+  in.issue(vin, C);                       // the input buffer's address never depends on the state
   const StageIn si = stage_in(c, role);
   if (!si.active) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -251,9 +263,8 @@ __global__ __launch_bounds__(kGBlock) void k_proj_resid(Common c, int role, cons
     rows[1] = W + (size_t)min(2 * task + 1, n_rows - 1) * C;
   };
   Trip<WT, kTripRows, kTripBlocks> trip;
-  stage_copy<kGBlock>(vin, C, xs, [&] {
-    if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(C), C); }
-  });
+  if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(C), C); }
+  in.finish(C, xs);
   const float *resid = xslot(c, resid_sel);
   float *out = xslot(c, out_sel);
   gemv_tasks<WT>(trip, rows, gw, n_tasks, tw, C, xs, set_rows, [&](int task, float s0, float s1) {
@@ -270,10 +281,13 @@ __global__ __launch_bounds__(kGBlock) void k_gate_up(Common c, int role, int xin
                                                      const WT *wgu, float *mout) {
   extern __shared__ float xs[];
   __shared__ float red[kGWaves];
-  const StageIn si = stage_in(c, role);
-  if (!si.active) return;
   const Dims &m = c.dm;
   const int d = m.d, f = m.f;
+  NormStage<WT, kGBlock> in;
+  const bool early = static_slot(xin_sel);
+  if (early) in.issue(c.xbuf + (size_t)xin_sel * d, (const WT *)nullptr, gain, d);
+  const StageIn si = stage_in(c, role);
+  if (!si.active) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int gw = blockIdx.x * kGWaves + wave, tw = gridDim.x * kGWaves;
   const WT *rows[kTripRows];
@@ -282,9 +296,9 @@ __global__ __launch_bounds__(kGBlock) void k_gate_up(Common c, int role, int xin
     rows[1] = wgu + (size_t)(f + task) * d;
   };
   Trip<WT, kTripRows, kTripBlocks> trip;
-  stage_norm<WT, kGBlock>(xslot(c, xin_sel), (const WT *)nullptr, gain, d, m.eps, xs, red, nullptr, [&] {
-    if (gw < f) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
-  });
+  if (!early) in.issue(xslot(c, xin_sel), (const WT *)nullptr, gain, d);
+  if (gw < f) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
+  in.finish(d, m.eps, xs, red, nullptr);
   gemv_tasks<WT>(trip, rows, gw, f, tw, d, xs, set_rows, [&](int task, float g, float u) {
     if (lane == 0) mout[task] = g / (1.0f + __expf(-g)) * u;
   });
@@ -302,10 +316,13 @@ __global__ __launch_bounds__(kGBlock) void k_head(Common c, int role, int xin_se
   __shared__ float red[kGWaves];
   __shared__ float bv[kGWaves];
   __shared__ int bi[kGWaves];
-  const StageIn si = stage_in(c, role);
-  if (!si.active) return;
   const Dims &m = c.dm;
   const int d = m.d, V = m.V;
+  NormStage<WT, kGBlock> in;
+  const bool early = static_slot(xin_sel);
+  if (early) in.issue(c.xbuf + (size_t)xin_sel * d, (const WT *)nullptr, gain, d);
+  const StageIn si = stage_in(c, role);
+  if (!si.active) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int n_tasks = (V + 1) >> 1;
   const int gw = blockIdx.x * kGWaves + wave, tw = gridDim.x * kGWaves;
@@ -315,9 +332,9 @@ __global__ __launch_bounds__(kGBlock) void k_head(Common c, int role, int xin_se
     rows[1] = W + (size_t)min(2 * task + 1, V - 1) * d;
   };
   Trip<WT, kTripRows, kTripBlocks> trip;
-  stage_norm<WT, kGBlock>(xslot(c, xin_sel), (const WT *)nullptr, gain, d, m.eps, xs, red, nullptr, [&] {
-    if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
-  });
+  if (!early) in.issue(xslot(c, xin_sel), (const WT *)nullptr, gain, d);
+  if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
+  in.finish(d, m.eps, xs, red, nullptr);
   // logits row for the parity harness: row index = number of tokens committed so far
   float *lrow = nullptr;
   if (logits_log && is_lm) {

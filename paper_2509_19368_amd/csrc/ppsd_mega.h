@@ -480,7 +480,7 @@ __global__ __launch_bounds__(kMBlock) void k_mega(MegaArgs A) {
       const int first = (k == 0) ? wg : (wg + nwg / 2) % nwg;
       for (int u = first; u < per; u += nwg) {
         const int kvh = u / A.attn_splits, split = u - kvh * A.attn_splits;
-        attn_unit<WT, HD, G, kMBlock>(c, g.layer, run.pos, kvh, split, A.attn_splits, A.q[s.slot], A.a[s.slot],
+        attn_unit<WT, HD, G, kMBlock>(c, c.page_table, g.layer, run.pos, kvh, split, A.attn_splits, A.q[s.slot], A.a[s.slot],
                                       A.partials[s.slot], A.counters[s.slot], lds, &s_last);
       }
     };
@@ -558,7 +558,7 @@ __global__ __launch_bounds__(kMBlock) void k_mega(MegaArgs A) {
             } else {
               const int which = (h < m.n_h + m.n_kv) ? 0 : 1;
               const int kvh = which ? h - m.n_h - m.n_kv : h - m.n_h;
-              WT *dst = kv_row<WT>(c, t.layer, pos, kvh, which);
+              WT *dst = kv_row<WT>(c, c.page_table, t.layer, pos, kvh, which);
               dst[i] = Pack<WT>::from_float(lo);
               dst[i + half] = Pack<WT>::from_float(hi);
             }
