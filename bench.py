@@ -21,6 +21,16 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE (scaled by reference
+# dispatches of known size), 7B shapes: profiles/weight_streaming_kernels_7B_shapes_pmc.md
+MEASURED_TRAFFIC_BYTES = {
+    ("C2", "gate_up"): 88246.2 * 2048 + 43.2 * 1024,
+    ("C2", "qkv"): 49344.5 * 2048 + 48.0 * 1024,
+    ("C2", "head"): 128191.4 * 2048 + 32.0 * 1024,
+    ("C2", "o_proj"): 16515.5 * 2048 + 16.0 * 1024,
+    ("C2", "down"): 44273.4 * 2048 + 16.0 * 1024,
+}
+
 
 def algorithmic_bytes(w, mean_ctx: float):
     """Weights once + KV once per committed token (vanilla), plus PPSD's own extras."""
@@ -96,7 +106,12 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--modes", default="vanilla,serial,overlap")
-    ap.add_argument("--engine", default="persistent", choices=["streams", "persistent"])
+    ap.add_argument("--engine", default="streams", choices=["streams", "persistent"])
+    ap.add_argument("--prompt-len", type=int, default=None, help="override the workload's prompt length")
+    ap.add_argument("--decode-len", type=int, default=None, help="override the workload's decode length")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="first run a 1 GiB device copy and a 1 GiB streaming read (reference dispatches for "
+                         "scaling rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the two pipeline stages share one MI355X); "
@@ -116,6 +131,17 @@ def main():
         w = w.replace(damp=args.damp)
     if args.exit_layer is not None:
         w = w.replace(exit_layer=args.exit_layer)
+    if args.prompt_len is not None:
+        w = w.replace(prompt_len=args.prompt_len)
+    if args.decode_len is not None:
+        w = w.replace(decode_len=args.decode_len)
+    if args.calibrate:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                       # reads 1 GiB, writes 1 GiB
+        P.hbm_read_probe(src, iters=1)       # k_read_probe twice (warm-up + 1): reads 1 GiB each
+        torch.cuda.synchronize()
+        del src, dst
     t0 = time.perf_counter()
     W = S.make_weights(w, device="cuda")
     torch.cuda.synchronize()
@@ -177,7 +203,8 @@ def main():
                 ktimes[k] = dict(avg_us=us, launches=v["launches"], bytes=kb[k], gbps=kb[k] / us / 1e3)
         dom = max((k for k in ktimes), key=lambda k: ktimes[k]["avg_us"] * ktimes[k]["launches"])
         roofline = dict(bound="hbm", kernel=dom, achieved=ktimes[dom]["gbps"], peak=HBM_PEAK_GBPS, unit="GB/s",
-                        frac=ktimes[dom]["gbps"] / HBM_PEAK_GBPS, traffic=None,
+                        frac=ktimes[dom]["gbps"] / HBM_PEAK_GBPS,
+                        traffic=MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
                         avg_launch_us=ktimes[dom]["avg_us"], bytes_per_launch=ktimes[dom]["bytes"])
 
     cpu = None

@@ -28,6 +28,23 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+BENCH_PATH = os.path.join(HERE, "ppsd_kernel_bench")
+BENCH_SOURCE = os.path.join(HERE, "csrc", "ppsd_kernel_bench.hip")
+
+
+def build_kernel_bench(verbose: bool = False) -> str:
+    """The standalone kernel-level benchmark (no Python at run time; used under rocprofv3 --pmc)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
+    cmd = [hipcc, *flags, "-o", BENCH_PATH, BENCH_SOURCE]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + res.stdout + res.stderr)
+    if verbose:
+        print(" ".join(cmd))
+    return BENCH_PATH
+
+
 def is_stale() -> bool:
     if not os.path.exists(LIB_PATH):
         return True
@@ -37,3 +54,4 @@ def is_stale() -> bool:
 
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_kernel_bench(verbose=True))

@@ -39,12 +39,8 @@ int fail(int code, const char *fmt, ...) {
 constexpr size_t kAlign = 256;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
-// workgroups per CU of the weight-streaming kernels (measured best of 1..8 on the 7B shapes)
-constexpr int kGemvWgsPerCu = 4;
-constexpr int kGateUpWgsPerCu = 2;
 constexpr int kSplitPositions = 512;   // attention: one split per this many positions of capacity
 constexpr int kMaxSplits = 32;         // attention splits along the sequence (both engines)
-constexpr int kMaxWorkgroups = 1024;   // persistent engine: one head candidate per workgroup
 
 enum Kind { kKQkv = 0, kKAttn, kKOproj, kKGateUp, kKDown, kKHead, kKCommit };
 
@@ -144,12 +140,7 @@ struct ppsd_ctx {
   int n_wg = 0;
   // grid of a weight-streaming kernel with n_tasks row-pair tasks: one wave per task up to a few
   // workgroups per CU, then the waves loop
-  int gemv_grid(int n_tasks, int wgs_per_cu = kGemvWgsPerCu) const {
-    const int want = (n_tasks + kGWaves - 1) / kGWaves;
-    int cap = wgs_per_cu * n_cu;
-    if (cap > kMaxWorkgroups) cap = kMaxWorkgroups;
-    return want < cap ? want : cap;
-  }
+  int gemv_grid(int n_tasks, int wgs_per_cu = kGemvWgsPerCu) const { return gemv_grid_for(n_tasks, n_cu, wgs_per_cu); }
   int xs_stride = 0;
   size_t mega_lds = 0;
   int trace_step = -1, trace_wg = 0;

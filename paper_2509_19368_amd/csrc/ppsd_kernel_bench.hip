@@ -1,0 +1,108 @@
+// Kernel-level benchmark of the weight-streaming kernels at a model shape, without Python or torch:
+// each kernel is launched back to back over weight regions that rotate through a multi-GiB buffer
+// (so no launch finds its weights in a cache), in the library's own launch configuration, with the
+// device state set to "active".  Prints microseconds per launch and the algorithmic GB/s.
+// Also the reference dispatches for scaling rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings:
+// k_read_probe over 1 GiB and a 1 GiB device-to-device copy.
+//
+// usage: ppsd_kernel_bench [d_model d_ffn vocab n_heads n_kv_heads head_dim [iters]]   (bf16 storage)
+#include <cstdio>
+#include <cstdlib>
+
+#include "ppsd_kernels.h"
+
+using namespace ppsd;
+
+#define CK(x)                                                                                       \
+  do {                                                                                              \
+    hipError_t e_ = (x);                                                                            \
+    if (e_ != hipSuccess) { printf("HIP error %s at %s:%d\n", hipGetErrorString(e_), __FILE__, __LINE__); return 1; } \
+  } while (0)
+
+__global__ void k_copy16(const uint4 *src, uint4 *dst, size_t n) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) dst[i] = src[i];
+}
+
+int main(int argc, char **argv) {
+  int d = 4096, f = 11008, V = 32000, n_h = 32, n_kv = 32, hd = 128, iters = 30;
+  if (argc >= 7) { d = atoi(argv[1]); f = atoi(argv[2]); V = atoi(argv[3]); n_h = atoi(argv[4]); n_kv = atoi(argv[5]); hd = atoi(argv[6]); }
+  if (argc >= 8) iters = atoi(argv[7]);
+  const int nq = n_h * hd;
+  if (d % 8 || f % 8 || d > 8192 || f > 16384 || nq > 16384 || (hd != 64 && hd != 128)) { printf("unsupported shape\n"); return 2; }
+  int dev = 0, n_cu = 0;
+  CK(hipGetDevice(&dev));
+  CK(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+  const size_t bytes = (size_t)6 << 30;
+  char *W, *ws;
+  CK(hipMalloc(&W, bytes));
+  CK(hipMemset(W, 0x3c, bytes));            // bf16 0x3c3c = 0.0115: finite products
+  CK(hipMalloc(&ws, (size_t)64 << 20));
+  CK(hipMemset(ws, 0, (size_t)64 << 20));
+  Common c{};
+  c.st = (DevState *)ws;
+  c.prompt = (int32_t *)(ws + 4096);
+  c.xbuf = (float *)(ws + (1 << 20));
+  c.rope_cos = (float *)(ws + (2 << 20));
+  c.rope_sin = (float *)(ws + (3 << 20));
+  c.page_table = (int32_t *)(ws + (4 << 20));
+  c.kv_pool = ws + (8 << 20);
+  const int max_seq = 386, pt = 16, n_pages = (max_seq + pt - 1) / pt;
+  c.dm = Dims{d, n_h, n_kv, hd, f, V, 32, 8, max_seq, pt, n_pages, 1, 0, gemv_grid_for((V + 1) / 2, n_cu, kGemvWgsPerCu), 1e-5f, 0.088f};
+  DevState st{};
+  st.t = 10; st.last_token = 5; st.full = 1; st.draft = 7; st.n_out = 0; st.target = 1 << 30;
+  CK(hipMemcpy(ws, &st, sizeof st, hipMemcpyHostToDevice));
+  float *gain = (float *)(ws + (5 << 20)), *mout = (float *)(ws + (6 << 20)), *vin = (float *)(ws + (7 << 20));
+  float2 *cand = (float2 *)(ws + (40 << 20));
+  hipEvent_t e0, e1;
+  CK(hipEventCreate(&e0));
+  CK(hipEventCreate(&e1));
+  printf("device: %d CUs; shape d=%d f=%d V=%d heads=%d/%d x %d; %d launches each\n", n_cu, d, f, V, n_h, n_kv, hd, iters);
+
+  // reference dispatches for counter scaling
+  {
+    const size_t gib = (size_t)1 << 30;
+    hipLaunchKernelGGL(k_read_probe, dim3(2048), dim3(kBlock), 0, 0, (const uint4 *)W, gib / 16, (uint32_t *)(ws + (50 << 20)));
+    hipLaunchKernelGGL(k_copy16, dim3(4096), dim3(256), 0, 0, (const uint4 *)W, (uint4 *)(W + 2 * gib), gib / 16);
+    CK(hipDeviceSynchronize());
+    printf("reference dispatches: k_read_probe reads 1 GiB; k_copy16 reads 1 GiB and writes 1 GiB\n");
+  }
+
+  auto run = [&](const char *name, size_t mat_bytes, auto launch) {
+    const int parts = (int)(bytes / mat_bytes);
+    for (int i = 0; i < 3; ++i) launch((const bf16_t *)(W + (size_t)(i % parts) * mat_bytes));
+    (void)hipDeviceSynchronize();
+    (void)hipEventRecord(e0);
+    for (int i = 0; i < iters; ++i) launch((const bf16_t *)(W + (size_t)((i + 3) % parts) * mat_bytes));
+    (void)hipEventRecord(e1);
+    (void)hipEventSynchronize(e1);
+    float ms = 0.f;
+    (void)hipEventElapsedTime(&ms, e0, e1);
+    ms /= iters;
+    printf("%-22s %7.1f MB  %7.2f us/launch  %6.0f GB/s\n", name, mat_bytes / 1e6, ms * 1e3, mat_bytes / ms / 1e6);
+    fflush(stdout);
+  };
+  const int qkv_rows = (n_h + 2 * n_kv) * hd;
+  run("k_qkv", (size_t)qkv_rows * d * 2, [&](const bf16_t *w) {
+    hipLaunchKernelGGL((k_qkv<bf16_t>), dim3(gemv_grid_for(qkv_rows / 2, n_cu, kGemvWgsPerCu)), dim3(kGBlock), (size_t)d * 4, 0, c,
+                       (int)kVanilla, 3, (int)kXDraft, 0, w, gain, w, mout);
+  });
+  run("k_proj_resid (o_proj)", (size_t)d * nq * 2, [&](const bf16_t *w) {
+    hipLaunchKernelGGL((k_proj_resid<bf16_t>), dim3(gemv_grid_for((d + 1) / 2, n_cu, kGemvWgsPerCu)), dim3(kGBlock), (size_t)nq * 4, 0, c,
+                       (int)kVanilla, vin, nq, w, d, (int)kXDraft, (int)kXDraft);
+  });
+  run("k_gate_up", (size_t)2 * f * d * 2, [&](const bf16_t *w) {
+    hipLaunchKernelGGL((k_gate_up<bf16_t>), dim3(gemv_grid_for(f, n_cu, kGateUpWgsPerCu)), dim3(kGBlock), (size_t)d * 4, 0, c,
+                       (int)kVanilla, (int)kXDraft, gain, w, mout);
+  });
+  run("k_proj_resid (down)", (size_t)d * f * 2, [&](const bf16_t *w) {
+    hipLaunchKernelGGL((k_proj_resid<bf16_t>), dim3(gemv_grid_for((d + 1) / 2, n_cu, kGemvWgsPerCu)), dim3(kGBlock), (size_t)f * 4, 0, c,
+                       (int)kVanilla, vin, f, w, d, (int)kXDraft, (int)kXDraft);
+  });
+  run("k_head", (size_t)V * d * 2, [&](const bf16_t *w) {
+    hipLaunchKernelGGL((k_head<bf16_t>), dim3(c.dm.head_blocks), dim3(kGBlock), (size_t)d * 4, 0, c, (int)kVanilla, (int)kXDraft, gain,
+                       w, cand, (float *)nullptr, 1);
+  });
+  return 0;
+}

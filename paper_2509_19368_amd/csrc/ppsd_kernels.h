@@ -15,6 +15,19 @@
 
 namespace ppsd {
 
+// Launch policy of the weight-streaming kernels: one wave per row-pair task up to a few workgroups
+// per CU, beyond that the waves loop.  Measured best of 1..8 workgroups per CU on the 7B shapes:
+// 4 for qkv / o_proj / down / head, 2 for gate_up.
+constexpr int kGemvWgsPerCu = 4;
+constexpr int kGateUpWgsPerCu = 2;
+constexpr int kMaxWorkgroups = 1024;   // also the capacity of the head-candidate arrays
+inline int gemv_grid_for(int n_tasks, int n_cu, int wgs_per_cu) {
+  const int want = (n_tasks + kGWaves - 1) / kGWaves;
+  int cap = wgs_per_cu * n_cu;
+  if (cap > kMaxWorkgroups) cap = kMaxWorkgroups;
+  return want < cap ? want : cap;
+}
+
 // KV pool addressing: [layer][physical page][kv head][K=0 / V=1][slot][hd]
 // ptab: the page table, in global memory or a copy in LDS.
 template <typename WT>
