@@ -95,6 +95,45 @@ def cpu_oracle_baseline(w, W_gpu, prompt, torch, budget_s=25.0):
                        f"({dt:.1f} s)")
 
 
+def c3_grid_report(args, torch, S, P):
+    """Exit layer x acceptance grid on the 7B shape: PPSD speedup over vanilla GPU decode per cell."""
+    from oracle import speedup_model as M
+    cells_out = []
+    vanilla_tps = None
+    engine = P.ENGINE_PERSISTENT if args.engine == "persistent" else P.ENGINE_STREAMS
+    for w in S.c3_grid():
+        W = S.make_weights(w, device="cuda")
+        prompt = S.make_prompt(w)
+        n, max_seq = w.decode_len, w.prompt_len + w.decode_len + 2
+        ab = algorithmic_bytes(w, w.prompt_len + 1 + n / 2.0)
+        if vanilla_tps is None:          # depends on the shape only
+            ss = P.Session(w, W, max_seq=max_seq, mode=P.MODE_VANILLA, engine=engine)
+            t, _, _ = run_generations(ss, prompt, n, args.steps, args.warmup, torch)
+            ss.close()
+            vanilla_tps = args.steps * n / sum(t)
+        ss = P.Session(w, W, max_seq=max_seq, mode=P.MODE_OVERLAP, engine=engine)
+        t, st, _ = run_generations(ss, prompt, n, args.steps, args.warmup, torch)
+        ss.close()
+        tps = args.steps * n / sum(t)
+        alpha = st["accepted"] / st["drafts_compared"]
+        cells_out.append({
+            "cell": w.name, "exit_layer": w.exit_layer, "damp": w.damp, "acceptance_rate": alpha, "tokens_per_s": tps,
+            "speedup_vs_vanilla_gpu": tps / vanilla_tps,
+            "byte_model_ratio": ab["vanilla"] / (ab["accept_step"] + (1 - alpha) * ab["reject_extra"]),
+            "paper_eq7_gain_one_gpu_per_stage": M.ppsd_gain(alpha, w.exit_layer, w.n_layers)})
+        del W
+        torch.cuda.empty_cache()
+    best = max(cells_out, key=lambda c: c["tokens_per_s"])
+    print(json.dumps({
+        "metric": "committed tokens/sec at batch 1 (PPSD decode), exit-layer x acceptance grid on the 7B shape",
+        "value": best["tokens_per_s"], "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * 256 / best["tokens_per_s"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "C3: 7B shape bf16, prompt 256, decode 256, batch 1; value = best cell " + best["cell"],
+                   "engine": args.engine},
+        "vanilla_tokens_per_s": vanilla_tps, "cells": cells_out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -126,7 +165,10 @@ def main():
         sys.exit(2)
     P.load_library()
 
-    w = S.WORKLOADS[args.workload]
+    cells = {c.name: c for c in S.c3_grid()}
+    if args.workload == "C3":
+        return c3_grid_report(args, torch, S, P)
+    w = cells[args.workload] if args.workload in cells else S.WORKLOADS[args.workload]
     if args.damp is not None:
         w = w.replace(damp=args.damp)
     if args.exit_layer is not None:

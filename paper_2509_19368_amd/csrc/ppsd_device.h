@@ -268,21 +268,29 @@ __device__ __forceinline__ float wg_sum(float v, float *red) {
 // norm gain) into registers, *_finish reduces and writes LDS.  A residual slot that does not depend
 // on the state (the stage's working slot) is loaded before stage_in() resolves; the embedding row
 // and the hExit buffers are loaded after it.
-constexpr int kNormPer = 16;   // d <= kNormPer * BLOCK
-constexpr int kCopyPer = 32;   // C <= kCopyPer * BLOCK
+constexpr int kNormPer = 4;    // 16-byte pieces per thread: d <= 4 * kNormPer * BLOCK
+constexpr int kCopyPer = 8;    // C <= 4 * kCopyPer * BLOCK
+
+// Four consecutive elements of a storage-dtype row as floats.
+__device__ __forceinline__ float4 load4_as_float(const float *p) { return *(const float4 *)p; }
+__device__ __forceinline__ float4 load4_as_float(const bf16_t *p) {
+  const uint2 u = *(const uint2 *)p;
+  return make_float4(__uint_as_float(u.x << 16), __uint_as_float(u.x & 0xffff0000u), __uint_as_float(u.y << 16),
+                     __uint_as_float(u.y & 0xffff0000u));
+}
 
 template <typename WT, int BLOCK>
 struct NormStage {
-  float xv[kNormPer], gv[kNormPer];
-  // xrow (storage dtype) or xf (fp32): exactly one is non-null
+  float4 xv[kNormPer], gv[kNormPer];
+  // xrow (storage dtype) or xf (fp32): exactly one is non-null.  d % 4 == 0.
   __device__ __forceinline__ void issue(const float *xf, const WT *xrow, const float *gain, int d) {
 #pragma unroll
     for (int e = 0; e < kNormPer; ++e) {
-      const int i = threadIdx.x + e * BLOCK;
-      xv[e] = 0.f; gv[e] = 0.f;
+      const int i = 4 * (threadIdx.x + e * BLOCK);
+      xv[e] = make_float4(0.f, 0.f, 0.f, 0.f); gv[e] = xv[e];
       if (i < d) {
-        xv[e] = xrow ? Pack<WT>::to_float(xrow[i]) : xf[i];
-        gv[e] = gain[i];
+        xv[e] = xrow ? load4_as_float(xrow + i) : load4_as_float(xf + i);
+        gv[e] = load4_as_float(gain + i);
       }
     }
   }
@@ -292,18 +300,21 @@ struct NormStage {
     float ss = 0.f;
 #pragma unroll
     for (int e = 0; e < kNormPer; ++e) {
-      const int i = threadIdx.x + e * BLOCK;
+      const int i = 4 * (threadIdx.x + e * BLOCK);
       if (i < d) {
-        if (copy_out) copy_out[i] = xv[e];
-        ss = fmaf(xv[e], xv[e], ss);
+        if (copy_out) *(float4 *)(copy_out + i) = xv[e];
+        ss = fmaf(xv[e].x, xv[e].x, ss); ss = fmaf(xv[e].y, xv[e].y, ss);
+        ss = fmaf(xv[e].z, xv[e].z, ss); ss = fmaf(xv[e].w, xv[e].w, ss);
       }
     }
     ss = wg_sum<BLOCK>(ss, red);
     const float rs = 1.0f / sqrtf(ss / (float)d + eps);
 #pragma unroll
     for (int e = 0; e < kNormPer; ++e) {
-      const int i = threadIdx.x + e * BLOCK;
-      if (i < d) xs[i] = xv[e] * rs * gv[e];
+      const int i = 4 * (threadIdx.x + e * BLOCK);
+      if (i < d)
+        *(float4 *)(xs + i) = make_float4(xv[e].x * rs * gv[e].x, xv[e].y * rs * gv[e].y, xv[e].z * rs * gv[e].z,
+                                          xv[e].w * rs * gv[e].w);
     }
     __syncthreads();
   }
@@ -311,19 +322,19 @@ struct NormStage {
 
 template <int BLOCK>
 struct CopyStage {
-  float xv[kCopyPer];
-  __device__ __forceinline__ void issue(const float *vin, int C) {
+  float4 xv[kCopyPer];
+  __device__ __forceinline__ void issue(const float *vin, int C) {   // C % 4 == 0
 #pragma unroll
     for (int e = 0; e < kCopyPer; ++e) {
-      const int i = threadIdx.x + e * BLOCK;
-      xv[e] = i < C ? vin[i] : 0.f;
+      const int i = 4 * (threadIdx.x + e * BLOCK);
+      xv[e] = i < C ? *(const float4 *)(vin + i) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
   }
   __device__ __forceinline__ void finish(int C, float *xs) {
 #pragma unroll
     for (int e = 0; e < kCopyPer; ++e) {
-      const int i = threadIdx.x + e * BLOCK;
-      if (i < C) xs[i] = xv[e];
+      const int i = 4 * (threadIdx.x + e * BLOCK);
+      if (i < C) *(float4 *)(xs + i) = xv[e];
     }
     __syncthreads();
   }

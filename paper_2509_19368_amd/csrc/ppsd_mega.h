@@ -438,37 +438,13 @@ __global__ __launch_bounds__(kMBlock) void k_mega(MegaArgs A) {
           gain = s.head == 2 ? A.exit_norm : A.final_norm;
           xf = slot_ptr(s.head_xin);
         }
-        // x and gain are fetched together; d <= 16 * 512 keeps both in registers
-        constexpr int kPer = 16;
-        float xv[kPer], gv[kPer];
-        float ss = 0.f;
-#pragma unroll
-        for (int e = 0; e < kPer; ++e) {
-          const int i = tid + e * kMBlock;
-          xv[e] = 0.f; gv[e] = 0.f;
-          if (i < m.d) {
-            xv[e] = xrow ? Pack<WT>::to_float(xrow[i]) : xf[i];
-            gv[e] = gain[i];
-          }
-        }
-#pragma unroll
-        for (int e = 0; e < kPer; ++e) {
-          const int i = tid + e * kMBlock;
-          if (i < m.d) {
-            if (copy_out) copy_out[i] = xv[e];
-            ss = fmaf(xv[e], xv[e], ss);
-          }
-        }
-        ss = mblock_sum(ss, red);
-        const float rs = 1.0f / sqrtf(ss / (float)m.d + m.eps);
-#pragma unroll
-        for (int e = 0; e < kPer; ++e) {
-          const int i = tid + e * kMBlock;
-          if (i < m.d) xs[i] = xv[e] * rs * gv[e];
-        }
+        NormStage<WT, kMBlock> in;       // same code, same reduction order as the per-operation kernels
+        in.issue(xf, xrow, gain, m.d);
+        in.finish(m.d, m.eps, xs, red, copy_out);
       } else if (g.kind == SK_OPROJ || g.kind == SK_DOWN) {
-        const float *vin = g.kind == SK_OPROJ ? A.a[s.slot] : A.m[s.slot];
-        for (int i = tid; i < g.C; i += kMBlock) xs[i] = vin[i];
+        CopyStage<kMBlock> in;
+        in.issue(g.kind == SK_OPROJ ? A.a[s.slot] : A.m[s.slot], g.C);
+        in.finish(g.C, xs);
       }
     };
     // ---- attention is workgroup-level work done at phase entry (such a phase has no weight tasks)

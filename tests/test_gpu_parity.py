@@ -282,3 +282,35 @@ def test_c2_shape_with_fp32_storage_matches_the_oracle_closely(P):
     err = ((logits.double() - ref).abs().max(dim=1).values / ref.abs().max(dim=1).values).max().item()
     print(f"C2 shape, fp32 storage: max relative logit error {err:.3e}")
     assert err <= REL_TOL_FP32
+
+
+def _big_shape_parity(P, w, n):
+    Wg = S.make_weights(w, device="cuda")
+    prompt = S.make_prompt(w)
+    max_seq = w.prompt_len + n + 2
+    ss = P.Session(w, Wg, max_seq=max_seq, mode=P.MODE_OVERLAP, debug_logits=n + 1)
+    toks = [ss.ppsd_prefill(prompt)] + ss.ppsd_decode(n)
+    logits, st = ss.read_logits(0, n + 1), ss.ppsd_stats()
+    ss.close()
+    sv = P.Session(w, Wg, max_seq=max_seq, mode=P.MODE_VANILLA, debug_logits=n + 1)
+    vt = [sv.ppsd_prefill(prompt)] + sv.ppsd_decode(n)
+    vl = sv.read_logits(0, n + 1)
+    sv.close()
+    assert vt == toks and torch.equal(vl, logits)
+    W = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in Wg.items()}
+    del Wg
+    torch.cuda.empty_cache()
+    worst, loose = check_against_teacher_forced_oracle(O.Decoder(w, W), prompt, toks, logits, REL_TOL_BF16)
+    print(f"{w.name}: max relative logit error {worst:.3e}; {loose} of {n + 1} positions inside the margin; "
+          f"accepted {st['accepted']} rejected {st['rejected']}")
+
+
+def test_c4_shape_13b_parity(P):
+    """Workload C4's model (13B shape, bf16, E = 10) on a shortened prompt: teacher-forced protocol."""
+    _big_shape_parity(P, S.WORKLOADS["C4"].replace(prompt_len=48, decode_len=8), 8)
+
+
+def test_c5_shape_gqa_long_context_parity(P):
+    """Workload C5's model (8B GQA shape, vocab 128256, rope base 5e5) with a context long enough for
+    two attention splits (the full 8192-token prompt is beyond what the fp64 oracle finishes in a test)."""
+    _big_shape_parity(P, S.WORKLOADS["C5"].replace(prompt_len=600, decode_len=6), 6)
