@@ -63,9 +63,13 @@ def run_generations(ss, prompt, n_decode, steps, warmup, torch):
     times = []
     stats = None
     toks = None
+    ss.prefill_ms = []
     for it in range(warmup + steps):
+        torch.cuda.synchronize()
+        tp = time.perf_counter()
         first = ss.ppsd_prefill(prompt)
         torch.cuda.synchronize()
+        ss.prefill_ms.append(1e3 * (time.perf_counter() - tp))
         t0 = time.perf_counter()
         out = ss.ppsd_decode(n_decode)
         torch.cuda.synchronize()
@@ -146,6 +150,7 @@ def main():
     ap.add_argument("--no-kernel-timing", action="store_true")
     ap.add_argument("--modes", default="vanilla,serial,overlap")
     ap.add_argument("--engine", default="streams", choices=["streams", "persistent"])
+    ap.add_argument("--prefill-loop", action="store_true", help="prefill with the decode kernels, one position at a time")
     ap.add_argument("--prompt-len", type=int, default=None, help="override the workload's prompt length")
     ap.add_argument("--decode-len", type=int, default=None, help="override the workload's decode length")
     ap.add_argument("--calibrate", action="store_true",
@@ -200,12 +205,13 @@ def main():
     for name, mode in (("vanilla", P.MODE_VANILLA), ("serial", P.MODE_SERIAL), ("overlap", P.MODE_OVERLAP)):
         if name not in args.modes.split(","):
             continue
-        ss = P.Session(w, W, max_seq=max_seq, mode=mode, engine=engine)
+        ss = P.Session(w, W, max_seq=max_seq, mode=mode, engine=engine, prefill_loop=args.prefill_loop)
         times, st, toks = run_generations(ss, prompt, n, args.steps, args.warmup, torch)
+        prefill_ms = min(ss.prefill_ms)
         ss.close()
         total = sum(times)
         res[name] = dict(tokens_per_s=args.steps * n / total, ms_per_generation=1e3 * total / args.steps,
-                         ms_per_token=1e3 * total / (args.steps * n), stats=st)
+                         ms_per_token=1e3 * total / (args.steps * n), stats=st, prefill_ms=prefill_ms)
         streams[name] = toks
     if len(streams) > 1:
         first = next(iter(streams.values()))
@@ -276,6 +282,8 @@ def main():
         if "vanilla" in res else None,
         "hbm_frac_per_moved_byte": (r["tokens_per_s"] * (ab["accept_step"] + (1 - alpha) * ab["reject_extra"])
                                     / (HBM_PEAK_GBPS * 1e9)) if alpha is not None else None,
+        "prefill": {"ms": r["prefill_ms"], "tokens_per_s": w.prompt_len / r["prefill_ms"] * 1e3,
+                    "path": "looped decode kernels" if args.prefill_loop else "MFMA GEMMs in chunks of 512 positions (when eligible)"},
         "roofline": roofline, "kernels": ktimes, "cpu_baseline": cpu,
         "weight_generation_s": gen_s,
     }

@@ -83,7 +83,11 @@ typedef struct {
   int32_t time_kernels;    /* 1: profiling mode -- direct launches on one stream with a HIP event
                               pair around every kernel, totals via ppsd_kernel_times (slow) */
   int32_t engine;          /* PPSD_ENGINE_*: how a step is executed on the GPU */
-  int32_t reserved[6];     /* must be zero */
+  int32_t prefill_loop;    /* 0: prefill on the matrix cores (MFMA GEMMs over chunks of the prompt) when the
+                              configuration allows it (bf16, head_dim 128, d_model % 128 == 0,
+                              d_ffn % 64 == 0), else the loop below; 1: always run the prompt through the
+                              decode kernels one position at a time */
+  int32_t reserved[5];     /* must be zero */
 } ppsd_config;
 
 /* DEVICE pointers, BORROWED.  Per-layer entries are HOST arrays of n_layers DEVICE pointers. */

@@ -13,6 +13,7 @@
 
 #include "../../include/ppsd.h"
 #include "ppsd_mega.h"
+#include "ppsd_prefill.h"
 
 using namespace ppsd;
 
@@ -48,6 +49,8 @@ struct Layout {
   size_t state, prompt, out_tokens, drafts, page_table, rope_cos, rope_sin, xbuf;
   size_t q[2], a[2], mbuf[2], partials[2], counters[2], cand_lm, cand_exit, sink, logits, kv;
   size_t layer_ptrs, bar, abort_flag, trace;
+  size_t pf_x, pf_q, pf_ao, pf_m, pf_rs;   // MFMA prefill chunk buffers (0 bytes when not used)
+  bool pf;
   size_t total;
   int n_pages, n_splits, head_blocks;
 };
@@ -77,9 +80,16 @@ bool valid_config(const ppsd_config *c, const char **why) {
   REJECT(c->d_ffn > 32 * kGBlock || c->n_heads * c->head_dim > 32 * kGBlock, "d_ffn / n_heads*head_dim exceed the staging capacity (16384)");
   REJECT(c->engine != PPSD_ENGINE_STREAMS && c->engine != PPSD_ENGINE_PERSISTENT, "engine must be 0 or 1");
   REJECT(c->engine == PPSD_ENGINE_PERSISTENT && c->time_kernels, "time_kernels needs the per-operation engine");
-  for (int k = 0; k < 6; ++k) REJECT(c->reserved[k] != 0, "reserved fields must be zero");
+  REJECT(c->prefill_loop != 0 && c->prefill_loop != 1, "prefill_loop must be 0 or 1");
+  for (int k = 0; k < 5; ++k) REJECT(c->reserved[k] != 0, "reserved fields must be zero");
 #undef REJECT
   return true;
+}
+
+// The matrix-core prefill covers bf16 storage, head_dim 128 and tile-aligned widths.
+bool pf_eligible(const ppsd_config *c) {
+  return !c->prefill_loop && c->dtype == PPSD_BF16 && c->head_dim == 128 && c->d_model % kPfBN == 0 && c->d_ffn % 64 == 0 &&
+         c->d_model % kPfBK == 0 && c->d_ffn % kPfBK == 0;
 }
 
 Layout make_layout(const ppsd_config *c) {
@@ -114,6 +124,13 @@ Layout make_layout(const ppsd_config *c) {
   L.bar = take(256);
   L.abort_flag = take(256);
   L.trace = take(8ull * kTraceSlots * kTracePhases);
+  L.pf = pf_eligible(c);
+  const size_t pc = L.pf ? kPfChunk : 0;
+  L.pf_x = take(4ull * pc * c->d_model);
+  L.pf_q = take(4ull * pc * nq);
+  L.pf_ao = take(4ull * pc * nq);
+  L.pf_m = take(4ull * pc * c->d_ffn);
+  L.pf_rs = take(4ull * pc);
   L.sink = take(256);
   L.logits = take(4ull * c->debug_logits * c->vocab);
   L.kv = take((size_t)c->n_layers * L.n_pages * c->n_kv_heads * 2 * c->kv_page_tokens * c->head_dim * es);
@@ -449,6 +466,56 @@ int mega_setup(ppsd_ctx *x) {
   return PPSD_OK;
 }
 
+// ---------------------------------------------------------------- matrix-core prefill
+template <int EPI>
+void pf_launch_gemm(ppsd_ctx *x, const PfGemm &g, int n_tiles_n) {
+  const dim3 grid(n_tiles_n, (g.n_valid + kPfBM - 1) / kPfBM);
+  hipLaunchKernelGGL((k_pf_gemm<EPI>), grid, dim3(kPfBlock), 0, x->sA, x->cm, g);
+}
+
+int prefill_mfma(ppsd_ctx *x, int n_prompt) {
+  const ppsd_config &c = x->cfg;
+  const int d = c.d_model, f = c.d_ffn, nq = c.n_heads * c.head_dim;
+  const int qkv_heads = c.n_heads + 2 * c.n_kv_heads, G = c.n_heads / c.n_kv_heads;
+  float *X = at<float>(x, x->lay.pf_x), *Q = at<float>(x, x->lay.pf_q), *AO = at<float>(x, x->lay.pf_ao);
+  float *M = at<float>(x, x->lay.pf_m), *rs = at<float>(x, x->lay.pf_rs);
+  const int waves = kPfBlock / kWave;
+  for (int c0 = 0; c0 < n_prompt; c0 += kPfChunk) {
+    const int nv = n_prompt - c0 < kPfChunk ? n_prompt - c0 : kPfChunk;
+    hipLaunchKernelGGL(k_pf_embed, dim3(nv), dim3(kPfBlock), 0, x->sA, (const bf16_t *)x->embed, x->cm.prompt, c0, nv, d, X);
+    for (int l = 0; l < c.n_layers; ++l) {
+      PfGemm g{};
+      g.n_valid = nv; g.c0 = c0; g.layer = l; g.X = X; g.Q = Q; g.M = M;
+      hipLaunchKernelGGL(k_pf_rowscale, dim3((nv + waves - 1) / waves), dim3(kPfBlock), 0, x->sA, (const float *)X, d, nv, c.rms_eps, rs);
+      g.A = X; g.rs = rs; g.gain = (const float *)x->attn_norm[l]; g.W = (const bf16_t *)x->wqkv[l]; g.K = d;
+      pf_launch_gemm<kPfQkv>(x, g, qkv_heads);
+      const dim3 agrid(c.n_kv_heads, nv);
+      if (G == 1) hipLaunchKernelGGL((k_pf_attn<1>), agrid, dim3(kPfBlock), 0, x->sA, x->cm, l, c0, (const float *)Q, AO);
+      else if (G == 2) hipLaunchKernelGGL((k_pf_attn<2>), agrid, dim3(kPfBlock), 0, x->sA, x->cm, l, c0, (const float *)Q, AO);
+      else hipLaunchKernelGGL((k_pf_attn<4>), agrid, dim3(kPfBlock), 0, x->sA, x->cm, l, c0, (const float *)Q, AO);
+      g.A = AO; g.rs = nullptr; g.gain = nullptr; g.W = (const bf16_t *)x->wo[l]; g.K = nq;
+      pf_launch_gemm<kPfResid>(x, g, d / kPfBN);
+      hipLaunchKernelGGL(k_pf_rowscale, dim3((nv + waves - 1) / waves), dim3(kPfBlock), 0, x->sA, (const float *)X, d, nv, c.rms_eps, rs);
+      g.A = X; g.rs = rs; g.gain = (const float *)x->mlp_norm[l]; g.W = (const bf16_t *)x->wgu[l]; g.K = d;
+      pf_launch_gemm<kPfSwiglu>(x, g, f / 64);
+      g.A = M; g.rs = nullptr; g.gain = nullptr; g.W = (const bf16_t *)x->wdown[l]; g.K = f;
+      pf_launch_gemm<kPfResid>(x, g, d / kPfBN);
+      HIP_TRY(hipGetLastError());
+    }
+    if (c0 + nv == n_prompt)
+      hipLaunchKernelGGL(k_pf_last_row, dim3(4), dim3(256), 0, x->sA, (const float *)X, nv - 1, d, x->cm.xbuf + (size_t)kXDraft * d);
+  }
+  // the LM head and the commit run as for the last position of the looped prefill
+  hipLaunchKernelGGL(k_begin_prefill, dim3(1), dim3(64), 0, x->sA, at<DevState>(x, x->lay.state), n_prompt, n_prompt - 1);
+  Launcher A{x, x->sA, false};
+  if (c.dtype == PPSD_FP32) return fail(PPSD_ESTATE, "matrix-core prefill is bf16 only");
+  launch_head<bf16_t>(A, kPrefill, kXDraft, true);
+  launch_commit(A, 3);
+  if (A.err != hipSuccess) return fail(PPSD_EHIP, "prefill head: %s", hipGetErrorString(A.err));
+  HIP_TRY(hipGetLastError());
+  return PPSD_OK;
+}
+
 int read_state(ppsd_ctx *x) {
   HIP_TRY(hipMemcpyAsync(x->h_state, at<DevState>(x, x->lay.state), sizeof(DevState), hipMemcpyDeviceToHost, x->sA));
   HIP_TRY(hipStreamSynchronize(x->sA));
@@ -611,10 +678,13 @@ int ppsd_prefill(ppsd_ctx *x, const int32_t *prompt, int32_t n_prompt, int32_t *
     if (prompt[i] < 0 || prompt[i] >= x->cfg.vocab) return fail(PPSD_EARG, "prompt[%d] = %d is outside the vocabulary", i, prompt[i]);
   x->prefilled = false;
   HIP_TRY(hipMemcpyAsync(at<int32_t>(x, x->lay.prompt), prompt, 4ull * n_prompt, hipMemcpyHostToDevice, x->sA));
-  hipLaunchKernelGGL(k_begin_prefill, dim3(1), dim3(64), 0, x->sA, at<DevState>(x, x->lay.state), n_prompt);
+  hipLaunchKernelGGL(k_begin_prefill, dim3(1), dim3(64), 0, x->sA, at<DevState>(x, x->lay.state), n_prompt, 0);
   HIP_TRY(hipGetLastError());
   int rc;
-  if (x->cfg.engine == PPSD_ENGINE_PERSISTENT) {
+  if (x->lay.pf) {
+    rc = prefill_mfma(x, n_prompt);
+    if (rc != PPSD_OK) return rc;
+  } else if (x->cfg.engine == PPSD_ENGINE_PERSISTENT) {
     rc = mega_launch(x, true, n_prompt);
     if (rc != PPSD_OK) return rc;
     rc = mega_check_abort(x);

@@ -472,11 +472,11 @@ __global__ __launch_bounds__(kBlock) void k_commit(Common c, int kind, const flo
 }
 
 // Host-requested state edits (tiny, one thread): new prefill / new decode target.
-__global__ void k_begin_prefill(DevState *st, int n_prompt) {
+__global__ void k_begin_prefill(DevState *st, int n_prompt, int start_pos) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
     st->t = -1; st->last_token = -1; st->full = 0; st->draft = -1; st->cur = 0;
     st->n_out = 0; st->target = 0; st->gen_count = 0;
-    st->prefill_pos = 0; st->prefill_len = n_prompt;
+    st->prefill_pos = start_pos; st->prefill_len = n_prompt;
     for (int k = 0; k < 8; ++k) st->stats[k] = 0;
   }
 }

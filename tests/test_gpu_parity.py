@@ -314,3 +314,33 @@ def test_c5_shape_gqa_long_context_parity(P):
     """Workload C5's model (8B GQA shape, vocab 128256, rope base 5e5) with a context long enough for
     two attention splits (the full 8192-token prompt is beyond what the fp64 oracle finishes in a test)."""
     _big_shape_parity(P, S.WORKLOADS["C5"].replace(prompt_len=600, decode_len=6), 6)
+
+
+@pytest.mark.parametrize("prompt_len", [200, 700], ids=["one_chunk_ragged", "two_chunks"])
+def test_matrix_core_prefill_matches_oracle_and_looped_prefill(P, prompt_len):
+    """Prefill through the MFMA GEMMs (chunks of 512 positions) against the oracle and against the
+    decode kernels looped over the prompt: same first token and decode stream under the bf16 protocol,
+    and logits of the two prefill paths within 2e-3 of each other (both carry fp32-grade activations;
+    what differs is summation order and the bf16 rounding of K/V computed from slightly different sums)."""
+    w = S.Workload("pf", n_layers=3, exit_layer=1, d_model=256, n_heads=2, n_kv_heads=1, head_dim=128, d_ffn=704,
+                   vocab=777, dtype="bf16", damp=0.2, seed=31, prompt_len=prompt_len, decode_len=10)
+    W = S.make_weights(w)
+    prompt = S.make_prompt(w)
+    dec = O.Decoder(w, W)
+    Wg = to_device(W, "cuda")
+    runs = []
+    for loop in (False, True):
+        ss = P.Session(w, Wg, max_seq=prompt_len + 12, mode=P.MODE_OVERLAP, debug_logits=11, prefill_loop=loop)
+        toks = [ss.ppsd_prefill(prompt)] + ss.ppsd_decode(10)
+        logits = ss.read_logits(0, 11)
+        ss.close()
+        check_against_teacher_forced_oracle(dec, prompt, toks, logits, REL_TOL_BF16)
+        runs.append((toks, logits))
+    a, b = runs
+    scale = b[1].abs().max(dim=1).values
+    diff = ((a[1] - b[1]).abs().max(dim=1).values / scale)
+    same = 0
+    while same < 11 and a[0][same] == b[0][same]:
+        same += 1
+    assert same >= 1
+    assert diff[:same].max().item() < 2e-3, diff
