@@ -48,7 +48,7 @@ enum Kind { kKQkv = 0, kKAttn, kKOproj, kKGateUp, kKDown, kKHead, kKCommit };
 struct Layout {
   size_t state, prompt, out_tokens, drafts, page_table, rope_cos, rope_sin, xbuf;
   size_t q[2], a[2], mbuf[2], partials[2], counters[2], cand_lm, cand_exit, sink, logits, kv;
-  size_t layer_ptrs, bar, abort_flag, trace;
+  size_t layer_ptrs, bar, abort_flag, trace, cand_counts;
   size_t pf_x, pf_q, pf_ao, pf_m, pf_rs;   // MFMA prefill chunk buffers (0 bytes when not used)
   bool pf;
   size_t total;
@@ -123,6 +123,7 @@ Layout make_layout(const ppsd_config *c) {
   L.layer_ptrs = take(sizeof(LayerPtrs) * (size_t)c->n_layers);
   L.bar = take(256);
   L.abort_flag = take(256);
+  L.cand_counts = take(256);
   L.trace = take(8ull * kTraceSlots * kTracePhases);
   L.pf = pf_eligible(c);
   const size_t pc = L.pf ? kPfChunk : 0;
@@ -385,6 +386,7 @@ MegaArgs mega_args(ppsd_ctx *x, bool prefill, int max_steps) {
   A.cand_lm = at<float2>(x, x->lay.cand_lm); A.cand_exit = at<float2>(x, x->lay.cand_exit);
   A.logits = c.debug_logits > 0 ? at<float>(x, x->lay.logits) : nullptr;
   A.out_tokens = at<int32_t>(x, x->lay.out_tokens); A.drafts = at<int32_t>(x, x->lay.drafts);
+  A.cand_counts = at<int>(x, x->lay.cand_counts);
   A.bar = at<unsigned>(x, x->lay.bar); A.abort_flag = at<int>(x, x->lay.abort_flag);
   A.max_steps = max_steps; A.attn_splits = x->lay.n_splits; A.xs_stride = x->xs_stride;
   A.trace = (!prefill && x->trace_step >= 0) ? at<unsigned long long>(x, x->lay.trace) : nullptr;
@@ -448,16 +450,17 @@ int mega_setup(ppsd_ctx *x) {
   const int vec = c.dtype == PPSD_FP32 ? 4 : 8;
   const int G = c.n_heads / c.n_kv_heads;
   const size_t merge_floats = (size_t)(kMBlock / (c.head_dim / vec)) * G * (c.head_dim + 2);
-  size_t lds_floats = 2 * (size_t)x->xs_stride;
+  size_t lds_floats = (size_t)x->xs_stride;          // one staged input vector per workgroup
   if (merge_floats > lds_floats) lds_floats = merge_floats;
   x->mega_lds = lds_floats * 4;
-  if (x->mega_lds > 150 * 1024) return fail(PPSD_EARG, "persistent engine needs %zu bytes of LDS", x->mega_lds);
   const void *fn = mega_fn(c);
   HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)x->mega_lds));
   int per_cu = 0;
   HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kMBlock, x->mega_lds));
   if (per_cu < 1) return fail(PPSD_EARG, "persistent kernel does not fit on a CU (LDS %zu bytes)", x->mega_lds);
-  x->n_wg = x->n_cu > kMaxWorkgroups ? kMaxWorkgroups : x->n_cu;
+  if (per_cu > kMegaWgsPerCu) per_cu = kMegaWgsPerCu;
+  x->n_wg = per_cu * x->n_cu;
+  if (x->n_wg > kMaxWorkgroups) x->n_wg = kMaxWorkgroups;
   std::vector<LayerPtrs> lp(c.n_layers);
   for (int l = 0; l < c.n_layers; ++l)
     lp[l] = LayerPtrs{(const float *)x->attn_norm[l], x->wqkv[l], x->wo[l], (const float *)x->mlp_norm[l], x->wgu[l], x->wdown[l]};

@@ -399,11 +399,11 @@ __device__ __forceinline__ int reduce_candidates(const float2 *cand, int n, floa
 
 // Called by all BLOCK threads of ONE workgroup.  sv / si_: BLOCK/64 entries of LDS each.
 template <int BLOCK>
-__device__ __forceinline__ void commit_step(const Common &c, int kind, const float2 *cand_lm,
-                                            const float2 *cand_exit, int n_cand, int32_t *out_tokens,
+__device__ __forceinline__ void commit_step(const Common &c, int kind, const float2 *cand_lm, int n_cand_lm,
+                                            const float2 *cand_exit, int n_cand_exit, int32_t *out_tokens,
                                             int32_t *drafts_log, float *sv, int *si_) {
   DevState *st = c.st;
-  const int nb = n_cand;
+  const int nb = n_cand_lm;
   if (kind == 2 || kind == 3) {   // prefill
     if (!(st->prefill_pos < st->prefill_len)) return;
     int tok = -1;
@@ -433,7 +433,7 @@ __device__ __forceinline__ void commit_step(const Common &c, int kind, const flo
     return;
   }
   // PPSD step
-  const int d_next = reduce_candidates<BLOCK>(cand_exit, nb, sv, si_);   // draft stage always ran
+  const int d_next = reduce_candidates<BLOCK>(cand_exit, n_cand_exit, sv, si_);   // draft stage always ran
   int v = -1;
   if (full) v = reduce_candidates<BLOCK>(cand_lm, nb, sv, si_);
   if (threadIdx.x == 0) {
@@ -468,7 +468,7 @@ __global__ __launch_bounds__(kBlock) void k_commit(Common c, int kind, const flo
                                                    int32_t *drafts_log) {
   __shared__ float sv[kWavesPerBlock];
   __shared__ int si_[kWavesPerBlock];
-  commit_step<kBlock>(c, kind, cand_lm, cand_exit, c.dm.head_blocks, out_tokens, drafts_log, sv, si_);
+  commit_step<kBlock>(c, kind, cand_lm, c.dm.head_blocks, cand_exit, c.dm.head_blocks, out_tokens, drafts_log, sv, si_);
 }
 
 // Host-requested state edits (tiny, one thread): new prefill / new decode target.
