@@ -119,3 +119,127 @@ def decode(ss: PPSDSession, n_tokens: int) -> List[int]:
     while len(out) < n_tokens:
         step(ss, out)
     return out
+
+
+# ----------------------------------------------------------------------------
+# The full ceil(N/E)-stage schedule (Sec. 4.1, 4.2, Alg. 1)
+# ----------------------------------------------------------------------------
+# The N layers are cut into S = ceil(N/E) stages of E layers (the last one takes what remains);
+# stage 0 also holds the early-exit head and keeps drafting one token per tick from its own
+# previous draft, every later stage carries the token it received one tick earlier one stage
+# further, and the last stage's LM head yields the model's true next token.  That token is
+# compared with the draft made for the same position (the check token of Alg. 1); on a mismatch
+# every token in flight was computed from a wrong draft: all of them, and the KV rows they wrote in
+# every stage, are dropped and stage 0 restarts from the verified token at the position after it
+# (Alg. 1's index reset).  An accepted token therefore costs one tick and a rejected one S ticks,
+# which is Eq. (7).
+
+
+@dataclass
+class PipelineStats:
+    committed: int = 0
+    drafts_compared: int = 0
+    accepted: int = 0
+    rejected: int = 0
+    ticks: int = 0
+    stage_runs: int = 0            # stage executions, summed over stages and ticks
+    flushed_tokens: int = 0        # in-flight speculative tokens dropped by rejections
+
+    @property
+    def acceptance(self) -> float:
+        return self.accepted / self.drafts_compared if self.drafts_compared else 0.0
+
+
+def stage_ranges(n_layers: int, exit_layer: int) -> List[range]:
+    """Layers of each pipeline stage: E per stage, the remainder forms a last, shorter stage."""
+    return [range(lo, min(lo + exit_layer, n_layers)) for lo in range(0, n_layers, exit_layer)]
+
+
+@dataclass
+class PipelineSession:
+    dec: Decoder
+    kv: KVState
+    t: int                                   # position of the last committed token
+    last_token: int
+    stages: List[range] = None
+    valid: List[bool] = None                 # valid[k]: stage k has an input for the coming tick
+    pos: List[int] = None                    # position that input belongs to
+    hidden: List[torch.Tensor] = None        # hidden[k]: input of stage k (k >= 1)
+    tok0: int = -1                           # token stage 0 will embed
+    token_at: dict = field(default_factory=dict)   # position -> token stage 0 used there
+    stats: PipelineStats = field(default_factory=PipelineStats)
+
+
+def pipeline_prefill(dec: Decoder, prompt: Sequence[int], max_seq: int) -> PipelineSession:
+    base = prefill(dec, prompt, max_seq)
+    S = len(stage_ranges(dec.s.n_layers, dec.s.exit_layer))
+    ss = PipelineSession(dec=dec, kv=base.kv, t=base.t, last_token=base.last_token,
+                         stages=stage_ranges(dec.s.n_layers, dec.s.exit_layer))
+    ss.valid = [True] + [False] * (S - 1)
+    ss.pos = [base.t] + [0] * (S - 1)
+    ss.hidden = [None] * S
+    ss.tok0 = base.last_token
+    return ss
+
+
+def pipeline_tick(ss: PipelineSession, out: List[int]) -> None:
+    dec, kv = ss.dec, ss.kv
+    S = len(ss.stages)
+    st = ss.stats
+    st.ticks += 1
+    produced = [None] * S            # produced[k]: hidden state leaving stage k this tick
+    draft_next = None
+    # all stages work on different tokens within a tick; their order does not matter
+    for k in range(S):
+        if not ss.valid[k]:
+            continue
+        st.stage_runs += 1
+        x_in = dec.embed([ss.tok0])[0] if k == 0 else ss.hidden[k]
+        if k == 0:
+            ss.token_at[ss.pos[0]] = ss.tok0
+        # a stage re-running a position after a flush overwrites the dropped row
+        for l in ss.stages[k]:
+            if kv.len[l] > ss.pos[k]:
+                kv.len[l] = ss.pos[k]
+        produced[k] = run_layers(dec, kv, x_in, ss.pos[k], ss.stages[k])
+        if k == 0:
+            draft_next = argmax_lowest(dec.head_logits(produced[0], "exit"))
+    flush = False
+    if ss.valid[S - 1]:
+        v = argmax_lowest(dec.head_logits(produced[S - 1], "lm"))
+        p = ss.pos[S - 1] + 1                      # the position v belongs to
+        st.committed += 1
+        out.append(v)
+        ss.t, ss.last_token = p, v
+        if p in ss.token_at:                       # a draft for that position is in flight: check token
+            st.drafts_compared += 1
+            if ss.token_at[p] == v:
+                st.accepted += 1
+            else:
+                st.rejected += 1
+                flush = True
+        elif S > 1:
+            raise AssertionError("a committed token without a draft can only happen with a single stage")
+    if flush or S == 1:
+        if flush:
+            st.flushed_tokens += sum(1 for q in ss.token_at if q >= ss.t)   # the rejected draft and all after it
+        ss.token_at = {}
+        ss.valid = [True] + [False] * (S - 1)
+        ss.pos = [ss.t] + [0] * (S - 1)
+        ss.tok0 = ss.last_token
+        return
+    # no flush: every token moves one stage on, stage 0 continues from its own draft
+    for k in range(S - 1, 0, -1):
+        ss.valid[k] = ss.valid[k - 1]
+        ss.pos[k] = ss.pos[k - 1]
+        ss.hidden[k] = produced[k - 1]
+    ss.pos[0] += 1
+    ss.tok0 = draft_next
+    ss.token_at = {q: tk for q, tk in ss.token_at.items() if q > ss.t}
+
+
+def pipeline_decode(ss: PipelineSession, n_tokens: int) -> List[int]:
+    out: List[int] = []
+    while len(out) < n_tokens:
+        pipeline_tick(ss, out)
+    return out

@@ -102,3 +102,92 @@ def test_rollback_is_needed_for_losslessness(tiny_shape):
     except AssertionError:
         raised = True
     assert raised
+
+
+# ------------------------------------------------------------------ full ceil(N/E)-stage schedule
+def _pipeline(w, W=None, n=None):
+    W = S.make_weights(w) if W is None else W
+    dec = O.Decoder(w, W)
+    prompt = S.make_prompt(w)
+    n = w.decode_len if n is None else n
+    ss = P.pipeline_prefill(dec, prompt, len(prompt) + n + 8)
+    committed = []
+    reject_at = []
+    while len(committed) < n:
+        before = ss.stats.rejected
+        P.pipeline_tick(ss, committed)
+        if ss.stats.rejected > before:
+            reject_at.append(len(committed) - 1)
+    return dec, prompt, [ss_first(dec, prompt)] + committed, ss, reject_at
+
+
+def ss_first(dec, prompt):
+    return O.argmax_lowest(dec.logits_full(list(prompt))[-1])
+
+
+def test_stage_partition_follows_the_paper():
+    assert [list(r) for r in P.stage_ranges(8, 3)] == [[0, 1, 2], [3, 4, 5], [6, 7]]     # remainder = own stage
+    assert len(P.stage_ranges(32, 8)) == 4 and len(P.stage_ranges(32, 12)) == 3
+    assert [len(r) for r in P.stage_ranges(40, 10)] == [10, 10, 10, 10]
+
+
+def test_pipeline_schedule_is_lossless_for_every_granularity(tiny_shape):
+    base = tiny_shape.replace(n_layers=5, decode_len=18)
+    for E in (1, 2, 3, 4):
+        for head in ("tied", "independent"):
+            w = base.replace(exit_layer=E, exit_head=head)
+            dec, prompt, toks, ss, _ = _pipeline(w)
+            assert toks == O.greedy_decode_no_cache(dec, prompt, w.decode_len + 1), (E, head)
+            st = ss.stats
+            assert st.committed == w.decode_len == st.accepted + st.rejected == st.drafts_compared
+
+
+def test_pipeline_tick_count_is_eq7s_cost_model(tiny_shape):
+    """An accepted token costs one tick, a rejected one ceil(N/E) ticks (Eq. (7)); the first token after
+    prefill pays the pipeline fill, and the refill of a rejection is paid before the NEXT commit."""
+    base = tiny_shape.replace(n_layers=6, decode_len=24, damp=0.2)
+    for E in (1, 2, 3, 4):
+        w = base.replace(exit_layer=E)
+        Sg = -(-w.n_layers // E)
+        _, _, _, ss, reject_at = _pipeline(w)
+        n = w.decode_len
+        paid = sum(1 for k in reject_at if k < n - 1)
+        assert ss.stats.ticks == (Sg - 1) + n + (Sg - 1) * paid
+        # in the long run: ticks per token -> alpha + (1 - alpha) S, i.e. Eq. (7)'s denominator / E
+    w = base.replace(exit_layer=2, damp=0.0)          # every draft right: N/E tokens per N/E ticks
+    _, _, _, ss, reject_at = _pipeline(w)
+    assert not reject_at and ss.stats.ticks == 2 + w.decode_len
+    from oracle import speedup_model as M
+    assert (w.n_layers / 2) * w.decode_len / (ss.stats.ticks - 2) == M.ppsd_gain(1.0, 2, w.n_layers)
+
+
+def test_pipeline_with_two_stages_equals_the_two_stage_schedule(tiny_shape):
+    w = tiny_shape.replace(n_layers=4, exit_layer=2, decode_len=20)
+    dec = O.Decoder(w, S.make_weights(w))
+    prompt = S.make_prompt(w)
+    a = P.prefill(dec, prompt, 40)
+    ta = P.decode(a, 20)
+    b = P.pipeline_prefill(dec, prompt, 40)
+    tb = P.pipeline_decode(b, 20)
+    assert ta == tb
+    assert (a.stats.accepted, a.stats.rejected) == (b.stats.accepted, b.stats.rejected)
+    assert b.stats.ticks == a.stats.steps_overlapped + a.stats.steps_draft_only
+
+
+def test_pipeline_acceptance_equals_the_gold_prefix_rate(tiny_shape):
+    """Chained drafts do not change what is compared: a draft reaches its check only if every
+    draft before it was right, so it was computed on the true prefix (Sec. 5.3, acceptance at gamma = 1)."""
+    w = tiny_shape.replace(n_layers=6, exit_layer=2, decode_len=24, damp=0.15)
+    dec, prompt, toks, ss, _ = _pipeline(w)
+    ex = dec.exit_logits_full((list(prompt) + toks)[:-1])
+    agree = [O.argmax_lowest(ex[len(prompt) + k]) == toks[k + 1] for k in range(w.decode_len)]
+    assert ss.stats.accepted == sum(agree) and 0 < sum(agree) < w.decode_len
+    assert ss.stats.flushed_tokens >= ss.stats.rejected
+
+
+def test_pipeline_always_missing_head_degenerates_to_autoregressive_speed(tiny_shape):
+    w = tiny_shape.replace(n_layers=6, exit_layer=2, decode_len=10)
+    W = S.make_weights(w.replace(damp=0.0)); W["exit_head"] = -W["lm_head"]
+    dec, prompt, toks, ss, _ = _pipeline(w, W)
+    assert ss.stats.accepted == 0 and toks == O.greedy_decode(dec, prompt, 11).tokens
+    assert ss.stats.ticks == 3 * 10                   # S ticks per token: Eq. (7) at alpha = 0 gives 1
