@@ -148,7 +148,8 @@ def main():
     ap.add_argument("--exit-layer", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-timing", action="store_true")
-    ap.add_argument("--modes", default="vanilla,serial,overlap")
+    ap.add_argument("--modes", default="vanilla,serial,overlap,pipeline",
+                    help="pipeline = the full ceil(N/E)-stage schedule, reported beside the two-stage path")
     ap.add_argument("--engine", default="streams", choices=["streams", "persistent"])
     ap.add_argument("--prefill-loop", action="store_true", help="prefill with the decode kernels, one position at a time")
     ap.add_argument("--prompt-len", type=int, default=None, help="override the workload's prompt length")
@@ -195,15 +196,19 @@ def main():
     gen_s = time.perf_counter() - t0
     prompt = S.make_prompt(w)
     n = w.decode_len
-    max_seq = w.prompt_len + n + 2
+    n_stages = -(-w.n_layers // w.exit_layer)
+    max_seq = w.prompt_len + 1 + n + max(1, n_stages - 1)     # + the positions drafted ahead of the last commit
     mean_ctx = w.prompt_len + 1 + n / 2.0
     ab = algorithmic_bytes(w, mean_ctx)
 
     engine = P.ENGINE_PERSISTENT if args.engine == "persistent" else P.ENGINE_STREAMS
     res = {}
     streams = {}
-    for name, mode in (("vanilla", P.MODE_VANILLA), ("serial", P.MODE_SERIAL), ("overlap", P.MODE_OVERLAP)):
+    for name, mode in (("vanilla", P.MODE_VANILLA), ("serial", P.MODE_SERIAL), ("overlap", P.MODE_OVERLAP),
+                       ("pipeline", P.MODE_PIPELINE)):
         if name not in args.modes.split(","):
+            continue
+        if mode == P.MODE_PIPELINE and (engine != P.ENGINE_STREAMS or n_stages > 16):
             continue
         ss = P.Session(w, W, max_seq=max_seq, mode=mode, engine=engine, prefill_loop=args.prefill_loop)
         times, st, toks = run_generations(ss, prompt, n, args.steps, args.warmup, torch)
@@ -272,7 +277,9 @@ def main():
         "ms_per_token": r["ms_per_token"],
         "modes": {k: {"tokens_per_s": v["tokens_per_s"], "ms_per_token": v["ms_per_token"],
                       "steps_draft_only": v["stats"]["steps_draft_only"], "accepted": v["stats"]["accepted"],
-                      "rejected": v["stats"]["rejected"], "device_ms": v["stats"]["device_ms"]}
+                      "rejected": v["stats"]["rejected"], "device_ms": v["stats"]["device_ms"],
+                      **({"stages": n_stages, "ticks": v["stats"]["pipeline_ticks"], "stage_runs": v["stats"]["stage_runs"],
+                          "flushed_tokens": v["stats"]["flushed_tokens"]} if k == "pipeline" else {})}
                   for k, v in res.items()},
         "speedup_vs_vanilla_gpu": (r["tokens_per_s"] / res["vanilla"]["tokens_per_s"]) if "vanilla" in res else None,
         "bytes_per_token": {"vanilla": ab["vanilla"], "ppsd_accept_step": ab["accept_step"],

@@ -50,6 +50,16 @@ extern "C" {
 #define PPSD_MODE_VANILLA    0  /* autoregressive: all N layers + LM head per token, no draft */
 #define PPSD_MODE_SERIAL     1  /* draft stage then verify stage on one stream */
 #define PPSD_MODE_OVERLAP    2  /* draft stage and verify stage on two streams (verify-while-draft) */
+#define PPSD_MODE_PIPELINE   3  /* the full schedule of Sec. 4.1-4.2 / Alg. 1: S = ceil(N/E) stages of E layers
+                                   (the last takes what remains), stage 0 + exit head drafting one token per
+                                   tick from its own previous draft, every later stage carrying the token it
+                                   received one tick earlier, the last stage + LM head yielding the verified
+                                   token.  A mismatch with the draft used at that position drops all S-1
+                                   tokens in flight and restarts stage 0 from the verified token, so an
+                                   accepted token costs one tick and a rejected one S ticks (Eq. 7).  On one
+                                   GPU the S stages of a tick share the chip: even stages run on stream_draft,
+                                   odd ones on stream_verify.  Per-operation engine only, S <= 16, no
+                                   time_kernels.  With S = 2 it commits what PPSD_MODE_OVERLAP commits. */
 
 /* Execution engines.  Both run every step of the path in this library's HIP kernels and give
  * the same tokens; logits agree to fp32 rounding (the RMSNorm sums are grouped differently). */
@@ -72,7 +82,8 @@ typedef struct {
   int32_t d_ffn;
   int32_t vocab;
   int32_t dtype;           /* PPSD_FP32 / PPSD_BF16: storage of weights and KV cache */
-  int32_t max_seq;         /* capacity in positions (prompt + generated + 1 speculative) */
+  int32_t max_seq;         /* capacity in positions (prompt + generated + speculative: 1, or S-1 in
+                              PPSD_MODE_PIPELINE) */
   int32_t kv_page_tokens;  /* positions per KV page: 8, 16, 32 or 64 */
   int32_t mode;            /* PPSD_MODE_* */
   float   rope_base;       /* rotary base; pair (i, i+hd/2) turns by pos * base^(-2i/hd) */
@@ -123,6 +134,11 @@ typedef struct {
   int64_t kv_rollbacks;      /* rejected drafts whose KV rows (layers 1..E) were dropped */
   int64_t steps_launched;    /* steps the host enqueued, including ones that found nothing to do */
   double  device_ms;         /* HIP-event time spent inside ppsd_decode */
+  /* PPSD_MODE_PIPELINE only (zero otherwise); there steps_overlapped / steps_draft_only count the ticks
+   * in which several stages / only stage 0 ran, and kv_rollbacks the rejections. */
+  int64_t pipeline_ticks;    /* ticks that did work; Eq. (7): committed + (S-1) * rejected, up to fill/drain */
+  int64_t stage_runs;        /* stage executions summed over ticks */
+  int64_t flushed_tokens;    /* speculative tokens in flight dropped by rejections (S-1 per rejection) */
 } ppsd_stats_t;
 
 #define PPSD_N_KERNEL_KINDS 7   /* qkv, attention, o_proj, gate_up, down, head, commit */
@@ -147,8 +163,9 @@ int ppsd_prefill(ppsd_ctx *ctx, const int32_t *prompt, int32_t n_prompt, int32_t
 /* Commits exactly n_tokens further tokens into out_tokens (HOST) and sets *n_written = n_tokens.
  * One step drafts with layers 1..E + exit head and verifies with layers E+1..N + LM head
  * (Sec. 4.2); accept/reject and KV rollback happen on the device (Alg. 1).  Resumable: a second
- * call continues the same sequence, keeping an in-flight draft.  PPSD_ESTATE before prefill;
- * PPSD_ECAPACITY if the sequence plus one speculative position would pass max_seq. */
+ * call continues the same sequence, keeping the drafts in flight.  PPSD_ESTATE before prefill;
+ * PPSD_ECAPACITY if the sequence plus the speculative positions (one; S-1 in PPSD_MODE_PIPELINE)
+ * would pass max_seq. */
 int ppsd_decode(ppsd_ctx *ctx, int32_t n_tokens, int32_t *out_tokens, int32_t *n_written);
 
 /* Copies the counters (HOST out). */

@@ -167,6 +167,7 @@ class PipelineSession:
     hidden: List[torch.Tensor] = None        # hidden[k]: input of stage k (k >= 1)
     tok0: int = -1                           # token stage 0 will embed
     token_at: dict = field(default_factory=dict)   # position -> token stage 0 used there
+    compared: List[int] = field(default_factory=list)   # per committed token: the draft it was checked against
     stats: PipelineStats = field(default_factory=PipelineStats)
 
 
@@ -213,6 +214,7 @@ def pipeline_tick(ss: PipelineSession, out: List[int]) -> None:
         ss.t, ss.last_token = p, v
         if p in ss.token_at:                       # a draft for that position is in flight: check token
             st.drafts_compared += 1
+            ss.compared.append(ss.token_at[p])
             if ss.token_at[p] == v:
                 st.accepted += 1
             else:

@@ -13,7 +13,7 @@ import torch
 
 from .build import LIB_PATH
 
-MODE_VANILLA, MODE_SERIAL, MODE_OVERLAP = 0, 1, 2
+MODE_VANILLA, MODE_SERIAL, MODE_OVERLAP, MODE_PIPELINE = 0, 1, 2, 3
 ENGINE_STREAMS, ENGINE_PERSISTENT = 0, 1
 KERNEL_KINDS = ("qkv", "attention", "o_proj", "gate_up", "down", "head", "commit")
 
@@ -42,7 +42,8 @@ class ppsd_buffers(C.Structure):
 class ppsd_stats_t(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("committed", "drafts_compared", "accepted", "rejected", "steps_overlapped",
                                           "steps_draft_only", "kv_rollbacks", "steps_launched")] + \
-               [("device_ms", C.c_double)]
+               [("device_ms", C.c_double)] + \
+               [(n, C.c_int64) for n in ("pipeline_ticks", "stage_runs", "flushed_tokens")]
 
 
 class ppsd_kernel_times_t(C.Structure):

@@ -71,7 +71,7 @@ bool valid_config(const ppsd_config *c, const char **why) {
   REJECT(c->max_seq < 3, "max_seq too small");
   REJECT(c->kv_page_tokens != 8 && c->kv_page_tokens != 16 && c->kv_page_tokens != 32 && c->kv_page_tokens != 64,
          "kv_page_tokens must be 8, 16, 32 or 64");
-  REJECT(c->mode < 0 || c->mode > 2, "mode must be 0, 1 or 2");
+  REJECT(c->mode < 0 || c->mode > 3, "mode must be 0, 1, 2 or 3");
   REJECT(!(c->rope_base > 1.0f) || !(c->rms_eps >= 0.0f), "bad rope_base / rms_eps");
   REJECT(c->debug_logits < 0, "debug_logits < 0");
   REJECT((size_t)c->d_ffn * 4 > 64 * 1024 || (size_t)c->d_model * 4 > 64 * 1024 ||
@@ -81,6 +81,11 @@ bool valid_config(const ppsd_config *c, const char **why) {
   REJECT(c->engine != PPSD_ENGINE_STREAMS && c->engine != PPSD_ENGINE_PERSISTENT, "engine must be 0 or 1");
   REJECT(c->engine == PPSD_ENGINE_PERSISTENT && c->time_kernels, "time_kernels needs the per-operation engine");
   REJECT(c->prefill_loop != 0 && c->prefill_loop != 1, "prefill_loop must be 0 or 1");
+  if (c->mode == PPSD_MODE_PIPELINE) {
+    REJECT(c->engine != PPSD_ENGINE_STREAMS, "the full pipeline schedule runs on the per-operation engine only");
+    REJECT(c->time_kernels, "time_kernels is not available with the full pipeline schedule");
+    REJECT((c->n_layers + c->exit_layer - 1) / c->exit_layer > kMaxStages, "more than 16 pipeline stages (n_layers / exit_layer)");
+  }
   for (int k = 0; k < 5; ++k) REJECT(c->reserved[k] != 0, "reserved fields must be zero");
 #undef REJECT
   return true;
@@ -108,7 +113,7 @@ Layout make_layout(const ppsd_config *c) {
   L.page_table = take(4ull * L.n_pages);
   L.rope_cos = take(4ull * c->max_seq * (c->head_dim / 2));
   L.rope_sin = take(4ull * c->max_seq * (c->head_dim / 2));
-  L.xbuf = take(4ull * 4 * c->d_model);
+  L.xbuf = take(4ull * kXSlots * c->d_model);
   const size_t nq = (size_t)c->n_heads * c->head_dim;
   for (int s = 0; s < 2; ++s) {
     L.q[s] = take(4 * nq);
@@ -207,7 +212,7 @@ struct Launcher {
 };
 
 template <typename WT>
-void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int xout_last_sel, bool from_embed) {
+void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int xout_last_sel, bool from_embed, int xwork) {
   ppsd_ctx *x = L.x;
   const ppsd_config &c = x->cfg;
   const Common &cm = x->cm;
@@ -215,9 +220,7 @@ void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int 
   float *q = at<float>(x, x->lay.q[stage]);
   float *a = at<float>(x, x->lay.a[stage]);
   float *mb = at<float>(x, x->lay.mbuf[stage]);
-  // residual slot used inside the layer after the first residual add
-  const int xwork = (role == kVerify) ? kXVerify : kXDraft;
-
+  // xwork: residual slot used inside the layer after the first residual add
   const int total_pairs = (c.n_heads + 2 * c.n_kv_heads) * (c.head_dim / 2);
   L.before(kKQkv);
   hipLaunchKernelGGL((k_qkv<WT>), dim3(x->gemv_grid(total_pairs)), dim3(kGBlock), (size_t)d * 4, L.s, cm, role, layer,
@@ -277,13 +280,16 @@ void launch_commit(Launcher &L, int kind) {
 }
 
 // A stage = a run of layers [lo, hi) for one role.  The first layer reads xin_first (or the
-// embedding); the last layer's down-projection writes xout_last.
+// embedding); the last layer's down-projection writes xout_last; xwork (a fixed-address slot)
+// carries the residual stream in between.  `stage` picks the set of scratch vectors (q, attention
+// output, MLP activation, split partials): stages that may run concurrently need different sets.
 template <typename WT>
-void launch_stage(Launcher &L, int role, int lo, int hi, int stage, int xin_first, bool from_embed, int xout_last) {
-  const int xwork = (role == kVerify) ? kXVerify : kXDraft;
+void launch_stage(Launcher &L, int role, int lo, int hi, int stage, int xin_first, bool from_embed, int xout_last,
+                  int xwork = -1) {
+  if (xwork < 0) xwork = (role == kVerify) ? kXVerify : kXDraft;
   for (int l = lo; l < hi; ++l)
     launch_layer<WT>(L, role, l, stage, l == lo ? xin_first : xwork, l == hi - 1 ? xout_last : xwork,
-                     from_embed && l == lo);
+                     from_embed && l == lo, xwork);
 }
 
 // One decode step in the given mode.  With two_streams the verify stage goes to stream B between
@@ -304,6 +310,33 @@ hipError_t enqueue_step(ppsd_ctx *x, int mode, bool two_streams, bool timed) {
     if (e != hipSuccess) return e;
     e = hipStreamWaitEvent(x->sB, x->ev_fork, 0);
     if (e != hipSuccess) return e;
+  }
+  if (mode == PPSD_MODE_PIPELINE) {
+    // One tick of the ceil(N/E)-stage schedule: every stage works on its own token, so the stages
+    // are independent within a tick.  Even stages go to stream A, odd ones to stream B; a stream's
+    // stages run one after the other and share that stream's scratch vectors.  Stage k reads the
+    // readable buffer of boundary k and writes the other buffer of boundary k+1; the commit kernel
+    // swaps the buffers when the tokens move on.
+    const int S = x->cm.dm.n_stages;
+    for (int k = 0; k < S; ++k) {
+      Launcher &Lk = (k & 1) ? B : A;
+      const int lo = k * c.exit_layer, hi = (k + 1) * c.exit_layer < c.n_layers ? (k + 1) * c.exit_layer : c.n_layers;
+      const int work = kXStageWork0 + k;
+      const int xin = k == 0 ? work : kXBoundRead0 + k;
+      const int xout = k == S - 1 ? work : kXBoundWrite0 + k + 1;
+      launch_stage<WT>(Lk, kPipeStage0 + k, lo, hi, k & 1, xin, k == 0, xout, work);
+      if (k == 0) launch_head<WT>(Lk, kPipeStage0, kXBoundWrite0 + 1, false);
+      if (k == S - 1) launch_head<WT>(Lk, kPipeStage0 + k, work, true);
+    }
+    if (B.err != hipSuccess) return B.err;
+    if (two_streams) {
+      hipError_t e = hipEventRecord(x->ev_join, x->sB);
+      if (e != hipSuccess) return e;
+      e = hipStreamWaitEvent(x->sA, x->ev_join, 0);
+      if (e != hipSuccess) return e;
+    }
+    launch_commit(A, 4);
+    return A.err;
   }
   // draft stage: layers 1..E + exit head; its last layer writes the other hExit buffer
   launch_stage<WT>(A, kDraft, 0, c.exit_layer, 0, kXDraft, true, kHExitNext);
@@ -602,6 +635,7 @@ int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *b, ppsd_ctx **
   m.V = cfg->vocab; m.L = cfg->n_layers; m.E = cfg->exit_layer; m.max_seq = cfg->max_seq;
   m.page_tokens = cfg->kv_page_tokens; m.n_pages = lay.n_pages; m.n_splits = lay.n_splits;
   m.debug_rows = cfg->debug_logits; m.head_blocks = 0;   // set below, once the device is known
+  m.n_stages = (cfg->n_layers + cfg->exit_layer - 1) / cfg->exit_layer; m.pad0 = 0;
   m.eps = cfg->rms_eps; m.qscale = (float)(1.0 / std::sqrt((double)cfg->head_dim));
 
   auto cleanup = [&](int rc) { ppsd_free(x); return rc; };
@@ -647,7 +681,7 @@ int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *b, ppsd_ctx **
     int rc = mega_setup(x);
     if (rc != PPSD_OK) return cleanup(rc);
   } else if (cfg->use_graph && !cfg->time_kernels) {
-    int rc = capture(x, &x->g_step, [&] { return enqueue_step_any(x, cfg->mode, cfg->mode == PPSD_MODE_OVERLAP, false); });
+    int rc = capture(x, &x->g_step, [&] { return enqueue_step_any(x, cfg->mode, cfg->mode >= PPSD_MODE_OVERLAP, false); });
     if (rc != PPSD_OK) return cleanup(rc);
     rc = capture(x, &x->g_prefill, [&] { return enqueue_prefill_any(x, false, false); });
     if (rc != PPSD_OK) return cleanup(rc);
@@ -719,13 +753,15 @@ int ppsd_decode(ppsd_ctx *x, int32_t n_tokens, int32_t *out_tokens, int32_t *n_w
   if (!x->prefilled) return fail(PPSD_ESTATE, "ppsd_decode before ppsd_prefill");
   if (n_tokens == 0) return PPSD_OK;
   // positions 0..host_len-1 are committed; committing n more needs rows up to host_len+n-1 plus
-  // one speculative row written by the draft stage
-  if ((int64_t)x->host_len + n_tokens + 1 > x->cfg.max_seq)
-    return fail(PPSD_ECAPACITY, "%d committed + %d new + 1 speculative position exceed max_seq %d", x->host_len, n_tokens,
-                x->cfg.max_seq);
+  // the speculative rows written ahead of the last committed token: one by the draft stage, or
+  // one per stage in front of the last one in the full pipeline schedule
+  const int spec = x->cfg.mode == PPSD_MODE_PIPELINE ? x->cm.dm.n_stages - 1 : 1;
+  if ((int64_t)x->host_len + n_tokens + spec > x->cfg.max_seq)
+    return fail(PPSD_ECAPACITY, "%d committed + %d new + %d speculative position(s) exceed max_seq %d", x->host_len, n_tokens,
+                spec, x->cfg.max_seq);
   const ppsd_config &c = x->cfg;
   const bool timed = c.time_kernels != 0;
-  const bool two = c.mode == PPSD_MODE_OVERLAP && !timed;
+  const bool two = c.mode >= PPSD_MODE_OVERLAP && !timed;
   hipLaunchKernelGGL(k_begin_decode, dim3(1), dim3(64), 0, x->sA, at<DevState>(x, x->lay.state), n_tokens);
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipEventRecord(x->ev_t0, x->sA));
@@ -793,6 +829,7 @@ int ppsd_stats(const ppsd_ctx *cx, ppsd_stats_t *out) {
   out->steps_overlapped = s[4]; out->steps_draft_only = s[5]; out->kv_rollbacks = s[6];
   out->steps_launched = x->steps_launched;
   out->device_ms = x->device_ms;
+  out->pipeline_ticks = s[8]; out->stage_runs = s[9]; out->flushed_tokens = s[10];
   return PPSD_OK;
 }
 

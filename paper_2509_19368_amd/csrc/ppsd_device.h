@@ -20,10 +20,19 @@ constexpr int kTripBlocks = 2;       // column blocks per trip: 4 independent 16
 constexpr float kNegBig = -1.0e30f;  // finite stand-in for -inf in the running softmax maximum
 
 // Stage roles: which part of the device state a kernel takes its input from.
-enum Role : int { kVanilla = 0, kDraft = 1, kVerify = 2, kPrefill = 3 };
+// kPipeStage0 + k is stage k of the full ceil(N/E)-stage schedule (Sec. 4.1, Alg. 1).
+enum Role : int { kVanilla = 0, kDraft = 1, kVerify = 2, kPrefill = 3, kPipeStage0 = 16 };
 
-// Residual-stream slots inside xbuf (each d floats).
-enum XSel : int { kXDraft = 0, kXVerify = 1, kHExitCur = 2, kHExitNext = 3 };
+constexpr int kMaxStages = 16;       // stages of the full pipeline schedule
+constexpr int kTokRing = 32;         // ring of the tokens stage 0 used, by position (> kMaxStages)
+
+// Residual-stream slots inside xbuf (each d floats).  The two-stage path uses the first four.
+// The full pipeline adds one working slot per stage (kXStageWork0 + k, fixed address) and, for the
+// boundary in front of stage b >= 1, two buffers that swap roles every tick: the stage reads
+// kXBoundRead0 + b while stage b-1 writes kXBoundWrite0 + b.
+enum XSel : int { kXDraft = 0, kXVerify = 1, kHExitCur = 2, kHExitNext = 3,
+                  kXStageWork0 = 4, kXBoundRead0 = 32, kXBoundWrite0 = 64 };
+constexpr int kXSlots = 4 + kMaxStages + 2 * kMaxStages;   // slots in xbuf
 
 // Device-resident decode state.  Only the commit kernel writes it, once per step, after
 // both stages have finished; every other kernel of the step reads a stable copy.
@@ -39,13 +48,22 @@ struct DevState {
   int32_t prefill_pos;  // next prompt position to process
   int32_t prefill_len;
   int32_t pad[6];
-  int64_t stats[8];     // committed, compared, accepted, rejected, overlapped, draft_only, rollbacks, spare
+  int64_t stats[12];    // committed, compared, accepted, rejected, overlapped, draft_only, rollbacks, spare,
+                        // pipeline ticks, stage runs, flushed in-flight tokens
+  // full pipeline schedule: what each stage works on in the coming tick
+  int32_t pl_valid[kMaxStages];   // stage k has an input
+  int32_t pl_pos[kMaxStages];     // the position it belongs to
+  int32_t pl_tok0;                // token stage 0 embeds
+  int32_t pl_par;                 // which buffer of every stage boundary is the readable one
+  int32_t pl_pad[2];
+  int32_t pl_tok_at[kTokRing];    // token stage 0 used at position p, at index p % kTokRing
 };
 
 struct Dims {
   int32_t d, n_h, n_kv, hd, f, V, L, E;
   int32_t max_seq, page_tokens, n_pages, n_splits;
   int32_t debug_rows, head_blocks;
+  int32_t n_stages, pad0;   // ceil(L / E)
   float eps, qscale;     // qscale = 1/sqrt(hd)
 };
 
@@ -53,7 +71,7 @@ struct Dims {
 struct Common {
   DevState *st;
   const int32_t *prompt;      // [max_seq] prompt ids (device)
-  float *xbuf;                // [4][d]
+  float *xbuf;                // [kXSlots][d]
   const float *rope_cos;      // [max_seq][hd/2]
   const float *rope_sin;
   const int32_t *page_table;  // [n_pages]
@@ -84,10 +102,15 @@ __device__ __forceinline__ StageIn stage_in(const Common &c, int role) {
     s.active = running;
     s.pos = st->full ? st->t + 1 : st->t;
     s.tok = st->full ? st->draft : st->last_token;
-  } else {  // kVerify
+  } else if (role == kVerify) {
     s.active = running && st->full;
     s.pos = st->t;
     s.tok = -1;
+  } else {  // kPipeStage0 + k, k < kMaxStages (the host launches no other role)
+    const int k = (role - kPipeStage0) & (kMaxStages - 1);
+    s.active = running && st->pl_valid[k];
+    s.pos = st->pl_pos[k];
+    s.tok = k == 0 ? st->pl_tok0 : -1;
   }
   return s;
 }
@@ -96,6 +119,8 @@ __device__ __forceinline__ float *xslot(const Common &c, int sel) {
   int slot = sel;
   if (sel == kHExitCur) slot = 2 + (c.st->cur & 1);
   else if (sel == kHExitNext) slot = 2 + ((c.st->cur & 1) ^ 1);
+  else if (sel >= kXBoundWrite0) slot = kXStageWork0 + kMaxStages + 2 * ((sel - kXBoundWrite0) & (kMaxStages - 1)) + ((c.st->pl_par & 1) ^ 1);
+  else if (sel >= kXBoundRead0) slot = kXStageWork0 + kMaxStages + 2 * ((sel - kXBoundRead0) & (kMaxStages - 1)) + (c.st->pl_par & 1);
   return c.xbuf + (size_t)slot * c.dm.d;
 }
 
@@ -341,7 +366,9 @@ struct CopyStage {
 };
 
 // A residual selector whose address does not depend on the device state.
-__device__ __forceinline__ bool static_slot(int sel) { return sel == kXDraft || sel == kXVerify; }
+__device__ __forceinline__ bool static_slot(int sel) {
+  return sel == kXDraft || sel == kXVerify || (sel >= kXStageWork0 && sel < kXStageWork0 + kMaxStages);
+}
 
 // A wave's share of a GEMV: tasks task, task + tw, ... of kTripRows rows each.  set_rows(t) points
 // rows[] at task t; the first trip of `task` is already in flight in trip.  After a task's last

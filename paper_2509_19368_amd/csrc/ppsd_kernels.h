@@ -375,7 +375,7 @@ __global__ __launch_bounds__(kGBlock) void k_head(Common c, int role, int xin_se
 // ------------------------------------------------------------------------------------------
 // a10: finish both argmax reductions, compare draft with the verifier's token, commit, roll back.
 // One workgroup.  kind: 0 vanilla step, 1 PPSD step, 2 prefill position (no head), 3 last prefill
-// position (LM head ran).
+// position (LM head ran), 4 one tick of the full pipeline schedule.
 template <int BLOCK>
 __device__ __forceinline__ int reduce_candidates(const float2 *cand, int n, float *sv, int *si_) {
   constexpr int NW = BLOCK / kWave;
@@ -416,11 +416,65 @@ __device__ __forceinline__ void commit_step(const Common &c, int kind, const flo
         st->full = 0;
         st->gen_count = 1;
         drafts_log[0] = -1;
+        // full pipeline schedule: only stage 0 has work, the committed token at its position
+        for (int k = 0; k < kMaxStages; ++k) { st->pl_valid[k] = 0; st->pl_pos[k] = 0; }
+        st->pl_valid[0] = 1; st->pl_pos[0] = st->prefill_len; st->pl_tok0 = tok; st->pl_par = 0;
       }
     }
     return;
   }
   if (!(st->n_out < st->target)) return;
+  if (kind == 4) {
+    // One tick of the ceil(N/E)-stage schedule (Sec. 4.1-4.2, Alg. 1).  Stage 0 always ran and
+    // drafted the token after its own; if the last stage ran, its LM head gives the model's token
+    // for the position after the one it carried.  That token is emitted and compared with the one
+    // stage 0 used at that position.  Equal: every token moves one stage on.  Different: all
+    // tokens in flight came from a wrong draft; their KV rows are dropped by not advancing past
+    // them (the restart rewrites those positions before anything reads them) and stage 0 restarts
+    // from the verified token.
+    const int S = c.dm.n_stages;
+    const int ran_last = st->pl_valid[S - 1];
+    const int d_next = reduce_candidates<BLOCK>(cand_exit, n_cand_exit, sv, si_);
+    int v = -1;
+    if (ran_last) v = reduce_candidates<BLOCK>(cand_lm, nb, sv, si_);
+    if (threadIdx.x == 0) {
+      int n_ran = 0;
+      for (int k = 0; k < S; ++k) n_ran += st->pl_valid[k] ? 1 : 0;
+      st->stats[8] += 1;
+      st->stats[9] += n_ran;
+      if (n_ran > 1) st->stats[4] += 1; else st->stats[5] += 1;
+      const int pos0 = st->pl_pos[0];
+      st->pl_tok_at[pos0 & (kTokRing - 1)] = st->pl_tok0;
+      bool flush = false;
+      if (ran_last) {
+        const int p = st->pl_pos[S - 1] + 1;                  // the position v belongs to
+        const int d = st->pl_tok_at[p & (kTokRing - 1)];      // stage 0 has used a draft there (S >= 2)
+        out_tokens[st->n_out] = v;
+        drafts_log[st->gen_count] = d;
+        st->n_out += 1; st->gen_count += 1;
+        st->stats[0] += 1; st->stats[1] += 1;
+        st->t = p; st->last_token = v;
+        if (v == d) {
+          st->stats[2] += 1;
+        } else {
+          st->stats[3] += 1; st->stats[6] += 1;
+          st->stats[10] += pos0 - p + 1;                      // the rejected draft and all after it
+          flush = true;
+        }
+      }
+      if (flush) {
+        for (int k = 1; k < S; ++k) st->pl_valid[k] = 0;
+        st->pl_pos[0] = st->t;
+        st->pl_tok0 = v;
+      } else {
+        for (int k = S - 1; k > 0; --k) { st->pl_valid[k] = st->pl_valid[k - 1]; st->pl_pos[k] = st->pl_pos[k - 1]; }
+        st->pl_pos[0] = pos0 + 1;
+        st->pl_tok0 = d_next;
+        st->pl_par ^= 1;                                      // what the stages wrote becomes readable
+      }
+    }
+    return;
+  }
   const int full = st->full;
   if (kind == 0) {   // vanilla: the LM head's token is the next token
     const int v = reduce_candidates<BLOCK>(cand_lm, nb, sv, si_);
@@ -477,7 +531,9 @@ __global__ void k_begin_prefill(DevState *st, int n_prompt, int start_pos) {
     st->t = -1; st->last_token = -1; st->full = 0; st->draft = -1; st->cur = 0;
     st->n_out = 0; st->target = 0; st->gen_count = 0;
     st->prefill_pos = start_pos; st->prefill_len = n_prompt;
-    for (int k = 0; k < 8; ++k) st->stats[k] = 0;
+    for (int k = 0; k < 12; ++k) st->stats[k] = 0;
+    for (int k = 0; k < kMaxStages; ++k) { st->pl_valid[k] = 0; st->pl_pos[k] = 0; }
+    st->pl_tok0 = -1; st->pl_par = 0;
   }
 }
 

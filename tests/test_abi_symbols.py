@@ -34,7 +34,19 @@ def test_config_validation_runs_on_the_host():
     cfg = make_config(S.WORKLOADS["C2"], 400, P.MODE_OVERLAP)
     n = P.ppsd_workspace_bytes(cfg)
     kv = 32 * 25 * 32 * 2 * 16 * 128 * 2          # layers * pages * kv heads * (K,V) * slots * hd * bytes
-    assert kv < n < kv + (8 << 20)
+    # besides the KV pool: ~46 MiB of prompt-chunk buffers of the matrix-core prefill (512 positions x
+    # (d + 2 * n_heads * head_dim + d_ffn) floats) and under 2 MiB of activations and tables
+    pf = 4 * 512 * (4096 + 2 * 4096 + 11008)
+    assert kv + pf < n < kv + pf + (4 << 20)
+    cfg.mode = P.MODE_PIPELINE
+    assert P.ppsd_workspace_bytes(cfg) == n           # the schedule does not change the layout
+    cfg.exit_layer = 1                                # 32 stages: more than the schedule supports
+    try:
+        P.ppsd_workspace_bytes(cfg)
+        assert False
+    except P.PpsdError as e:
+        assert "pipeline stages" in str(e)
+    cfg.mode = P.MODE_OVERLAP
     cfg.exit_layer = 32
     try:
         P.ppsd_workspace_bytes(cfg)
