@@ -57,8 +57,8 @@ extern "C" {
                                    token.  A mismatch with the draft used at that position drops all S-1
                                    tokens in flight and restarts stage 0 from the verified token, so an
                                    accepted token costs one tick and a rejected one S ticks (Eq. 7).  On one
-                                   GPU the S stages of a tick share the chip: even stages run on stream_draft,
-                                   odd ones on stream_verify.  Per-operation engine only, S <= 16, no
+                                   GPU the S stages of a tick share the chip: stage k runs on stream
+                                   k mod pipeline_streams.  Per-operation engine only, S <= 16, no
                                    time_kernels.  With S = 2 it commits what PPSD_MODE_OVERLAP commits. */
 
 /* Execution engines.  Both run every step of the path in this library's HIP kernels and give
@@ -98,7 +98,12 @@ typedef struct {
                               configuration allows it (bf16, head_dim 128, d_model % 128 == 0,
                               d_ffn % 64 == 0), else the loop below; 1: always run the prompt through the
                               decode kernels one position at a time */
-  int32_t reserved[5];     /* must be zero */
+  int32_t pipeline_streams;/* PPSD_MODE_PIPELINE: streams the stages of a tick are spread over; 0 = default
+                              (min(S, 4)), else 2..4.  Streams beyond the caller's two are created (default
+                              priority) and destroyed by the library */
+  int32_t tune_wgs_per_cu; /* launch tuning: workgroups per compute unit of the weight-streaming kernels,
+                              1..4; 0 = the library's defaults (4; 2 for gate/up) */
+  int32_t reserved[3];     /* must be zero */
 } ppsd_config;
 
 /* DEVICE pointers, BORROWED.  Per-layer entries are HOST arrays of n_layers DEVICE pointers. */

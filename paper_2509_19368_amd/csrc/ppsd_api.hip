@@ -42,12 +42,13 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 constexpr int kSplitPositions = 512;   // attention: one split per this many positions of capacity
 constexpr int kMaxSplits = 32;         // attention splits along the sequence (both engines)
+constexpr int kMaxStreams = 4;         // streams the stages of a pipeline tick are spread over
 
 enum Kind { kKQkv = 0, kKAttn, kKOproj, kKGateUp, kKDown, kKHead, kKCommit };
 
 struct Layout {
   size_t state, prompt, out_tokens, drafts, page_table, rope_cos, rope_sin, xbuf;
-  size_t q[2], a[2], mbuf[2], partials[2], counters[2], cand_lm, cand_exit, sink, logits, kv;
+  size_t q[kMaxStreams], a[kMaxStreams], mbuf[kMaxStreams], partials[kMaxStreams], counters[kMaxStreams], cand_lm, cand_exit, sink, logits, kv;
   size_t layer_ptrs, bar, abort_flag, trace, cand_counts;
   size_t pf_x, pf_q, pf_ao, pf_m, pf_rs;   // MFMA prefill chunk buffers (0 bytes when not used)
   bool pf;
@@ -86,7 +87,9 @@ bool valid_config(const ppsd_config *c, const char **why) {
     REJECT(c->time_kernels, "time_kernels is not available with the full pipeline schedule");
     REJECT((c->n_layers + c->exit_layer - 1) / c->exit_layer > kMaxStages, "more than 16 pipeline stages (n_layers / exit_layer)");
   }
-  for (int k = 0; k < 5; ++k) REJECT(c->reserved[k] != 0, "reserved fields must be zero");
+  REJECT(c->pipeline_streams < 0 || c->pipeline_streams == 1 || c->pipeline_streams > kMaxStreams, "pipeline_streams must be 0 (default) or 2..4");
+  REJECT(c->tune_wgs_per_cu < 0 || c->tune_wgs_per_cu > 4, "tune_wgs_per_cu must be 0..4");
+  for (int k = 0; k < 3; ++k) REJECT(c->reserved[k] != 0, "reserved fields must be zero");
 #undef REJECT
   return true;
 }
@@ -115,7 +118,7 @@ Layout make_layout(const ppsd_config *c) {
   L.rope_sin = take(4ull * c->max_seq * (c->head_dim / 2));
   L.xbuf = take(4ull * kXSlots * c->d_model);
   const size_t nq = (size_t)c->n_heads * c->head_dim;
-  for (int s = 0; s < 2; ++s) {
+  for (int s = 0; s < kMaxStreams; ++s) {
     L.q[s] = take(4 * nq);
     L.a[s] = take(4 * nq);
     L.mbuf[s] = take(4ull * c->d_ffn);
@@ -154,7 +157,10 @@ struct ppsd_ctx {
   std::vector<const void *> attn_norm, wqkv, wo, mlp_norm, wgu, wdown;
   char *ws;
   hipStream_t sA, sB;
+  hipStream_t sx[kMaxStreams] = {};     // pipeline ticks: sx[0] = sA, sx[1] = sB, the rest created here
+  int n_streams = 2;
   hipEvent_t ev_fork, ev_join, ev_t0, ev_t1;
+  hipEvent_t ev_joinx[kMaxStreams] = {};
   hipGraphExec_t g_step = nullptr;      // decode step in cfg.mode
   hipGraphExec_t g_prefill = nullptr;   // one prompt position, no head
   DevState *h_state = nullptr;          // pinned
@@ -163,7 +169,9 @@ struct ppsd_ctx {
   int n_wg = 0;
   // grid of a weight-streaming kernel with n_tasks row-pair tasks: one wave per task up to a few
   // workgroups per CU, then the waves loop
-  int gemv_grid(int n_tasks, int wgs_per_cu = kGemvWgsPerCu) const { return gemv_grid_for(n_tasks, n_cu, wgs_per_cu); }
+  int gemv_grid(int n_tasks, int wgs_per_cu = kGemvWgsPerCu) const {
+    return gemv_grid_for(n_tasks, n_cu, cfg.tune_wgs_per_cu > 0 ? cfg.tune_wgs_per_cu : wgs_per_cu);
+  }
   int xs_stride = 0;
   size_t mega_lds = 0;
   int trace_step = -1, trace_wg = 0;
@@ -304,39 +312,44 @@ hipError_t enqueue_step(ppsd_ctx *x, int mode, bool two_streams, bool timed) {
     launch_commit(A, 0);
     return A.err;
   }
+  if (mode == PPSD_MODE_PIPELINE) {
+    // One tick of the ceil(N/E)-stage schedule: every stage works on its own token, so the stages
+    // are independent within a tick.  Stage k goes to stream k mod n_streams; a stream's stages run
+    // one after the other and share that stream's scratch vectors.  Stage k reads the readable
+    // buffer of boundary k and writes the other buffer of boundary k+1; the commit kernel swaps
+    // the buffers when the tokens move on.
+    const int S = x->cm.dm.n_stages;
+    const int ns = two_streams ? x->n_streams : 1;
+    hipError_t e = ns > 1 ? hipEventRecord(x->ev_fork, x->sA) : hipSuccess;
+    for (int i = 1; i < ns && e == hipSuccess; ++i) e = hipStreamWaitEvent(x->sx[i], x->ev_fork, 0);
+    if (e != hipSuccess) return e;
+    for (int k = 0; k < S; ++k) {
+      const int si = k % ns;
+      Launcher Lk{x, x->sx[si], false};
+      const int lo = k * c.exit_layer, hi = (k + 1) * c.exit_layer < c.n_layers ? (k + 1) * c.exit_layer : c.n_layers;
+      const int work = kXStageWork0 + k;
+      const int xin = k == 0 ? work : kXBoundRead0 + k;
+      const int xout = k == S - 1 ? work : kXBoundWrite0 + k + 1;
+      launch_stage<WT>(Lk, kPipeStage0 + k, lo, hi, si, xin, k == 0, xout, work);
+      if (k == 0) launch_head<WT>(Lk, kPipeStage0, kXBoundWrite0 + 1, false);
+      if (k == S - 1) launch_head<WT>(Lk, kPipeStage0 + k, work, true);
+      if (Lk.err != hipSuccess) return Lk.err;
+    }
+    for (int i = 1; i < ns; ++i) {
+      e = hipEventRecord(x->ev_joinx[i], x->sx[i]);
+      if (e != hipSuccess) return e;
+      e = hipStreamWaitEvent(x->sA, x->ev_joinx[i], 0);
+      if (e != hipSuccess) return e;
+    }
+    launch_commit(A, 4);
+    return A.err;
+  }
   Launcher B{x, two_streams ? x->sB : x->sA, timed};
   if (two_streams) {
     hipError_t e = hipEventRecord(x->ev_fork, x->sA);
     if (e != hipSuccess) return e;
     e = hipStreamWaitEvent(x->sB, x->ev_fork, 0);
     if (e != hipSuccess) return e;
-  }
-  if (mode == PPSD_MODE_PIPELINE) {
-    // One tick of the ceil(N/E)-stage schedule: every stage works on its own token, so the stages
-    // are independent within a tick.  Even stages go to stream A, odd ones to stream B; a stream's
-    // stages run one after the other and share that stream's scratch vectors.  Stage k reads the
-    // readable buffer of boundary k and writes the other buffer of boundary k+1; the commit kernel
-    // swaps the buffers when the tokens move on.
-    const int S = x->cm.dm.n_stages;
-    for (int k = 0; k < S; ++k) {
-      Launcher &Lk = (k & 1) ? B : A;
-      const int lo = k * c.exit_layer, hi = (k + 1) * c.exit_layer < c.n_layers ? (k + 1) * c.exit_layer : c.n_layers;
-      const int work = kXStageWork0 + k;
-      const int xin = k == 0 ? work : kXBoundRead0 + k;
-      const int xout = k == S - 1 ? work : kXBoundWrite0 + k + 1;
-      launch_stage<WT>(Lk, kPipeStage0 + k, lo, hi, k & 1, xin, k == 0, xout, work);
-      if (k == 0) launch_head<WT>(Lk, kPipeStage0, kXBoundWrite0 + 1, false);
-      if (k == S - 1) launch_head<WT>(Lk, kPipeStage0 + k, work, true);
-    }
-    if (B.err != hipSuccess) return B.err;
-    if (two_streams) {
-      hipError_t e = hipEventRecord(x->ev_join, x->sB);
-      if (e != hipSuccess) return e;
-      e = hipStreamWaitEvent(x->sA, x->ev_join, 0);
-      if (e != hipSuccess) return e;
-    }
-    launch_commit(A, 4);
-    return A.err;
   }
   // draft stage: layers 1..E + exit head; its last layer writes the other hExit buffer
   launch_stage<WT>(A, kDraft, 0, c.exit_layer, 0, kXDraft, true, kHExitNext);
@@ -653,6 +666,14 @@ int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *b, ppsd_ctx **
   } while (0)
   HIP_TRY_X(hipEventCreateWithFlags(&x->ev_fork, hipEventDisableTiming));
   HIP_TRY_X(hipEventCreateWithFlags(&x->ev_join, hipEventDisableTiming));
+  x->sx[0] = x->sA; x->sx[1] = x->sB;
+  if (cfg->mode == PPSD_MODE_PIPELINE) {
+    const int S = m.n_stages;
+    x->n_streams = cfg->pipeline_streams ? cfg->pipeline_streams : (S < kMaxStreams ? S : kMaxStreams);
+    if (x->n_streams > S) x->n_streams = S;
+    for (int i = 2; i < x->n_streams; ++i) HIP_TRY_X(hipStreamCreateWithFlags(&x->sx[i], hipStreamNonBlocking));
+    for (int i = 1; i < x->n_streams; ++i) HIP_TRY_X(hipEventCreateWithFlags(&x->ev_joinx[i], hipEventDisableTiming));
+  }
   HIP_TRY_X(hipEventCreate(&x->ev_t0));
   HIP_TRY_X(hipEventCreate(&x->ev_t1));
   HIP_TRY_X(hipHostMalloc((void **)&x->h_state, sizeof(DevState), hipHostMallocDefault));
@@ -695,10 +716,13 @@ void ppsd_free(ppsd_ctx *x) {
   if (!x) return;
   if (x->sA) (void)hipStreamSynchronize(x->sA);
   if (x->sB) (void)hipStreamSynchronize(x->sB);
+  for (int i = 2; i < kMaxStreams; ++i) if (x->sx[i]) (void)hipStreamSynchronize(x->sx[i]);
   if (x->g_step) (void)hipGraphExecDestroy(x->g_step);
   if (x->g_prefill) (void)hipGraphExecDestroy(x->g_prefill);
   if (x->ev_fork) (void)hipEventDestroy(x->ev_fork);
   if (x->ev_join) (void)hipEventDestroy(x->ev_join);
+  for (int i = 0; i < kMaxStreams; ++i) if (x->ev_joinx[i]) (void)hipEventDestroy(x->ev_joinx[i]);
+  for (int i = 2; i < kMaxStreams; ++i) if (x->sx[i]) (void)hipStreamDestroy(x->sx[i]);
   if (x->ev_t0) (void)hipEventDestroy(x->ev_t0);
   if (x->ev_t1) (void)hipEventDestroy(x->ev_t1);
   for (hipEvent_t e : x->tk_events) (void)hipEventDestroy(e);

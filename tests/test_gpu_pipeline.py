@@ -104,7 +104,10 @@ def test_pipeline_is_resumable_and_graph_replay_equals_direct_launch(P):
     Wg = to_device(W, "cuda")
     a = _run(P, w, Wg, prompt, calls, P.MODE_PIPELINE, use_graph=True)
     b = _run(P, w, Wg, prompt, calls, P.MODE_PIPELINE, use_graph=False)
-    c = _run(P, w, Wg, prompt, [sum(calls)], P.MODE_PIPELINE, use_graph=True)
+    c = _run(P, w, Wg, prompt, [sum(calls)], P.MODE_PIPELINE, use_graph=True, pipeline_streams=2)
+    for ns in (3, 4):      # the stages of a tick spread over more streams: same arithmetic, same result
+        e = _run(P, w, Wg, prompt, [sum(calls)], P.MODE_PIPELINE, pipeline_streams=ns)
+        assert e["tokens"] == toks and torch.equal(e["logits"], a["logits"])
     for r in (a, b):
         assert r["tokens"] == toks and r["drafts"] == [-1] + compared
         for got, want in zip(r["stats"], snaps):       # the counters agree at every call boundary
