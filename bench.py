@@ -108,7 +108,8 @@ def c3_grid_report(args, torch, S, P):
     for w in S.c3_grid():
         W = S.make_weights(w, device="cuda")
         prompt = S.make_prompt(w)
-        n, max_seq = w.decode_len, w.prompt_len + w.decode_len + 2
+        n_stages = -(-w.n_layers // w.exit_layer)
+        n, max_seq = w.decode_len, w.prompt_len + 1 + w.decode_len + max(1, n_stages - 1)
         ab = algorithmic_bytes(w, w.prompt_len + 1 + n / 2.0)
         if vanilla_tps is None:          # depends on the shape only
             ss = P.Session(w, W, max_seq=max_seq, mode=P.MODE_VANILLA, engine=engine)
@@ -118,11 +119,20 @@ def c3_grid_report(args, torch, S, P):
         ss = P.Session(w, W, max_seq=max_seq, mode=P.MODE_OVERLAP, engine=engine)
         t, st, _ = run_generations(ss, prompt, n, args.steps, args.warmup, torch)
         ss.close()
-        tps = args.steps * n / sum(t)
+        tps2 = args.steps * n / sum(t)
         alpha = st["accepted"] / st["drafts_compared"]
+        tps3 = None
+        if engine == P.ENGINE_STREAMS and n_stages <= 16:
+            ss = P.Session(w, W, max_seq=max_seq, mode=P.MODE_PIPELINE, engine=engine)
+            t, _, _ = run_generations(ss, prompt, n, args.steps, args.warmup, torch)
+            ss.close()
+            tps3 = args.steps * n / sum(t)
+        tps = max(tps2, tps3 or 0.0)
         cells_out.append({
             "cell": w.name, "exit_layer": w.exit_layer, "damp": w.damp, "acceptance_rate": alpha, "tokens_per_s": tps,
             "speedup_vs_vanilla_gpu": tps / vanilla_tps,
+            "two_stage": {"tokens_per_s": tps2, "speedup": tps2 / vanilla_tps},
+            "pipeline": {"stages": n_stages, "tokens_per_s": tps3, "speedup": tps3 and tps3 / vanilla_tps},
             "byte_model_ratio": ab["vanilla"] / (ab["accept_step"] + (1 - alpha) * ab["reject_extra"]),
             "paper_eq7_gain_one_gpu_per_stage": M.ppsd_gain(alpha, w.exit_layer, w.n_layers)})
         del W

@@ -140,6 +140,14 @@ __device__ __forceinline__ uint4 ld16_stream_global(const void *base, uint32_t b
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+// Hand-over of a few values between workgroups that are running at the same time (they may sit
+// on different L2 slices, which are not coherent with each other): relaxed atomic accesses at
+// agent scope go past the local L2, so no cache-wide write-back or invalidate is needed.  The
+// producer calls stores_done() in every wave, then a workgroup barrier, and only then signals.
+__device__ __forceinline__ float ld_agent(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void st_agent(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void stores_done() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // Values that are the same in every lane but arrive through vector loads: pin them to scalars.
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 template <typename T>

@@ -200,36 +200,40 @@ __device__ __forceinline__ void attn_unit(const Common &c, const int32_t *ptab, 
       aout[head * HD + dim] = A / L;
     } else {
       float *pr = partials + ((size_t)head * n_splits + split) * REC;
-      if (dim == 0) { pr[0] = M; pr[1] = L; }
-      pr[2 + dim] = A;
+      if (dim == 0) { st_agent(pr, M); st_agent(pr + 1, L); }
+      st_agent(pr + 2 + dim, A);
     }
   }
   if (n_splits > 1) {
-    // last workgroup of this KV head merges the splits
-    __threadfence();
+    // The last workgroup of this KV head to get here merges the splits.  The hand-over between
+    // workgroups (other compute units, other L2 slices) uses no cache-wide fence: the partials are
+    // written and read with agent-scope accesses, every wave waits for its own stores to complete,
+    // and only then does the workgroup count itself in.  (A release fence per workgroup writes the
+    // whole L2 back; measured, it costs more than the attention itself.)
+    stores_done();
     __syncthreads();
     if (tid == 0) {
-      const int prev = atomicAdd(&counters[kvh], 1);
+      const int prev = __hip_atomic_fetch_add(&counters[kvh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       *s_last = (prev == n_splits - 1);
     }
     __syncthreads();
     if (*s_last) {
-      __threadfence();
       for (int o = tid; o < G * HD; o += BLOCK) {
         const int g = o / HD, dim = o % HD;
         const int head = kvh * G + g;
         const float *pr = partials + (size_t)head * n_splits * REC;
         float M = kNegBig;
-        for (int s = 0; s < n_splits; ++s) M = fmaxf(M, __builtin_nontemporal_load(pr + s * REC));
+        for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ld_agent(pr + s * REC));
         float L = 0.f, A = 0.f;
         for (int s = 0; s < n_splits; ++s) {
-          const float w = __expf(__builtin_nontemporal_load(pr + s * REC) - M);
-          L = fmaf(__builtin_nontemporal_load(pr + s * REC + 1), w, L);
-          A = fmaf(__builtin_nontemporal_load(pr + s * REC + 2 + dim), w, A);
+          const float w = __expf(ld_agent(pr + s * REC) - M);
+          L = fmaf(ld_agent(pr + s * REC + 1), w, L);
+          A = fmaf(ld_agent(pr + s * REC + 2 + dim), w, A);
         }
         aout[head * HD + dim] = A / L;
       }
-      if (tid == 0) counters[kvh] = 0;   // ready for the next use (a later launch or a later phase)
+      // ready for the next use (a later launch or a later phase)
+      if (tid == 0) __hip_atomic_store(&counters[kvh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
   __syncthreads();   // merge / s_last may be reused by the caller
