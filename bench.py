@@ -163,6 +163,7 @@ def main():
     ap.add_argument("--engine", default="streams", choices=["streams", "persistent"])
     ap.add_argument("--pipeline-streams", type=int, default=0, help="streams of the pipeline mode (0 = library default)")
     ap.add_argument("--wgs-per-cu", type=int, default=0, help="launch tuning of the weight-streaming kernels (0 = defaults)")
+    ap.add_argument("--attn-split", type=int, default=0, help="launch tuning: positions of capacity per attention split (0 = default)")
     ap.add_argument("--prefill-loop", action="store_true", help="prefill with the decode kernels, one position at a time")
     ap.add_argument("--prompt-len", type=int, default=None, help="override the workload's prompt length")
     ap.add_argument("--decode-len", type=int, default=None, help="override the workload's decode length")
@@ -224,7 +225,7 @@ def main():
             continue
         ss = P.Session(w, W, max_seq=max_seq, mode=mode, engine=engine, prefill_loop=args.prefill_loop,
                        pipeline_streams=args.pipeline_streams if mode == P.MODE_PIPELINE else 0,
-                       tune_wgs_per_cu=args.wgs_per_cu)
+                       tune_wgs_per_cu=args.wgs_per_cu, tune_attn_split=args.attn_split)
         times, st, toks = run_generations(ss, prompt, n, args.steps, args.warmup, torch)
         prefill_ms = min(ss.prefill_ms)
         ss.close()
@@ -259,7 +260,8 @@ def main():
                         peak=HBM_PEAK_GBPS, unit="GB/s", frac=gbps / HBM_PEAK_GBPS, traffic=None,
                         avg_launch_us=dur_ms * 1e3, bytes_per_launch=moved)
     elif not args.no_kernel_timing:
-        ss = P.Session(w, W, max_seq=max_seq, mode=P.MODE_VANILLA, use_graph=False, time_kernels=True)
+        ss = P.Session(w, W, max_seq=max_seq, mode=P.MODE_VANILLA, use_graph=False, time_kernels=True,
+                       tune_wgs_per_cu=args.wgs_per_cu, tune_attn_split=args.attn_split)
         ss.ppsd_prefill(prompt)
         ss.ppsd_decode(min(n, 32))
         kt = ss.kernel_times()

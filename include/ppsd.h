@@ -103,7 +103,10 @@ typedef struct {
                               priority) and destroyed by the library */
   int32_t tune_wgs_per_cu; /* launch tuning: workgroups per compute unit of the weight-streaming kernels,
                               1..4; 0 = the library's defaults (4; 2 for gate/up) */
-  int32_t reserved[3];     /* must be zero */
+  int32_t tune_attn_split; /* launch tuning: positions of capacity (max_seq) per attention split, >= 64; the
+                              number of splits is capped at 64.  0 = the library's default (one split up to
+                              512 positions, beyond that one per 512) */
+  int32_t reserved[2];     /* must be zero */
 } ppsd_config;
 
 /* DEVICE pointers, BORROWED.  Per-layer entries are HOST arrays of n_layers DEVICE pointers. */

@@ -30,7 +30,7 @@ class ppsd_config(C.Structure):
                [("rope_base", C.c_float), ("rms_eps", C.c_float), ("debug_logits", C.c_int32),
                 ("use_graph", C.c_int32), ("time_kernels", C.c_int32), ("engine", C.c_int32),
                 ("prefill_loop", C.c_int32), ("pipeline_streams", C.c_int32), ("tune_wgs_per_cu", C.c_int32),
-                ("reserved", C.c_int32 * 3)]
+                ("tune_attn_split", C.c_int32), ("reserved", C.c_int32 * 2)]
 
 
 class ppsd_buffers(C.Structure):
@@ -94,7 +94,8 @@ def _check(rc: int):
 
 def make_config(shape, max_seq: int, mode: int, kv_page_tokens: int = 16, debug_logits: int = 0,
                 use_graph: bool = True, time_kernels: bool = False, engine: int = ENGINE_STREAMS,
-                prefill_loop: bool = False, pipeline_streams: int = 0, tune_wgs_per_cu: int = 0) -> ppsd_config:
+                prefill_loop: bool = False, pipeline_streams: int = 0, tune_wgs_per_cu: int = 0,
+                tune_attn_split: int = 0) -> ppsd_config:
     cfg = ppsd_config()
     for n in ("n_layers", "exit_layer", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab"):
         setattr(cfg, n, int(getattr(shape, n)))
@@ -106,6 +107,7 @@ def make_config(shape, max_seq: int, mode: int, kv_page_tokens: int = 16, debug_
     cfg.prefill_loop = int(prefill_loop)
     cfg.pipeline_streams = int(pipeline_streams)
     cfg.tune_wgs_per_cu = int(tune_wgs_per_cu)
+    cfg.tune_attn_split = int(tune_attn_split)
     return cfg
 
 
@@ -135,12 +137,13 @@ class Session:
     def __init__(self, shape, weights: dict, max_seq: int, mode: int = MODE_OVERLAP, kv_page_tokens: int = 16,
                  debug_logits: int = 0, use_graph: bool = True, time_kernels: bool = False,
                  page_table: Optional[Sequence[int]] = None, engine: int = ENGINE_STREAMS,
-                 prefill_loop: bool = False, pipeline_streams: int = 0, tune_wgs_per_cu: int = 0):
+                 prefill_loop: bool = False, pipeline_streams: int = 0, tune_wgs_per_cu: int = 0,
+                 tune_attn_split: int = 0):
         self.lib = load_library()
         self.shape = shape
         self.weights = weights
         self.cfg = make_config(shape, max_seq, mode, kv_page_tokens, debug_logits, use_graph, time_kernels, engine,
-                               prefill_loop, pipeline_streams, tune_wgs_per_cu)
+                               prefill_loop, pipeline_streams, tune_wgs_per_cu, tune_attn_split)
         nbytes = ppsd_workspace_bytes(self.cfg)
         dev = weights["embed"].device
         if dev.type != "cuda":

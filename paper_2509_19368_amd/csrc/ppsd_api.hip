@@ -40,8 +40,10 @@ int fail(int code, const char *fmt, ...) {
 constexpr size_t kAlign = 256;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
-constexpr int kSplitPositions = 512;   // attention: one split per this many positions of capacity
-constexpr int kMaxSplits = 32;         // attention splits along the sequence (both engines)
+constexpr int kOneSplitUpTo = 512;     // attention: a single split up to this capacity (max_seq)
+constexpr int kSplitPositions = 512;   // beyond it, one split per this many positions of capacity (measured at
+                                       // 8192 positions, 8 KV heads: 512 -> 25 us, 256 -> 26 us, 128 -> 28.5 us)
+constexpr int kMaxSplits = 64;         // attention splits along the sequence (both engines)
 constexpr int kMaxStreams = 4;         // streams the stages of a pipeline tick are spread over
 
 enum Kind { kKQkv = 0, kKAttn, kKOproj, kKGateUp, kKDown, kKHead, kKCommit };
@@ -89,7 +91,8 @@ bool valid_config(const ppsd_config *c, const char **why) {
   }
   REJECT(c->pipeline_streams < 0 || c->pipeline_streams == 1 || c->pipeline_streams > kMaxStreams, "pipeline_streams must be 0 (default) or 2..4");
   REJECT(c->tune_wgs_per_cu < 0 || c->tune_wgs_per_cu > 4, "tune_wgs_per_cu must be 0..4");
-  for (int k = 0; k < 3; ++k) REJECT(c->reserved[k] != 0, "reserved fields must be zero");
+  REJECT(c->tune_attn_split < 0 || (c->tune_attn_split > 0 && c->tune_attn_split < 64), "tune_attn_split must be 0 or >= 64");
+  for (int k = 0; k < 2; ++k) REJECT(c->reserved[k] != 0, "reserved fields must be zero");
 #undef REJECT
   return true;
 }
@@ -104,7 +107,8 @@ Layout make_layout(const ppsd_config *c) {
   Layout L{};
   const size_t es = c->dtype == PPSD_FP32 ? 4 : 2;
   L.n_pages = (c->max_seq + c->kv_page_tokens - 1) / c->kv_page_tokens;
-  int ns = (c->max_seq + kSplitPositions - 1) / kSplitPositions;
+  const int per_split = c->tune_attn_split > 0 ? c->tune_attn_split : kSplitPositions;
+  int ns = c->max_seq <= kOneSplitUpTo && c->tune_attn_split == 0 ? 1 : (c->max_seq + per_split - 1) / per_split;
   L.n_splits = ns < 1 ? 1 : (ns > kMaxSplits ? kMaxSplits : ns);
   L.head_blocks = kMaxWorkgroups;   // capacity of the candidate arrays; the live count is set at load
   size_t off = 0;
@@ -123,7 +127,7 @@ Layout make_layout(const ppsd_config *c) {
     L.a[s] = take(4 * nq);
     L.mbuf[s] = take(4ull * c->d_ffn);
     L.partials[s] = take(4ull * c->n_heads * kMaxSplits * (c->head_dim + 2));
-    L.counters[s] = take(4ull * c->n_kv_heads);
+    L.counters[s] = take(4ull * kCounterStride * c->n_kv_heads);
   }
   const size_t n_cand = kMaxWorkgroups;
   L.cand_lm = take(8ull * n_cand);

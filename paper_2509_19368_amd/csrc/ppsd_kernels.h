@@ -104,6 +104,9 @@ __global__ __launch_bounds__(kGBlock) void k_qkv(Common c, int role, int layer, 
 // groups are merged through LDS (`merge`, BLOCK/GS * G * (HD+2) floats) in a fixed order.  With
 // several splits the last workgroup to finish a KV head merges the splits, also in fixed order.
 // Must be called by all BLOCK threads of the workgroup; ends with the workgroup synchronised.
+constexpr int kCounterStride = 64;   // ints between the arrival counters of two KV heads: atomics on one
+                                    // cache line serialise, each head gets a line of its own
+constexpr int kMergeBatch = 16;   // splits whose partial results the merging workgroup loads at once
 template <typename WT, int HD, int G, int BLOCK>
 __device__ __forceinline__ void attn_unit(const Common &c, const int32_t *ptab, int layer, int pos, int kvh,
                                           int split, int n_splits, const float *q, float *aout, float *partials,
@@ -213,7 +216,7 @@ __device__ __forceinline__ void attn_unit(const Common &c, const int32_t *ptab, 
     stores_done();
     __syncthreads();
     if (tid == 0) {
-      const int prev = __hip_atomic_fetch_add(&counters[kvh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const int prev = __hip_atomic_fetch_add(&counters[kvh * kCounterStride], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       *s_last = (prev == n_splits - 1);
     }
     __syncthreads();
@@ -222,18 +225,35 @@ __device__ __forceinline__ void attn_unit(const Common &c, const int32_t *ptab, 
         const int g = o / HD, dim = o % HD;
         const int head = kvh * G + g;
         const float *pr = partials + (size_t)head * n_splits * REC;
-        float M = kNegBig;
-        for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ld_agent(pr + s * REC));
-        float L = 0.f, A = 0.f;
-        for (int s = 0; s < n_splits; ++s) {
-          const float w = __expf(ld_agent(pr + s * REC) - M);
-          L = fmaf(ld_agent(pr + s * REC + 1), w, L);
-          A = fmaf(ld_agent(pr + s * REC + 2 + dim), w, A);
+        // splits in fixed order, kMergeBatch at a time so that their loads are in flight together
+        // (one round trip past the L2 per batch instead of one per split)
+        float M = kNegBig, L = 0.f, A = 0.f;
+        for (int s0 = 0; s0 < n_splits; s0 += kMergeBatch) {
+          float pm[kMergeBatch], pl[kMergeBatch], pa[kMergeBatch];
+#pragma unroll
+          for (int k = 0; k < kMergeBatch; ++k) {
+            const float *ps = pr + (size_t)min(s0 + k, n_splits - 1) * REC;
+            pm[k] = ld_agent(ps); pl[k] = ld_agent(ps + 1); pa[k] = ld_agent(ps + 2 + dim);
+          }
+          float Mn = M;
+#pragma unroll
+          for (int k = 0; k < kMergeBatch; ++k) if (s0 + k < n_splits) Mn = fmaxf(Mn, pm[k]);
+          const float corr = __expf(M - Mn);
+          L *= corr; A *= corr;
+#pragma unroll
+          for (int k = 0; k < kMergeBatch; ++k) {
+            if (s0 + k < n_splits) {
+              const float w = __expf(pm[k] - Mn);
+              L = fmaf(pl[k], w, L);
+              A = fmaf(pa[k], w, A);
+            }
+          }
+          M = Mn;
         }
         aout[head * HD + dim] = A / L;
       }
       // ready for the next use (a later launch or a later phase)
-      if (tid == 0) __hip_atomic_store(&counters[kvh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (tid == 0) __hip_atomic_store(&counters[kvh * kCounterStride], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
   __syncthreads();   // merge / s_last may be reused by the caller

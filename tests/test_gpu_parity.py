@@ -150,15 +150,21 @@ def test_long_context_splits_and_shuffled_pages(P, engine):
     want = O.greedy_decode(dec, prompt, w.decode_len + 1, keep_logits=True)
     Wg = to_device(W, "cuda")
     max_seq = 333 + 24 + 2
-    a = _gpu_run(P, w, Wg, prompt, w.decode_len, P.MODE_OVERLAP, max_seq=max_seq, kv_page_tokens=8, engine=engine)
+    # 64 positions of capacity per split: 6 splits here, 16 and 19 (more than one merge batch) below
+    a = _gpu_run(P, w, Wg, prompt, w.decode_len, P.MODE_OVERLAP, max_seq=max_seq, kv_page_tokens=8, engine=engine,
+                 tune_attn_split=64)
     n_pages = (max_seq + 7) // 8
     b = _gpu_run(P, w, Wg, prompt, w.decode_len, P.MODE_OVERLAP, max_seq=max_seq, kv_page_tokens=8,
-                 page_table=S.page_permutation(5, n_pages), engine=engine)
-    c = _gpu_run(P, w, Wg, prompt, w.decode_len, P.MODE_VANILLA, max_seq=1024, kv_page_tokens=64, engine=engine)
-    assert a["tokens"] == want.tokens == b["tokens"] == c["tokens"]
+                 page_table=S.page_permutation(5, n_pages), engine=engine, tune_attn_split=64)
+    c = _gpu_run(P, w, Wg, prompt, w.decode_len, P.MODE_VANILLA, max_seq=1024, kv_page_tokens=64, engine=engine,
+                 tune_attn_split=64)
+    d = _gpu_run(P, w, Wg, prompt, w.decode_len, P.MODE_VANILLA, max_seq=1200, kv_page_tokens=16, engine=engine,
+                 tune_attn_split=64)
+    e = _gpu_run(P, w, Wg, prompt, w.decode_len, P.MODE_VANILLA, max_seq=1024, kv_page_tokens=64, engine=engine)
+    assert a["tokens"] == want.tokens == b["tokens"] == c["tokens"] == d["tokens"] == e["tokens"]
     assert torch.equal(a["logits"], b["logits"])
     ref = torch.stack(want.logits)
-    for r in (a, c):
+    for r in (a, c, d, e):
         err = ((r["logits"].double() - ref).abs().max(dim=1).values / ref.abs().max(dim=1).values).max().item()
         assert err <= REL_TOL_FP32
 
