@@ -70,6 +70,13 @@ extern "C" {
                                      (PPSD_MODE_OVERLAP) or back to back (PPSD_MODE_SERIAL), weight
                                      loads software-pipelined across barriers.  Uses stream_draft only. */
 
+#define PPSD_MODE_EESD       4  /* draft-then-verify rounds of early-exit speculative decoding (Sec. 3.1, Eq. 4-5),
+                                   the method the pipeline is measured against: eesd_gamma draft steps (layers
+                                   1..E + exit head, one token each), then ONE pass of layers E+1..N + LM head
+                                   over the gamma + 1 drafted positions, every weight streamed once for all of
+                                   them; the accepted prefix plus the full model's next token are committed.
+                                   One stream (stream_draft).  Per-operation engine only, no time_kernels. */
+
 typedef struct ppsd_ctx ppsd_ctx;
 
 typedef struct {
@@ -106,7 +113,9 @@ typedef struct {
   int32_t tune_attn_split; /* launch tuning: positions of capacity (max_seq) per attention split, >= 64; the
                               number of splits is capped at 64.  0 = the library's default (one split up to
                               512 positions, beyond that one per 512) */
-  int32_t reserved[2];     /* must be zero */
+  int32_t eesd_gamma;      /* PPSD_MODE_EESD: drafts per round, 1..4; 0 = default (3).  (gamma + 1) * d_model
+                              floats must fit the LDS of a compute unit (150 KiB) */
+  int32_t reserved[1];     /* must be zero */
 } ppsd_config;
 
 /* DEVICE pointers, BORROWED.  Per-layer entries are HOST arrays of n_layers DEVICE pointers. */
@@ -147,6 +156,9 @@ typedef struct {
   int64_t pipeline_ticks;    /* ticks that did work; Eq. (7): committed + (S-1) * rejected, up to fill/drain */
   int64_t stage_runs;        /* stage executions summed over ticks */
   int64_t flushed_tokens;    /* speculative tokens in flight dropped by rejections (S-1 per rejection) */
+  /* PPSD_MODE_EESD only: rounds run; there drafts_compared counts drafts up to and including a round's first
+   * mismatch, accepted the accepted ones, rejected = kv_rollbacks the rounds that ended at a mismatch. */
+  int64_t eesd_rounds;
 } ppsd_stats_t;
 
 #define PPSD_N_KERNEL_KINDS 7   /* qkv, attention, o_proj, gate_up, down, head, commit */
@@ -172,8 +184,8 @@ int ppsd_prefill(ppsd_ctx *ctx, const int32_t *prompt, int32_t n_prompt, int32_t
  * One step drafts with layers 1..E + exit head and verifies with layers E+1..N + LM head
  * (Sec. 4.2); accept/reject and KV rollback happen on the device (Alg. 1).  Resumable: a second
  * call continues the same sequence, keeping the drafts in flight.  PPSD_ESTATE before prefill;
- * PPSD_ECAPACITY if the sequence plus the speculative positions (one; S-1 in PPSD_MODE_PIPELINE)
- * would pass max_seq. */
+ * PPSD_ECAPACITY if the sequence plus the speculative positions (one; S-1 in PPSD_MODE_PIPELINE;
+ * eesd_gamma in PPSD_MODE_EESD) would pass max_seq. */
 int ppsd_decode(ppsd_ctx *ctx, int32_t n_tokens, int32_t *out_tokens, int32_t *n_written);
 
 /* Copies the counters (HOST out). */

@@ -5,6 +5,6 @@ include/ppsd.h; this package is the thin ctypes binding over it.  There is no
 CPU fallback: importing the binding without the built library raises.
 """
 from .binding import (  # noqa: F401
-    ENGINE_PERSISTENT, ENGINE_STREAMS, MODE_OVERLAP, MODE_PIPELINE, MODE_SERIAL, MODE_VANILLA, KERNEL_KINDS, PpsdError, Session,
+    ENGINE_PERSISTENT, ENGINE_STREAMS, MODE_EESD, MODE_OVERLAP, MODE_PIPELINE, MODE_SERIAL, MODE_VANILLA, KERNEL_KINDS, PpsdError, Session,
     hbm_read_probe, library_path, load_library, ppsd_workspace_bytes,
 )

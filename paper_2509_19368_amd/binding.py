@@ -13,7 +13,7 @@ import torch
 
 from .build import LIB_PATH
 
-MODE_VANILLA, MODE_SERIAL, MODE_OVERLAP, MODE_PIPELINE = 0, 1, 2, 3
+MODE_VANILLA, MODE_SERIAL, MODE_OVERLAP, MODE_PIPELINE, MODE_EESD = 0, 1, 2, 3, 4
 ENGINE_STREAMS, ENGINE_PERSISTENT = 0, 1
 KERNEL_KINDS = ("qkv", "attention", "o_proj", "gate_up", "down", "head", "commit")
 
@@ -30,7 +30,7 @@ class ppsd_config(C.Structure):
                [("rope_base", C.c_float), ("rms_eps", C.c_float), ("debug_logits", C.c_int32),
                 ("use_graph", C.c_int32), ("time_kernels", C.c_int32), ("engine", C.c_int32),
                 ("prefill_loop", C.c_int32), ("pipeline_streams", C.c_int32), ("tune_wgs_per_cu", C.c_int32),
-                ("tune_attn_split", C.c_int32), ("reserved", C.c_int32 * 2)]
+                ("tune_attn_split", C.c_int32), ("eesd_gamma", C.c_int32), ("reserved", C.c_int32 * 1)]
 
 
 class ppsd_buffers(C.Structure):
@@ -44,7 +44,7 @@ class ppsd_stats_t(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("committed", "drafts_compared", "accepted", "rejected", "steps_overlapped",
                                           "steps_draft_only", "kv_rollbacks", "steps_launched")] + \
                [("device_ms", C.c_double)] + \
-               [(n, C.c_int64) for n in ("pipeline_ticks", "stage_runs", "flushed_tokens")]
+               [(n, C.c_int64) for n in ("pipeline_ticks", "stage_runs", "flushed_tokens", "eesd_rounds")]
 
 
 class ppsd_kernel_times_t(C.Structure):
@@ -95,7 +95,7 @@ def _check(rc: int):
 def make_config(shape, max_seq: int, mode: int, kv_page_tokens: int = 16, debug_logits: int = 0,
                 use_graph: bool = True, time_kernels: bool = False, engine: int = ENGINE_STREAMS,
                 prefill_loop: bool = False, pipeline_streams: int = 0, tune_wgs_per_cu: int = 0,
-                tune_attn_split: int = 0) -> ppsd_config:
+                tune_attn_split: int = 0, eesd_gamma: int = 0) -> ppsd_config:
     cfg = ppsd_config()
     for n in ("n_layers", "exit_layer", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab"):
         setattr(cfg, n, int(getattr(shape, n)))
@@ -108,6 +108,7 @@ def make_config(shape, max_seq: int, mode: int, kv_page_tokens: int = 16, debug_
     cfg.pipeline_streams = int(pipeline_streams)
     cfg.tune_wgs_per_cu = int(tune_wgs_per_cu)
     cfg.tune_attn_split = int(tune_attn_split)
+    cfg.eesd_gamma = int(eesd_gamma)
     return cfg
 
 
@@ -138,12 +139,12 @@ class Session:
                  debug_logits: int = 0, use_graph: bool = True, time_kernels: bool = False,
                  page_table: Optional[Sequence[int]] = None, engine: int = ENGINE_STREAMS,
                  prefill_loop: bool = False, pipeline_streams: int = 0, tune_wgs_per_cu: int = 0,
-                 tune_attn_split: int = 0):
+                 tune_attn_split: int = 0, eesd_gamma: int = 0):
         self.lib = load_library()
         self.shape = shape
         self.weights = weights
         self.cfg = make_config(shape, max_seq, mode, kv_page_tokens, debug_logits, use_graph, time_kernels, engine,
-                               prefill_loop, pipeline_streams, tune_wgs_per_cu, tune_attn_split)
+                               prefill_loop, pipeline_streams, tune_wgs_per_cu, tune_attn_split, eesd_gamma)
         nbytes = ppsd_workspace_bytes(self.cfg)
         dev = weights["embed"].device
         if dev.type != "cuda":

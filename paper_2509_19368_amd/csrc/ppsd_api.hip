@@ -14,6 +14,7 @@
 #include "../../include/ppsd.h"
 #include "ppsd_mega.h"
 #include "ppsd_prefill.h"
+#include "ppsd_batch.h"
 
 using namespace ppsd;
 
@@ -44,6 +45,9 @@ constexpr int kOneSplitUpTo = 512;     // attention: a single split up to this c
 constexpr int kSplitPositions = 512;   // beyond it, one split per this many positions of capacity (measured at
                                        // 8192 positions, 8 KV heads: 512 -> 25 us, 256 -> 26 us, 128 -> 28.5 us)
 constexpr int kMaxSplits = 64;         // attention splits along the sequence (both engines)
+constexpr int kDefaultGamma = 3;       // drafts per round of PPSD_MODE_EESD
+constexpr size_t kBatchLdsMax = 150 * 1024;   // staged input vectors of a batched kernel: at most this much LDS
+constexpr size_t kBatchSlabBytes = 64 * 1024; // o_proj / down of the batched pass: column slabs of at most this much
 constexpr int kMaxStreams = 4;         // streams the stages of a pipeline tick are spread over
 
 enum Kind { kKQkv = 0, kKAttn, kKOproj, kKGateUp, kKDown, kKHead, kKCommit };
@@ -53,6 +57,7 @@ struct Layout {
   size_t q[kMaxStreams], a[kMaxStreams], mbuf[kMaxStreams], partials[kMaxStreams], counters[kMaxStreams], cand_lm, cand_exit, sink, logits, kv;
   size_t layer_ptrs, bar, abort_flag, trace, cand_counts;
   size_t pf_x, pf_q, pf_ao, pf_m, pf_rs;   // MFMA prefill chunk buffers (0 bytes when not used)
+  size_t qb, ab, mb, partials_b, counters_b, cand_b;   // batched verify pass (0 bytes unless PPSD_MODE_EESD)
   bool pf;
   size_t total;
   int n_pages, n_splits, head_blocks;
@@ -74,7 +79,7 @@ bool valid_config(const ppsd_config *c, const char **why) {
   REJECT(c->max_seq < 3, "max_seq too small");
   REJECT(c->kv_page_tokens != 8 && c->kv_page_tokens != 16 && c->kv_page_tokens != 32 && c->kv_page_tokens != 64,
          "kv_page_tokens must be 8, 16, 32 or 64");
-  REJECT(c->mode < 0 || c->mode > 3, "mode must be 0, 1, 2 or 3");
+  REJECT(c->mode < 0 || c->mode > 4, "mode must be 0..4");
   REJECT(!(c->rope_base > 1.0f) || !(c->rms_eps >= 0.0f), "bad rope_base / rms_eps");
   REJECT(c->debug_logits < 0, "debug_logits < 0");
   REJECT((size_t)c->d_ffn * 4 > 64 * 1024 || (size_t)c->d_model * 4 > 64 * 1024 ||
@@ -91,8 +96,15 @@ bool valid_config(const ppsd_config *c, const char **why) {
   }
   REJECT(c->pipeline_streams < 0 || c->pipeline_streams == 1 || c->pipeline_streams > kMaxStreams, "pipeline_streams must be 0 (default) or 2..4");
   REJECT(c->tune_wgs_per_cu < 0 || c->tune_wgs_per_cu > 4, "tune_wgs_per_cu must be 0..4");
+  REJECT(c->eesd_gamma < 0 || c->eesd_gamma > kMaxGamma, "eesd_gamma must be 0 (default) or 1..4");
+  if (c->mode == PPSD_MODE_EESD) {
+    REJECT(c->engine != PPSD_ENGINE_STREAMS, "draft-then-verify rounds run on the per-operation engine only");
+    REJECT(c->time_kernels, "time_kernels is not available with draft-then-verify rounds");
+    const int B = (c->eesd_gamma ? c->eesd_gamma : kDefaultGamma) + 1;
+    REJECT((size_t)B * c->d_model * 4 > kBatchLdsMax, "gamma + 1 input vectors of d_model floats exceed the LDS of a compute unit");
+  }
   REJECT(c->tune_attn_split < 0 || (c->tune_attn_split > 0 && c->tune_attn_split < 64), "tune_attn_split must be 0 or >= 64");
-  for (int k = 0; k < 2; ++k) REJECT(c->reserved[k] != 0, "reserved fields must be zero");
+  for (int k = 0; k < 1; ++k) REJECT(c->reserved[k] != 0, "reserved fields must be zero");
 #undef REJECT
   return true;
 }
@@ -144,6 +156,13 @@ Layout make_layout(const ppsd_config *c) {
   L.pf_ao = take(4ull * pc * nq);
   L.pf_m = take(4ull * pc * c->d_ffn);
   L.pf_rs = take(4ull * pc);
+  const size_t nb = c->mode == PPSD_MODE_EESD ? kMaxBatch : 0;
+  L.qb = take(4ull * nb * nq);
+  L.ab = take(4ull * nb * nq);
+  L.mb = take(4ull * nb * c->d_ffn);
+  L.partials_b = take(4ull * nb * c->n_heads * kMaxSplits * (c->head_dim + 2));
+  L.counters_b = take(4ull * nb * kCounterStride * c->n_kv_heads);
+  L.cand_b = take(8ull * nb * n_cand);
   L.sink = take(256);
   L.logits = take(4ull * c->debug_logits * c->vocab);
   L.kv = take((size_t)c->n_layers * L.n_pages * c->n_kv_heads * 2 * c->kv_page_tokens * c->head_dim * es);
@@ -163,6 +182,7 @@ struct ppsd_ctx {
   hipStream_t sA, sB;
   hipStream_t sx[kMaxStreams] = {};     // pipeline ticks: sx[0] = sA, sx[1] = sB, the rest created here
   int n_streams = 2;
+  int gamma = 0;                        // drafts per round (PPSD_MODE_EESD)
   hipEvent_t ev_fork, ev_join, ev_t0, ev_t1;
   hipEvent_t ev_joinx[kMaxStreams] = {};
   hipGraphExec_t g_step = nullptr;      // decode step in cfg.mode
@@ -304,11 +324,118 @@ void launch_stage(Launcher &L, int role, int lo, int hi, int stage, int xin_firs
                      from_embed && l == lo, xwork);
 }
 
+// ---------------------------------------------------------------- draft-then-verify round
+// Workgroups of a batched kernel: as many as stay resident with `lds` bytes of staged input each.
+int batch_grid(const ppsd_ctx *x, int n_tasks, size_t lds, int wgs_per_cu) {
+  int fit = (int)((160 * 1024) / (lds + 1024));
+  if (fit < 1) fit = 1;
+  if (fit < wgs_per_cu) wgs_per_cu = fit;
+  return x->gemv_grid(n_tasks, wgs_per_cu);
+}
+
+template <typename WT, int B>
+void launch_proj_b(Launcher &L, int kind, const float *vin, int C, const WT *W, int resid_slot0, int out_slot0) {
+  ppsd_ctx *x = L.x;
+  const int d = x->cfg.d_model;
+  const int blk = 512;                                  // slabs end on column-block boundaries
+  int n_slabs = (int)(((size_t)B * C * 4 + kBatchSlabBytes - 1) / kBatchSlabBytes);
+  int Cs = ((C + n_slabs - 1) / n_slabs + blk - 1) / blk * blk;
+  if ((size_t)B * Cs * 4 > kBatchLdsMax) Cs = (int)(kBatchLdsMax / (4 * B)) / blk * blk;
+  for (int c0 = 0; c0 < C; c0 += Cs) {
+    const int w = C - c0 < Cs ? C - c0 : Cs;
+    const size_t lds = (size_t)B * w * 4;
+    L.before(kind);
+    hipLaunchKernelGGL((k_proj_resid_b<WT, B>), dim3(batch_grid(x, (d + 1) / 2, lds, kGemvWgsPerCu)), dim3(kGBlock), lds, L.s,
+                       x->cm, vin, C, c0, w, W, d, c0 == 0 ? resid_slot0 : out_slot0, out_slot0);
+    L.after();
+  }
+}
+
+template <typename WT, int B>
+void launch_verify_batch(Launcher &L) {
+  ppsd_ctx *x = L.x;
+  const ppsd_config &c = x->cfg;
+  const Common &cm = x->cm;
+  const int d = c.d_model, f = c.d_ffn, nq = c.n_heads * c.head_dim;
+  float *q = at<float>(x, x->lay.qb), *a = at<float>(x, x->lay.ab), *mb = at<float>(x, x->lay.mb);
+  float *part = at<float>(x, x->lay.partials_b);
+  int *cnt = at<int>(x, x->lay.counters_b);
+  const size_t lds_d = (size_t)B * d * 4;
+  const int total_pairs = (c.n_heads + 2 * c.n_kv_heads) * (c.head_dim / 2);
+  const int G = c.n_heads / c.n_kv_heads;
+  for (int l = c.exit_layer; l < c.n_layers; ++l) {
+    const int xin0 = l == c.exit_layer ? kXBatchInSlot0 : kXBatchWorkSlot0;
+    L.before(kKQkv);
+    hipLaunchKernelGGL((k_qkv_b<WT, B>), dim3(batch_grid(x, total_pairs, lds_d, kGemvWgsPerCu)), dim3(kGBlock), lds_d, L.s, cm, l,
+                       xin0, (const float *)x->attn_norm[l], (const WT *)x->wqkv[l], q);
+    L.after();
+    const dim3 agrid(c.n_kv_heads, x->lay.n_splits, B);
+    L.before(kKAttn);
+#define ATTNB(HD, GG) hipLaunchKernelGGL((k_attn_b<WT, HD, GG>), agrid, dim3(kGBlock), 0, L.s, cm, l, (const float *)q, a, part, cnt)
+    if (c.head_dim == 64) { if (G == 1) ATTNB(64, 1); else if (G == 2) ATTNB(64, 2); else ATTNB(64, 4); }
+    else { if (G == 1) ATTNB(128, 1); else if (G == 2) ATTNB(128, 2); else ATTNB(128, 4); }
+#undef ATTNB
+    L.after();
+    launch_proj_b<WT, B>(L, kKOproj, a, nq, (const WT *)x->wo[l], xin0, kXBatchWorkSlot0);
+    L.before(kKGateUp);
+    hipLaunchKernelGGL((k_gate_up_b<WT, B>), dim3(batch_grid(x, f, lds_d, kGateUpWgsPerCu)), dim3(kGBlock), lds_d, L.s, cm,
+                       kXBatchWorkSlot0, (const float *)x->mlp_norm[l], (const WT *)x->wgu[l], mb);
+    L.after();
+    launch_proj_b<WT, B>(L, kKDown, mb, f, (const WT *)x->wdown[l], kXBatchWorkSlot0, kXBatchWorkSlot0);
+  }
+  float *logits = c.debug_logits > 0 ? at<float>(x, x->lay.logits) : nullptr;
+  L.before(kKHead);
+  hipLaunchKernelGGL((k_head_b<WT, B>), dim3(cm.dm.head_blocks), dim3(kGBlock), lds_d, L.s, cm, kXBatchWorkSlot0,
+                     (const float *)x->final_norm, (const WT *)x->lm_head, at<float2>(x, x->lay.cand_b), logits);
+  L.after();
+}
+
+// Largest dynamic LDS the batched kernels of this B may be launched with.
+template <typename WT, int B>
+hipError_t allow_batch_lds() {
+  const int bytes = (int)kBatchLdsMax;
+  hipError_t e = hipFuncSetAttribute((const void *)k_qkv_b<WT, B>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_gate_up_b<WT, B>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_head_b<WT, B>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_proj_resid_b<WT, B>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  return e;
+}
+
+template <typename WT>
+hipError_t enqueue_eesd_round(ppsd_ctx *x) {
+  const ppsd_config &c = x->cfg;
+  Launcher A{x, x->sA, false};
+  const int g = x->gamma;
+  // gamma draft steps (layers 1..E + exit head on one token each), then the layer-E hidden state of
+  // the last draft, each left in its batch slot
+  for (int j = 0; j <= g; ++j) {
+    launch_stage<WT>(A, kEesdDraft0 + j, 0, c.exit_layer, 0, kXStageWork0, true, kXBatchIn0 + j, kXStageWork0);
+    if (j < g) {
+      launch_head<WT>(A, kEesdDraft0 + j, kXBatchIn0 + j, false);
+      A.before(kKCommit);
+      hipLaunchKernelGGL(k_eesd_pick, dim3(1), dim3(kBlock), 0, A.s, x->cm, at<const float2>(x, x->lay.cand_exit), j);
+      A.after();
+    }
+  }
+  switch (g + 1) {
+    case 2: launch_verify_batch<WT, 2>(A); break;
+    case 3: launch_verify_batch<WT, 3>(A); break;
+    case 4: launch_verify_batch<WT, 4>(A); break;
+    default: launch_verify_batch<WT, 5>(A); break;
+  }
+  A.before(kKCommit);
+  hipLaunchKernelGGL(k_eesd_commit, dim3(1), dim3(kBlock), 0, A.s, x->cm, at<const float2>(x, x->lay.cand_b),
+                     at<int32_t>(x, x->lay.out_tokens), at<int32_t>(x, x->lay.drafts), g);
+  A.after();
+  return A.err;
+}
+
 // One decode step in the given mode.  With two_streams the verify stage goes to stream B between
 // a fork event and a join event (also valid under stream capture).
 template <typename WT>
 hipError_t enqueue_step(ppsd_ctx *x, int mode, bool two_streams, bool timed) {
   const ppsd_config &c = x->cfg;
+  if (mode == PPSD_MODE_EESD) return enqueue_eesd_round<WT>(x);
   Launcher A{x, x->sA, timed};
   if (mode == PPSD_MODE_VANILLA) {
     launch_stage<WT>(A, kVanilla, 0, c.n_layers, 0, kXDraft, true, kXDraft);
@@ -671,6 +798,18 @@ int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *b, ppsd_ctx **
   HIP_TRY_X(hipEventCreateWithFlags(&x->ev_fork, hipEventDisableTiming));
   HIP_TRY_X(hipEventCreateWithFlags(&x->ev_join, hipEventDisableTiming));
   x->sx[0] = x->sA; x->sx[1] = x->sB;
+  if (cfg->mode == PPSD_MODE_EESD) {
+    x->gamma = cfg->eesd_gamma ? cfg->eesd_gamma : kDefaultGamma;
+    hipError_t e = hipSuccess;
+    const bool f32 = cfg->dtype == PPSD_FP32;
+    switch (x->gamma + 1) {
+      case 2: e = f32 ? allow_batch_lds<float, 2>() : allow_batch_lds<bf16_t, 2>(); break;
+      case 3: e = f32 ? allow_batch_lds<float, 3>() : allow_batch_lds<bf16_t, 3>(); break;
+      case 4: e = f32 ? allow_batch_lds<float, 4>() : allow_batch_lds<bf16_t, 4>(); break;
+      default: e = f32 ? allow_batch_lds<float, 5>() : allow_batch_lds<bf16_t, 5>(); break;
+    }
+    HIP_TRY_X(e);
+  }
   if (cfg->mode == PPSD_MODE_PIPELINE) {
     const int S = m.n_stages;
     x->n_streams = cfg->pipeline_streams ? cfg->pipeline_streams : (S < kMaxStreams ? S : kMaxStreams);
@@ -706,7 +845,7 @@ int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *b, ppsd_ctx **
     int rc = mega_setup(x);
     if (rc != PPSD_OK) return cleanup(rc);
   } else if (cfg->use_graph && !cfg->time_kernels) {
-    int rc = capture(x, &x->g_step, [&] { return enqueue_step_any(x, cfg->mode, cfg->mode >= PPSD_MODE_OVERLAP, false); });
+    int rc = capture(x, &x->g_step, [&] { return enqueue_step_any(x, cfg->mode, cfg->mode == PPSD_MODE_OVERLAP || cfg->mode == PPSD_MODE_PIPELINE, false); });
     if (rc != PPSD_OK) return cleanup(rc);
     rc = capture(x, &x->g_prefill, [&] { return enqueue_prefill_any(x, false, false); });
     if (rc != PPSD_OK) return cleanup(rc);
@@ -783,13 +922,13 @@ int ppsd_decode(ppsd_ctx *x, int32_t n_tokens, int32_t *out_tokens, int32_t *n_w
   // positions 0..host_len-1 are committed; committing n more needs rows up to host_len+n-1 plus
   // the speculative rows written ahead of the last committed token: one by the draft stage, or
   // one per stage in front of the last one in the full pipeline schedule
-  const int spec = x->cfg.mode == PPSD_MODE_PIPELINE ? x->cm.dm.n_stages - 1 : 1;
+  const int spec = x->cfg.mode == PPSD_MODE_PIPELINE ? x->cm.dm.n_stages - 1 : x->cfg.mode == PPSD_MODE_EESD ? x->gamma : 1;
   if ((int64_t)x->host_len + n_tokens + spec > x->cfg.max_seq)
     return fail(PPSD_ECAPACITY, "%d committed + %d new + %d speculative position(s) exceed max_seq %d", x->host_len, n_tokens,
                 spec, x->cfg.max_seq);
   const ppsd_config &c = x->cfg;
   const bool timed = c.time_kernels != 0;
-  const bool two = c.mode >= PPSD_MODE_OVERLAP && !timed;
+  const bool two = (c.mode == PPSD_MODE_OVERLAP || c.mode == PPSD_MODE_PIPELINE) && !timed;
   hipLaunchKernelGGL(k_begin_decode, dim3(1), dim3(64), 0, x->sA, at<DevState>(x, x->lay.state), n_tokens);
   HIP_TRY(hipGetLastError());
   HIP_TRY(hipEventRecord(x->ev_t0, x->sA));
@@ -824,11 +963,14 @@ int ppsd_decode(ppsd_ctx *x, int32_t n_tokens, int32_t *out_tokens, int32_t *n_w
       rc = drain_kernel_events(x, &mask);
       if (rc != PPSD_OK) return rc;
     } else {
-      for (int k = 0; k < remaining; ++k) {
+      // a step commits at most one token; a draft-then-verify round at most gamma + 1
+      const int per = c.mode == PPSD_MODE_EESD ? x->gamma + 1 : 1;
+      const int n_steps = (remaining + per - 1) / per;
+      for (int k = 0; k < n_steps; ++k) {
         if (x->g_step) HIP_TRY(hipGraphLaunch(x->g_step, x->sA));
         else HIP_TRY(enqueue_step_any(x, c.mode, two, false));
       }
-      x->steps_launched += remaining;
+      x->steps_launched += n_steps;
       int rc = read_state(x);
       if (rc != PPSD_OK) return rc;
     }
@@ -857,7 +999,7 @@ int ppsd_stats(const ppsd_ctx *cx, ppsd_stats_t *out) {
   out->steps_overlapped = s[4]; out->steps_draft_only = s[5]; out->kv_rollbacks = s[6];
   out->steps_launched = x->steps_launched;
   out->device_ms = x->device_ms;
-  out->pipeline_ticks = s[8]; out->stage_runs = s[9]; out->flushed_tokens = s[10];
+  out->pipeline_ticks = s[8]; out->stage_runs = s[9]; out->flushed_tokens = s[10]; out->eesd_rounds = s[11];
   return PPSD_OK;
 }
 

@@ -21,7 +21,10 @@ constexpr float kNegBig = -1.0e30f;  // finite stand-in for -inf in the running 
 
 // Stage roles: which part of the device state a kernel takes its input from.
 // kPipeStage0 + k is stage k of the full ceil(N/E)-stage schedule (Sec. 4.1, Alg. 1).
-enum Role : int { kVanilla = 0, kDraft = 1, kVerify = 2, kPrefill = 3, kPipeStage0 = 16 };
+// kEesdDraft0 + j is draft step j of a draft-then-verify round (Sec. 3.1), kEesdVerify its batched
+// verify pass.
+enum Role : int { kVanilla = 0, kDraft = 1, kVerify = 2, kPrefill = 3, kPipeStage0 = 16, kEesdDraft0 = 40,
+                  kEesdVerify = 48 };
 
 constexpr int kMaxStages = 16;       // stages of the full pipeline schedule
 constexpr int kTokRing = 32;         // ring of the tokens stage 0 used, by position (> kMaxStages)
@@ -30,8 +33,12 @@ constexpr int kTokRing = 32;         // ring of the tokens stage 0 used, by posi
 // The full pipeline adds one working slot per stage (kXStageWork0 + k, fixed address) and, for the
 // boundary in front of stage b >= 1, two buffers that swap roles every tick: the stage reads
 // kXBoundRead0 + b while stage b-1 writes kXBoundWrite0 + b.
+// Draft-then-verify rounds reuse the boundary buffers' slots: kXBatchIn0 + b holds the layer-E
+// hidden state of the round's token b, kXBatchWork0 + b its residual stream in the verify pass.
 enum XSel : int { kXDraft = 0, kXVerify = 1, kHExitCur = 2, kHExitNext = 3,
-                  kXStageWork0 = 4, kXBoundRead0 = 32, kXBoundWrite0 = 64 };
+                  kXStageWork0 = 4, kXBoundRead0 = 32, kXBoundWrite0 = 64, kXBatchIn0 = 96, kXBatchWork0 = 112 };
+constexpr int kXBatchInSlot0 = 4 + kMaxStages;        // slot index of kXBatchIn0
+constexpr int kXBatchWorkSlot0 = kXBatchInSlot0 + 8;  // slot index of kXBatchWork0
 constexpr int kXSlots = 4 + kMaxStages + 2 * kMaxStages;   // slots in xbuf
 
 // Device-resident decode state.  Only the commit kernel writes it, once per step, after
@@ -57,6 +64,8 @@ struct DevState {
   int32_t pl_par;                 // which buffer of every stage boundary is the readable one
   int32_t pl_pad[2];
   int32_t pl_tok_at[kTokRing];    // token stage 0 used at position p, at index p % kTokRing
+  // draft-then-verify round: ee_draft[j] = token of draft step j (j >= 1; step 0 takes last_token)
+  int32_t ee_draft[8];
 };
 
 struct Dims {
@@ -106,6 +115,11 @@ __device__ __forceinline__ StageIn stage_in(const Common &c, int role) {
     s.active = running && st->full;
     s.pos = st->t;
     s.tok = -1;
+  } else if (role >= kEesdDraft0) {
+    const int j = (role - kEesdDraft0) & 7;      // kEesdVerify: j = 0, the pass starts at the committed token
+    s.active = running;
+    s.pos = st->t + (role == kEesdVerify ? 0 : j);
+    s.tok = (role == kEesdVerify || j == 0) ? st->last_token : st->ee_draft[j];
   } else {  // kPipeStage0 + k, k < kMaxStages (the host launches no other role)
     const int k = (role - kPipeStage0) & (kMaxStages - 1);
     s.active = running && st->pl_valid[k];
@@ -119,6 +133,8 @@ __device__ __forceinline__ float *xslot(const Common &c, int sel) {
   int slot = sel;
   if (sel == kHExitCur) slot = 2 + (c.st->cur & 1);
   else if (sel == kHExitNext) slot = 2 + ((c.st->cur & 1) ^ 1);
+  else if (sel >= kXBatchWork0) slot = kXBatchWorkSlot0 + ((sel - kXBatchWork0) & 7);
+  else if (sel >= kXBatchIn0) slot = kXBatchInSlot0 + ((sel - kXBatchIn0) & 7);
   else if (sel >= kXBoundWrite0) slot = kXStageWork0 + kMaxStages + 2 * ((sel - kXBoundWrite0) & (kMaxStages - 1)) + ((c.st->pl_par & 1) ^ 1);
   else if (sel >= kXBoundRead0) slot = kXStageWork0 + kMaxStages + 2 * ((sel - kXBoundRead0) & (kMaxStages - 1)) + (c.st->pl_par & 1);
   return c.xbuf + (size_t)slot * c.dm.d;
