@@ -82,8 +82,9 @@ bool valid_config(const ppsd_config *c, const char **why) {
   REJECT(c->mode < 0 || c->mode > 4, "mode must be 0..4");
   REJECT(!(c->rope_base > 1.0f) || !(c->rms_eps >= 0.0f), "bad rope_base / rms_eps");
   REJECT(c->debug_logits < 0, "debug_logits < 0");
-  REJECT((size_t)c->d_ffn * 4 > 64 * 1024 || (size_t)c->d_model * 4 > 64 * 1024 ||
-         (size_t)c->n_heads * c->head_dim * 4 > 64 * 1024, "activation vector exceeds 64 KiB of LDS");
+  const int esz = c->dtype == PPSD_FP32 ? 4 : 2;
+  REJECT((size_t)xs_floats(esz, c->d_ffn) * 4 > 64 * 1024 || (size_t)xs_floats(esz, c->d_model) * 4 > 64 * 1024 ||
+         (size_t)xs_floats(esz, c->n_heads * c->head_dim) * 4 > 64 * 1024, "activation vector exceeds 64 KiB of LDS");
   REJECT(c->d_model > 16 * kGBlock, "d_model exceeds the staging capacity (8192)");
   REJECT(c->d_ffn > 32 * kGBlock || c->n_heads * c->head_dim > 32 * kGBlock, "d_ffn / n_heads*head_dim exceed the staging capacity (16384)");
   REJECT(c->engine != PPSD_ENGINE_STREAMS && c->engine != PPSD_ENGINE_PERSISTENT, "engine must be 0 or 1");
@@ -101,7 +102,7 @@ bool valid_config(const ppsd_config *c, const char **why) {
     REJECT(c->engine != PPSD_ENGINE_STREAMS, "draft-then-verify rounds run on the per-operation engine only");
     REJECT(c->time_kernels, "time_kernels is not available with draft-then-verify rounds");
     const int B = (c->eesd_gamma ? c->eesd_gamma : kDefaultGamma) + 1;
-    REJECT((size_t)B * c->d_model * 4 > kBatchLdsMax, "gamma + 1 input vectors of d_model floats exceed the LDS of a compute unit");
+    REJECT((size_t)B * xs_floats(esz, c->d_model) * 4 > kBatchLdsMax, "gamma + 1 input vectors of d_model floats exceed the LDS of a compute unit");
   }
   REJECT(c->tune_attn_split < 0 || (c->tune_attn_split > 0 && c->tune_attn_split < 64), "tune_attn_split must be 0 or >= 64");
   for (int k = 0; k < 1; ++k) REJECT(c->reserved[k] != 0, "reserved fields must be zero");
@@ -193,6 +194,8 @@ struct ppsd_ctx {
   int n_wg = 0;
   // grid of a weight-streaming kernel with n_tasks row-pair tasks: one wave per task up to a few
   // workgroups per CU, then the waves loop
+  // bytes of LDS a staged input vector of C elements takes (padded to whole column blocks)
+  size_t xs_bytes(int C) const { return 4ull * xs_floats(cfg.dtype == PPSD_FP32 ? 4 : 2, C); }
   int gemv_grid(int n_tasks, int wgs_per_cu = kGemvWgsPerCu) const {
     return gemv_grid_for(n_tasks, n_cu, cfg.tune_wgs_per_cu > 0 ? cfg.tune_wgs_per_cu : wgs_per_cu);
   }
@@ -255,7 +258,7 @@ void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int 
   // xwork: residual slot used inside the layer after the first residual add
   const int total_pairs = (c.n_heads + 2 * c.n_kv_heads) * (c.head_dim / 2);
   L.before(kKQkv);
-  hipLaunchKernelGGL((k_qkv<WT>), dim3(x->gemv_grid(total_pairs)), dim3(kGBlock), (size_t)d * 4, L.s, cm, role, layer,
+  hipLaunchKernelGGL((k_qkv<WT>), dim3(x->gemv_grid(total_pairs)), dim3(kGBlock), x->xs_bytes(d), L.s, cm, role, layer,
                      xin_sel, from_embed ? 1 : 0, (const WT *)x->embed, (const float *)x->attn_norm[layer],
                      (const WT *)x->wqkv[layer], q);
   L.after();
@@ -274,17 +277,17 @@ void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int 
 
   const int proj_grid = x->gemv_grid((d + 1) / 2);
   L.before(kKOproj);
-  hipLaunchKernelGGL((k_proj_resid<WT>), dim3(proj_grid), dim3(kGBlock), (size_t)nq * 4, L.s, cm, role,
+  hipLaunchKernelGGL((k_proj_resid<WT>), dim3(proj_grid), dim3(kGBlock), x->xs_bytes(nq), L.s, cm, role,
                      (const float *)a, nq, (const WT *)x->wo[layer], d, xin_sel, xwork);
   L.after();
 
   L.before(kKGateUp);
-  hipLaunchKernelGGL((k_gate_up<WT>), dim3(x->gemv_grid(f, kGateUpWgsPerCu)), dim3(kGBlock), (size_t)d * 4, L.s, cm, role, xwork,
+  hipLaunchKernelGGL((k_gate_up<WT>), dim3(x->gemv_grid(f, kGateUpWgsPerCu)), dim3(kGBlock), x->xs_bytes(d), L.s, cm, role, xwork,
                      (const float *)x->mlp_norm[layer], (const WT *)x->wgu[layer], mb);
   L.after();
 
   L.before(kKDown);
-  hipLaunchKernelGGL((k_proj_resid<WT>), dim3(proj_grid), dim3(kGBlock), (size_t)f * 4, L.s, cm, role,
+  hipLaunchKernelGGL((k_proj_resid<WT>), dim3(proj_grid), dim3(kGBlock), x->xs_bytes(f), L.s, cm, role,
                      (const float *)mb, f, (const WT *)x->wdown[layer], d, xwork, xout_last_sel);
   L.after();
 }
@@ -296,7 +299,7 @@ void launch_head(Launcher &L, int role, int xin_sel, bool is_lm) {
   float2 *cand = at<float2>(x, is_lm ? x->lay.cand_lm : x->lay.cand_exit);
   float *logits = c.debug_logits > 0 ? at<float>(x, x->lay.logits) : nullptr;
   L.before(kKHead);
-  hipLaunchKernelGGL((k_head<WT>), dim3(x->cm.dm.head_blocks), dim3(kGBlock), (size_t)c.d_model * 4, L.s,
+  hipLaunchKernelGGL((k_head<WT>), dim3(x->cm.dm.head_blocks), dim3(kGBlock), x->xs_bytes(c.d_model), L.s,
                      x->cm, role, xin_sel, (const float *)(is_lm ? x->final_norm : x->exit_norm),
                      (const WT *)(is_lm ? x->lm_head : x->exit_head), cand, logits, is_lm ? 1 : 0);
   L.after();
@@ -343,7 +346,7 @@ void launch_proj_b(Launcher &L, int kind, const float *vin, int C, const WT *W, 
   if ((size_t)B * Cs * 4 > kBatchLdsMax) Cs = (int)(kBatchLdsMax / (4 * B)) / blk * blk;
   for (int c0 = 0; c0 < C; c0 += Cs) {
     const int w = C - c0 < Cs ? C - c0 : Cs;
-    const size_t lds = (size_t)B * w * 4;
+    const size_t lds = (size_t)B * x->xs_bytes(w);
     L.before(kind);
     hipLaunchKernelGGL((k_proj_resid_b<WT, B>), dim3(batch_grid(x, (d + 1) / 2, lds, kGemvWgsPerCu)), dim3(kGBlock), lds, L.s,
                        x->cm, vin, C, c0, w, W, d, c0 == 0 ? resid_slot0 : out_slot0, out_slot0);
@@ -360,7 +363,7 @@ void launch_verify_batch(Launcher &L) {
   float *q = at<float>(x, x->lay.qb), *a = at<float>(x, x->lay.ab), *mb = at<float>(x, x->lay.mb);
   float *part = at<float>(x, x->lay.partials_b);
   int *cnt = at<int>(x, x->lay.counters_b);
-  const size_t lds_d = (size_t)B * d * 4;
+  const size_t lds_d = (size_t)B * x->xs_bytes(d);
   const int total_pairs = (c.n_heads + 2 * c.n_kv_heads) * (c.head_dim / 2);
   const int G = c.n_heads / c.n_kv_heads;
   for (int l = c.exit_layer; l < c.n_layers; ++l) {
@@ -623,7 +626,7 @@ int mega_setup(ppsd_ctx *x) {
   const int nq = c.n_heads * c.head_dim;
   int xs = c.d_model > nq ? c.d_model : nq;
   if (c.d_ffn > xs) xs = c.d_ffn;
-  x->xs_stride = (xs + 63) / 64 * 64;
+  x->xs_stride = xs_floats(c.dtype == PPSD_FP32 ? 4 : 2, xs);
   const int vec = c.dtype == PPSD_FP32 ? 4 : 8;
   const int G = c.n_heads / c.n_kv_heads;
   const size_t merge_floats = (size_t)(kMBlock / (c.head_dim / vec)) * G * (c.head_dim + 2);

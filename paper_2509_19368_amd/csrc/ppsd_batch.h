@@ -53,7 +53,7 @@ struct BatchNormStage {
       for (int e = 0; e < kNormPer; ++e) {
         const int i = 4 * (threadIdx.x + e * BLOCK);
         if (i < d)
-          *(float4 *)(xs + (size_t)b * ldx + i) = make_float4(xv[b][e].x * rs * gv[e].x, xv[b][e].y * rs * gv[e].y,
+          *(float4 *)(xs + (size_t)b * ldx + xs_pos<WT>(i)) = make_float4(xv[b][e].x * rs * gv[e].x, xv[b][e].y * rs * gv[e].y,
                                                               xv[b][e].z * rs * gv[e].z, xv[b][e].w * rs * gv[e].w);
       }
     }
@@ -80,7 +80,10 @@ __device__ __forceinline__ void trip_consume_b(const Trip<WT, kTripRows, kTripBl
       for (int b = 0; b < B; ++b) {
         float x[N];
 #pragma unroll
-        for (int e = 0; e < N; ++e) x[e] = xs[(size_t)b * ldx + c + e];
+        for (int q = 0; q < N / 4; ++q) {
+          const float4 v = *(const float4 *)(xs + (size_t)b * ldx + (cb + k) * kStride + q * (4 * kWave) + lane * 4);
+          x[4 * q] = v.x; x[4 * q + 1] = v.y; x[4 * q + 2] = v.z; x[4 * q + 3] = v.w;
+        }
 #pragma unroll
         for (int e = 0; e < N; ++e) acc[0][b] = fmaf(w0[e], x[e], acc[0][b]);
 #pragma unroll
@@ -128,7 +131,7 @@ __device__ __forceinline__ void gemv_tasks_b(Trip<WT, kTripRows, kTripBlocks> &t
 template <typename WT, int B>
 __global__ __launch_bounds__(kGBlock) void k_qkv_b(Common c, int layer, int x_slot0, const float *gain, const WT *wqkv,
                                                    float *qout) {
-  extern __shared__ float xs[];
+  extern __shared__ __align__(16) float xs[];
   __shared__ float red[kGWaves];
   const Dims &m = c.dm;
   const int d = m.d;
@@ -149,8 +152,9 @@ __global__ __launch_bounds__(kGBlock) void k_qkv_b(Common c, int layer, int x_sl
   };
   Trip<WT, kTripRows, kTripBlocks> trip;
   if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
-  in.finish(d, m.eps, xs, d, red);
-  gemv_tasks_b<WT, B>(trip, rows, gw, n_tasks, tw, d, xs, d, set_rows, [&](int task, float (&s)[kTripRows][B]) {
+  const int ldx = xs_floats((int)sizeof(WT), d);
+  in.finish(d, m.eps, xs, ldx, red);
+  gemv_tasks_b<WT, B>(trip, rows, gw, n_tasks, tw, d, xs, ldx, set_rows, [&](int task, float (&s)[kTripRows][B]) {
     if (lane != 0) return;
     const int h = task / half, i = task - h * half;
 #pragma unroll
@@ -207,7 +211,7 @@ __global__ __launch_bounds__(kGBlock) void k_attn_b(Common c, int layer, const f
 template <typename WT, int B>
 __global__ __launch_bounds__(kGBlock) void k_proj_resid_b(Common c, const float *vin, int C_total, int c0, int Cs,
                                                           const WT *W, int n_rows, int resid_slot0, int out_slot0) {
-  extern __shared__ float xs[];
+  extern __shared__ __align__(16) float xs[];
   const StageIn si = stage_in(c, kEesdVerify);
   if (!si.active) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -220,15 +224,16 @@ __global__ __launch_bounds__(kGBlock) void k_proj_resid_b(Common c, const float 
   };
   Trip<WT, kTripRows, kTripBlocks> trip;
   if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(Cs), Cs); }
+  const int ldx = xs_floats((int)sizeof(WT), Cs);
 #pragma unroll
   for (int b = 0; b < B; ++b)
     for (int i = 4 * threadIdx.x; i < Cs; i += 4 * kGBlock)
-      *(float4 *)(xs + (size_t)b * Cs + i) = *(const float4 *)(vin + (size_t)b * C_total + c0 + i);
+      *(float4 *)(xs + (size_t)b * ldx + xs_pos<WT>(i)) = *(const float4 *)(vin + (size_t)b * C_total + c0 + i);
   __syncthreads();
   const int d = c.dm.d;
   const float *resid = c.xbuf + (size_t)resid_slot0 * d;
   float *out = c.xbuf + (size_t)out_slot0 * d;
-  gemv_tasks_b<WT, B>(trip, rows, gw, n_tasks, tw, Cs, xs, Cs, set_rows, [&](int task, float (&s)[kTripRows][B]) {
+  gemv_tasks_b<WT, B>(trip, rows, gw, n_tasks, tw, Cs, xs, ldx, set_rows, [&](int task, float (&s)[kTripRows][B]) {
     const int r = 2 * task + lane;
     if (lane < 2 && r < n_rows) {
 #pragma unroll
@@ -241,7 +246,7 @@ __global__ __launch_bounds__(kGBlock) void k_proj_resid_b(Common c, const float 
 template <typename WT, int B>
 __global__ __launch_bounds__(kGBlock) void k_gate_up_b(Common c, int x_slot0, const float *gain, const WT *wgu,
                                                        float *mout) {
-  extern __shared__ float xs[];
+  extern __shared__ __align__(16) float xs[];
   __shared__ float red[kGWaves];
   const Dims &m = c.dm;
   const int d = m.d, f = m.f;
@@ -258,8 +263,9 @@ __global__ __launch_bounds__(kGBlock) void k_gate_up_b(Common c, int x_slot0, co
   };
   Trip<WT, kTripRows, kTripBlocks> trip;
   if (gw < f) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
-  in.finish(d, m.eps, xs, d, red);
-  gemv_tasks_b<WT, B>(trip, rows, gw, f, tw, d, xs, d, set_rows, [&](int task, float (&s)[kTripRows][B]) {
+  const int ldx = xs_floats((int)sizeof(WT), d);
+  in.finish(d, m.eps, xs, ldx, red);
+  gemv_tasks_b<WT, B>(trip, rows, gw, f, tw, d, xs, ldx, set_rows, [&](int task, float (&s)[kTripRows][B]) {
     if (lane != 0) return;
 #pragma unroll
     for (int b = 0; b < B; ++b) {
@@ -274,7 +280,7 @@ __global__ __launch_bounds__(kGBlock) void k_gate_up_b(Common c, int x_slot0, co
 template <typename WT, int B>
 __global__ __launch_bounds__(kGBlock) void k_head_b(Common c, int x_slot0, const float *gain, const WT *W, float2 *cand,
                                                     float *logits_log) {
-  extern __shared__ float xs[];
+  extern __shared__ __align__(16) float xs[];
   __shared__ float red[kGWaves];
   __shared__ float bv[kGWaves][B];
   __shared__ int bi[kGWaves][B];
@@ -294,13 +300,14 @@ __global__ __launch_bounds__(kGBlock) void k_head_b(Common c, int x_slot0, const
   };
   Trip<WT, kTripRows, kTripBlocks> trip;
   if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
-  in.finish(d, m.eps, xs, d, red);
+  const int ldx = xs_floats((int)sizeof(WT), d);
+  in.finish(d, m.eps, xs, ldx, red);
   const int row0 = c.st->gen_count;
   float best[B];
   int besti[B];
 #pragma unroll
   for (int b = 0; b < B; ++b) { best[b] = -INFINITY; besti[b] = 0x7fffffff; }
-  gemv_tasks_b<WT, B>(trip, rows, gw, n_tasks, tw, d, xs, d, set_rows, [&](int task, float (&s)[kTripRows][B]) {
+  gemv_tasks_b<WT, B>(trip, rows, gw, n_tasks, tw, d, xs, ldx, set_rows, [&](int task, float (&s)[kTripRows][B]) {
     const int r = 2 * task;
 #pragma unroll
     for (int b = 0; b < B; ++b) {

@@ -248,6 +248,24 @@ __device__ __forceinline__ void wave_argmax(float &v, int &i) {
 // the weights a wave reads never depend on activations, so the prologue's latency chain runs under
 // the first loads.  Per row the FMA chain runs in increasing column order; the reduction order is
 // fixed (no atomics), which keeps every scheduling mode bitwise identical.
+// Layout of a staged input vector in LDS.  Lane l of a wave multiplies columns (blk*64 + l)*N .. +N
+// (N = elements per 16-byte weight load).  Stored in plain order, a lane's N = 8 floats are 32 bytes
+// and consecutive lanes sit 32 bytes apart: two-dword reads then hit 4 of the 32 banks (16-way
+// conflict), which made the reads of x, not the weight stream, the limit.  So each block of 64*N
+// elements is stored as N/4 planes of 64 float4: plane q holds elements 4q..4q+3 of every lane, and
+// a wave reads a plane with one conflict-free 16-byte access per lane.  (N = 4: the identity.)
+// The buffer is padded to whole blocks.
+template <typename WT>
+__host__ __device__ __forceinline__ int xs_pos(int i) {
+  constexpr int N = 16 / (int)sizeof(WT);
+  if (N == 4) return i;
+  return (i & ~511) | (((i >> 2) & 1) << 8) | (((i >> 3) & 63) << 2) | (i & 3);
+}
+__host__ __device__ __forceinline__ int xs_floats(int elem_bytes, int C) {
+  const int blk = 64 * (16 / elem_bytes);
+  return (C + blk - 1) / blk * blk;
+}
+
 template <typename WT, int R, int KB>
 struct Trip {
   uint4 u[R * KB];
@@ -287,7 +305,10 @@ __device__ __forceinline__ void trip_consume(const Trip<WT, R, KB> &t, const flo
     if (c < C) {
       float x[N];
 #pragma unroll
-      for (int e = 0; e < N; ++e) x[e] = xs[c + e];
+      for (int q = 0; q < N / 4; ++q) {
+        const float4 v = *(const float4 *)(xs + (cb + k) * kStride + q * (4 * kWave) + lane * 4);
+        x[4 * q] = v.x; x[4 * q + 1] = v.y; x[4 * q + 2] = v.z; x[4 * q + 3] = v.w;
+      }
 #pragma unroll
       for (int r = 0; r < R; ++r) {
         float w[N];
@@ -362,8 +383,8 @@ struct NormStage {
     for (int e = 0; e < kNormPer; ++e) {
       const int i = 4 * (threadIdx.x + e * BLOCK);
       if (i < d)
-        *(float4 *)(xs + i) = make_float4(xv[e].x * rs * gv[e].x, xv[e].y * rs * gv[e].y, xv[e].z * rs * gv[e].z,
-                                          xv[e].w * rs * gv[e].w);
+        *(float4 *)(xs + xs_pos<WT>(i)) = make_float4(xv[e].x * rs * gv[e].x, xv[e].y * rs * gv[e].y, xv[e].z * rs * gv[e].z,
+                                                      xv[e].w * rs * gv[e].w);
     }
     __syncthreads();
   }
@@ -379,11 +400,12 @@ struct CopyStage {
       xv[e] = i < C ? *(const float4 *)(vin + i) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
   }
+  template <typename WT>
   __device__ __forceinline__ void finish(int C, float *xs) {
 #pragma unroll
     for (int e = 0; e < kCopyPer; ++e) {
       const int i = 4 * (threadIdx.x + e * BLOCK);
-      if (i < C) *(float4 *)(xs + i) = xv[e];
+      if (i < C) *(float4 *)(xs + xs_pos<WT>(i)) = xv[e];
     }
     __syncthreads();
   }

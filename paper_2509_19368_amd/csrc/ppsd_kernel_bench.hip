@@ -85,23 +85,23 @@ int main(int argc, char **argv) {
   };
   const int qkv_rows = (n_h + 2 * n_kv) * hd;
   run("k_qkv", (size_t)qkv_rows * d * 2, [&](const bf16_t *w) {
-    hipLaunchKernelGGL((k_qkv<bf16_t>), dim3(gemv_grid_for(qkv_rows / 2, n_cu, kGemvWgsPerCu)), dim3(kGBlock), (size_t)d * 4, 0, c,
+    hipLaunchKernelGGL((k_qkv<bf16_t>), dim3(gemv_grid_for(qkv_rows / 2, n_cu, kGemvWgsPerCu)), dim3(kGBlock), (size_t)xs_floats(2, d) * 4, 0, c,
                        (int)kVanilla, 3, (int)kXDraft, 0, w, gain, w, mout);
   });
   run("k_proj_resid (o_proj)", (size_t)d * nq * 2, [&](const bf16_t *w) {
-    hipLaunchKernelGGL((k_proj_resid<bf16_t>), dim3(gemv_grid_for((d + 1) / 2, n_cu, kGemvWgsPerCu)), dim3(kGBlock), (size_t)nq * 4, 0, c,
+    hipLaunchKernelGGL((k_proj_resid<bf16_t>), dim3(gemv_grid_for((d + 1) / 2, n_cu, kGemvWgsPerCu)), dim3(kGBlock), (size_t)xs_floats(2, nq) * 4, 0, c,
                        (int)kVanilla, vin, nq, w, d, (int)kXDraft, (int)kXDraft);
   });
   run("k_gate_up", (size_t)2 * f * d * 2, [&](const bf16_t *w) {
-    hipLaunchKernelGGL((k_gate_up<bf16_t>), dim3(gemv_grid_for(f, n_cu, kGateUpWgsPerCu)), dim3(kGBlock), (size_t)d * 4, 0, c,
+    hipLaunchKernelGGL((k_gate_up<bf16_t>), dim3(gemv_grid_for(f, n_cu, kGateUpWgsPerCu)), dim3(kGBlock), (size_t)xs_floats(2, d) * 4, 0, c,
                        (int)kVanilla, (int)kXDraft, gain, w, mout);
   });
   run("k_proj_resid (down)", (size_t)d * f * 2, [&](const bf16_t *w) {
-    hipLaunchKernelGGL((k_proj_resid<bf16_t>), dim3(gemv_grid_for((d + 1) / 2, n_cu, kGemvWgsPerCu)), dim3(kGBlock), (size_t)f * 4, 0, c,
+    hipLaunchKernelGGL((k_proj_resid<bf16_t>), dim3(gemv_grid_for((d + 1) / 2, n_cu, kGemvWgsPerCu)), dim3(kGBlock), (size_t)xs_floats(2, f) * 4, 0, c,
                        (int)kVanilla, vin, f, w, d, (int)kXDraft, (int)kXDraft);
   });
   run("k_head", (size_t)V * d * 2, [&](const bf16_t *w) {
-    hipLaunchKernelGGL((k_head<bf16_t>), dim3(c.dm.head_blocks), dim3(kGBlock), (size_t)d * 4, 0, c, (int)kVanilla, (int)kXDraft, gain,
+    hipLaunchKernelGGL((k_head<bf16_t>), dim3(c.dm.head_blocks), dim3(kGBlock), (size_t)xs_floats(2, d) * 4, 0, c, (int)kVanilla, (int)kXDraft, gain,
                        w, cand, (float *)nullptr, 1);
   });
   return 0;

@@ -46,7 +46,7 @@ template <typename WT>
 __global__ __launch_bounds__(kGBlock) void k_qkv(Common c, int role, int layer, int xin_sel, int from_embed,
                                                  const WT *embed, const float *gain, const WT *wqkv,
                                                  float *qout) {
-  extern __shared__ float xs[];
+  extern __shared__ __align__(16) float xs[];
   __shared__ float red[kGWaves];
   const Dims &m = c.dm;
   const int d = m.d;
@@ -286,7 +286,7 @@ __global__ __launch_bounds__(kGBlock) void k_attn(Common c, int role, int layer,
 template <typename WT>
 __global__ __launch_bounds__(kGBlock) void k_proj_resid(Common c, int role, const float *vin, int C,
                                                         const WT *W, int n_rows, int resid_sel, int out_sel) {
-  extern __shared__ float xs[];
+  extern __shared__ __align__(16) float xs[];
   CopyStage<kGBlock> in;
   in.issue(vin, C);                       // the input buffer's address never depends on the state
   const StageIn si = stage_in(c, role);
@@ -301,7 +301,7 @@ __global__ __launch_bounds__(kGBlock) void k_proj_resid(Common c, int role, cons
   };
   Trip<WT, kTripRows, kTripBlocks> trip;
   if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(C), C); }
-  in.finish(C, xs);
+  in.template finish<WT>(C, xs);
   const float *resid = xslot(c, resid_sel);
   float *out = xslot(c, out_sel);
   gemv_tasks<WT>(trip, rows, gw, n_tasks, tw, C, xs, set_rows, [&](int task, float s0, float s1) {
@@ -316,7 +316,7 @@ __global__ __launch_bounds__(kGBlock) void k_proj_resid(Common c, int role, cons
 template <typename WT>
 __global__ __launch_bounds__(kGBlock) void k_gate_up(Common c, int role, int xin_sel, const float *gain,
                                                      const WT *wgu, float *mout) {
-  extern __shared__ float xs[];
+  extern __shared__ __align__(16) float xs[];
   __shared__ float red[kGWaves];
   const Dims &m = c.dm;
   const int d = m.d, f = m.f;
@@ -349,7 +349,7 @@ __global__ __launch_bounds__(kGBlock) void k_gate_up(Common c, int role, int xin
 template <typename WT>
 __global__ __launch_bounds__(kGBlock) void k_head(Common c, int role, int xin_sel, const float *gain,
                                                   const WT *W, float2 *cand, float *logits_log, int is_lm) {
-  extern __shared__ float xs[];
+  extern __shared__ __align__(16) float xs[];
   __shared__ float red[kGWaves];
   __shared__ float bv[kGWaves];
   __shared__ int bi[kGWaves];

@@ -174,7 +174,7 @@ __device__ __forceinline__ PhaseSegs phase_segs(const MegaArgs &A, int p, const 
 // ------------------------------------------------------------------------------------------
 template <typename WT, int HD, int G>
 __global__ __launch_bounds__(kMBlock, kMegaWgsPerCu) void k_mega(MegaArgs A) {
-  extern __shared__ float lds[];            // one staged input vector; reused as the attention merge buffer
+  extern __shared__ __align__(16) float lds[];            // one staged input vector; reused as the attention merge buffer
   __shared__ float red[kMWaves];
   __shared__ float bv[kMWaves];
   __shared__ int bi[kMWaves];
@@ -305,7 +305,7 @@ __global__ __launch_bounds__(kMBlock, kMegaWgsPerCu) void k_mega(MegaArgs A) {
         CopyStage<kMBlock> in;
         in.issue(g.kind == SK_OPROJ ? A.a[s.slot] : A.m[s.slot], C);
         if (gw < g.units) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(C), C); }
-        in.finish(C, xs);
+        in.template finish<WT>(C, xs);
         const float *resid = slot_ptr(g.kind == SK_OPROJ ? (first_layer ? s.xin_first : s.xwork) : s.xwork);
         float *out = slot_ptr(g.kind == SK_OPROJ ? s.xwork : (last_layer ? s.xout_last : s.xwork));
         gemv_tasks<WT>(trip, rows, gw, g.units, tw, C, xs, set_rows, [&](int task, float s0, float s1) {
