@@ -109,7 +109,7 @@ typedef struct {
                               (min(S, 4)), else 2..4.  Streams beyond the caller's two are created (default
                               priority) and destroyed by the library */
   int32_t tune_wgs_per_cu; /* launch tuning: workgroups per compute unit of the weight-streaming kernels,
-                              1..4; 0 = the library's defaults (4; 2 for gate/up) */
+                              1..4; 0 = the library's defaults (3; 2 for gate/up) */
   int32_t tune_attn_split; /* launch tuning: positions of capacity (max_seq) per attention split, >= 64; the
                               number of splits is capped at 64.  0 = the library's default (one split up to
                               512 positions, beyond that one per 512) */

@@ -175,9 +175,18 @@ class Decoder:
         """Full-model logits at every position: [T, V]."""
         return self.head_logits(self.hidden_full(tokens), "lm")
 
+    @property
+    def has_exit_block(self) -> bool:
+        """The early-exit head is a transformer layer (entry n_layers of the per-layer lists) followed
+        by the norm head (Sec. 5.4, "Impact of exit head") rather than the norm head alone."""
+        return bool(getattr(self.s, "exit_block", False))
+
     def exit_logits_full(self, tokens: Sequence[int]) -> torch.Tensor:
         """Early-exit head logits (after exit_layer layers) at every position."""
-        return self.head_logits(self.hidden_full(tokens, self.s.exit_layer), "exit")
+        h = self.hidden_full(tokens, self.s.exit_layer)
+        if self.has_exit_block:
+            h = self.layer_full(self.s.n_layers, h)
+        return self.head_logits(h, "exit")
 
 
 def argmax_lowest(logits: torch.Tensor) -> int:
@@ -207,9 +216,10 @@ class KVState:
     """Per-layer key/value rows with per-layer lengths (so a stage can roll back)."""
 
     def __init__(self, shape, max_seq: int):
-        self.K = torch.zeros(shape.n_layers, max_seq, shape.n_kv_heads, shape.head_dim, dtype=F64)
+        n = shape.n_layers + (1 if getattr(shape, "exit_block", False) else 0)   # the early-exit block keeps rows too
+        self.K = torch.zeros(n, max_seq, shape.n_kv_heads, shape.head_dim, dtype=F64)
         self.V = torch.zeros_like(self.K)
-        self.len = [0] * shape.n_layers
+        self.len = [0] * n
 
     def truncate(self, layers: range, new_len: int) -> None:
         for l in layers:
@@ -233,6 +243,20 @@ def run_layers(dec: Decoder, kv: KVState, x: torch.Tensor, pos: int, layers: ran
         a = attend_one(q[0], kv.K[l, : pos + 1], kv.V[l, : pos + 1])
         x = dec.after_attention(l, x, a[None])
     return x[0]
+
+
+def exit_logits(dec: Decoder, kv: KVState, h: torch.Tensor, pos: int) -> torch.Tensor:
+    """Early-exit head on the layer-E hidden state h of the token at position pos.  With an exit block
+    the state first goes through that layer, which appends its own K/V row at pos; the block's output
+    feeds the head only, never the later layers."""
+    if dec.has_exit_block:
+        h = run_layers(dec, kv, h, pos, range(dec.s.n_layers, dec.s.n_layers + 1))
+    return dec.head_logits(h, "exit")
+
+
+def draft_layers_of(dec: Decoder) -> List[int]:
+    """Layers whose KV rows a drafted token writes: 1..E, and the exit block."""
+    return list(range(dec.s.exit_layer)) + ([dec.s.n_layers] if dec.has_exit_block else [])
 
 
 class GreedyTrace:

@@ -28,7 +28,7 @@ from typing import List, Sequence
 
 import torch
 
-from .decoder_fp64 import Decoder, KVState, argmax_lowest, run_layers
+from .decoder_fp64 import Decoder, KVState, argmax_lowest, exit_logits, run_layers
 from .ppsd_schedule import prefill
 
 
@@ -71,8 +71,10 @@ def eesd_round(ss: EESDSession, out: List[int], limit: int) -> None:
     h: List[torch.Tensor] = []
     for j in range(g):
         h.append(run_layers(dec, kv, dec.embed([x[j]])[0], t + j, draft_layers))
-        x.append(argmax_lowest(dec.head_logits(h[j], "exit")))
+        x.append(argmax_lowest(exit_logits(dec, kv, h[j], t + j)))
     h.append(run_layers(dec, kv, dec.embed([x[g]])[0], t + g, draft_layers))
+    if dec.has_exit_block:            # the block's row at t+gamma: later drafts attend to it if all are accepted
+        exit_logits(dec, kv, h[g], t + g)
     v = [argmax_lowest(dec.head_logits(run_layers(dec, kv, h[j], t + j, verify_layers), "lm")) for j in range(g + 1)]
     n = 0
     while n < g and x[n + 1] == v[n]:
@@ -90,7 +92,7 @@ def eesd_round(ss: EESDSession, out: List[int], limit: int) -> None:
     st.committed += k
     ss.t = t + k
     ss.last_token = v[k - 1]
-    kv.truncate(range(s.n_layers), ss.t)
+    kv.truncate(range(len(kv.len)), ss.t)
 
 
 def eesd_decode(ss: EESDSession, n_tokens: int) -> List[int]:

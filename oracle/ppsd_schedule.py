@@ -35,7 +35,7 @@ from typing import List, Sequence
 
 import torch
 
-from .decoder_fp64 import Decoder, KVState, argmax_lowest, run_layers
+from .decoder_fp64 import Decoder, KVState, argmax_lowest, draft_layers_of, exit_logits, run_layers
 
 
 @dataclass
@@ -76,7 +76,12 @@ def prefill(dec: Decoder, prompt: Sequence[int], max_seq: int) -> PPSDSession:
     kv = KVState(s, max_seq)
     x = None
     for pos, tok in enumerate(prompt):
-        x = run_layers(dec, kv, dec.embed([tok])[0], pos, range(s.n_layers))
+        if dec.has_exit_block:        # the block attends over its own rows of every earlier position
+            h = run_layers(dec, kv, dec.embed([tok])[0], pos, range(s.exit_layer))
+            exit_logits(dec, kv, h, pos)
+            x = run_layers(dec, kv, h, pos, range(s.exit_layer, s.n_layers))
+        else:
+            x = run_layers(dec, kv, dec.embed([tok])[0], pos, range(s.n_layers))
     tok0 = argmax_lowest(dec.head_logits(x, "lm"))
     return PPSDSession(dec=dec, kv=kv, t=len(prompt), last_token=tok0, full=False)
 
@@ -87,13 +92,13 @@ def step(ss: PPSDSession, out: List[int]) -> None:
     draft_layers, verify_layers = range(0, s.exit_layer), range(s.exit_layer, s.n_layers)
     if not ss.full:
         h = run_layers(dec, kv, dec.embed([ss.last_token])[0], ss.t, draft_layers)
-        ss.h_exit, ss.draft = h, argmax_lowest(dec.head_logits(h, "exit"))
+        ss.h_exit, ss.draft = h, argmax_lowest(exit_logits(dec, kv, h, ss.t))
         ss.full = True
         ss.stats.steps_draft_only += 1
         return
     # draft stage on the speculative token, verify stage on the committed one
     h_next = run_layers(dec, kv, dec.embed([ss.draft])[0], ss.t + 1, draft_layers)
-    d_next = argmax_lowest(dec.head_logits(h_next, "exit"))
+    d_next = argmax_lowest(exit_logits(dec, kv, h_next, ss.t + 1))
     x = run_layers(dec, kv, ss.h_exit, ss.t, verify_layers)
     v = argmax_lowest(dec.head_logits(x, "lm"))
     st = ss.stats
@@ -107,7 +112,7 @@ def step(ss: PPSDSession, out: List[int]) -> None:
     else:
         st.rejected += 1
         st.kv_rollbacks += 1
-        kv.truncate(draft_layers, ss.t + 1)
+        kv.truncate(draft_layers_of(dec), ss.t + 1)
         ss.full = False
     ss.t += 1
     ss.last_token = v
@@ -199,12 +204,12 @@ def pipeline_tick(ss: PipelineSession, out: List[int]) -> None:
         if k == 0:
             ss.token_at[ss.pos[0]] = ss.tok0
         # a stage re-running a position after a flush overwrites the dropped row
-        for l in ss.stages[k]:
+        for l in list(ss.stages[k]) + ([dec.s.n_layers] if k == 0 and dec.has_exit_block else []):
             if kv.len[l] > ss.pos[k]:
                 kv.len[l] = ss.pos[k]
         produced[k] = run_layers(dec, kv, x_in, ss.pos[k], ss.stages[k])
         if k == 0:
-            draft_next = argmax_lowest(dec.head_logits(produced[0], "exit"))
+            draft_next = argmax_lowest(exit_logits(dec, kv, produced[0], ss.pos[0]))
     flush = False
     if ss.valid[S - 1]:
         v = argmax_lowest(dec.head_logits(produced[S - 1], "lm"))

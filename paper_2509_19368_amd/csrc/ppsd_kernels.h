@@ -16,16 +16,20 @@
 namespace ppsd {
 
 // Launch policy of the weight-streaming kernels: one wave per row-pair task up to a few workgroups
-// per CU, beyond that the waves loop.  Measured best of 1..8 workgroups per CU on the 7B shapes:
-// 4 for qkv / o_proj / down / head, 2 for gate_up.
-constexpr int kGemvWgsPerCu = 4;
+// per CU, beyond that the waves loop.
+constexpr int kGemvWgsPerCu = 3;       // what stays resident: the kernels take 72-80 VGPRs, 6 waves per SIMD
 constexpr int kGateUpWgsPerCu = 2;
 constexpr int kMaxWorkgroups = 1024;   // also the capacity of the head-candidate arrays
+// Every wave gets the same number k of tasks (the last ones one fewer at most): k = the smallest
+// count with which all workgroups are resident at once, grid = just enough workgroups for k tasks
+// per wave.  A grid of "capacity" workgroups leaves part of the waves with one task more than the
+// others (gate/up on 512 workgroups: 2.69 tasks per wave, a third of the run at 2/3 occupancy).
 inline int gemv_grid_for(int n_tasks, int n_cu, int wgs_per_cu) {
-  const int want = (n_tasks + kGWaves - 1) / kGWaves;
   int cap = wgs_per_cu * n_cu;
   if (cap > kMaxWorkgroups) cap = kMaxWorkgroups;
-  return want < cap ? want : cap;
+  const int k = (n_tasks + cap * kGWaves - 1) / (cap * kGWaves);
+  const int grid = (n_tasks + kGWaves * k - 1) / (kGWaves * k);
+  return grid < 1 ? 1 : grid;
 }
 
 // KV pool addressing: [layer][physical page][kv head][K=0 / V=1][slot][hd]

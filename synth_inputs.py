@@ -152,7 +152,11 @@ class Workload:
     draft equals the full model's token.  exit_head: "tied" stores separate
     copies of the LM head and final-norm gain as the exit head; "independent"
     draws the exit head from its own stream; "blend" = LM head + exit_beta *
-    independent noise.
+    independent noise.  exit_block: the early-exit head is one more transformer
+    layer of the model's own structure followed by the norm head (the head the
+    paper's main results use, Sec. 5.4 "Impact of exit head"); its tensors are
+    appended to the per-layer lists as entry n_layers, its W_o and W_down scaled
+    by exit_block_damp (0 makes the block the identity, i.e. the plain norm head).
     """
     name: str
     n_layers: int
@@ -169,6 +173,8 @@ class Workload:
     damp: float = 1.0
     exit_head: str = "tied"
     exit_beta: float = 0.0
+    exit_block: bool = False
+    exit_block_damp: float = 1.0
     seed: int = 2509
     prompt_len: int = 16
     decode_len: int = 64
@@ -195,6 +201,11 @@ class Workload:
 
     def head_weight_bytes(self) -> int:
         return self.vocab * self.d_model * self.elem_bytes
+
+    @property
+    def kv_layers(self) -> int:
+        """Layers that keep a KV cache: the model's, plus the early-exit block if there is one."""
+        return self.n_layers + (1 if self.exit_block else 0)
 
     def kv_bytes_per_position(self, n_layers: Optional[int] = None) -> int:
         L = self.n_layers if n_layers is None else n_layers
@@ -255,7 +266,8 @@ def make_weights(w: Workload, device="cpu") -> dict:
     embed [V,d]; per layer: attn_norm [d] (fp32), wqkv [(n_h+2n_kv)*hd, d] with
     rows ordered q heads, k heads, v heads; wo [d, n_h*hd]; mlp_norm [d] (fp32);
     wgu [2f, d] with rows ordered gate then up; wdown [d, f]; final_norm [d],
-    lm_head [V,d]; exit_norm [d], exit_head [V,d].  Matrices are row-major
+    lm_head [V,d]; exit_norm [d], exit_head [V,d].  With exit_block the per-layer
+    lists have one more entry, the early-exit block.  Matrices are row-major
     [out_features, in_features] in the storage dtype; gains are fp32.
     """
     dt = w.torch_dtype
@@ -268,8 +280,10 @@ def make_weights(w: Workload, device="cpu") -> dict:
     ones = lambda: torch.ones(d, dtype=torch.float32, device=device)
     out = {"embed": mat(_TAG_EMBED, V, d), "final_norm": ones(), "lm_head": mat(_TAG_LM, V, d),
            "attn_norm": [], "wqkv": [], "wo": [], "mlp_norm": [], "wgu": [], "wdown": []}
-    for l in range(w.n_layers):
+    for l in range(w.kv_layers):
         s = WEIGHT_STD * (w.damp if l >= w.exit_layer else 1.0)
+        if l == w.n_layers:                      # the early-exit block
+            s = WEIGHT_STD * w.exit_block_damp
         out["attn_norm"].append(ones())
         out["wqkv"].append(mat(_layer_tag(l, _TAG_WQKV), w.qkv_rows, d))
         out["wo"].append(mat(_layer_tag(l, _TAG_WO), d, nq, s))
