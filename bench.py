@@ -40,8 +40,9 @@ def algorithmic_bytes(w, mean_ctx: float):
     kv_draft = w.kv_bytes_per_position(w.exit_layer) * mean_ctx
     embed_row = w.d_model * w.elem_bytes
     vanilla = w.n_layers * layer + head + kv + embed_row
-    accept_step = vanilla + head                                   # + exit head
-    reject_extra = w.exit_layer * layer + head + kv_draft + embed_row   # the wasted draft pass
+    xb = layer + w.kv_bytes_per_position(1) * mean_ctx if w.exit_block else 0   # the transformer-layer exit head
+    accept_step = vanilla + head + xb                              # + exit head
+    reject_extra = w.exit_layer * layer + head + xb + kv_draft + embed_row   # the wasted draft pass
     return dict(vanilla=vanilla, accept_step=accept_step, reject_extra=reject_extra, layer=layer, head=head)
 
 
@@ -161,6 +162,9 @@ def main():
     ap.add_argument("--modes", default="vanilla,serial,overlap,pipeline,eesd",
                     help="pipeline = the full ceil(N/E)-stage schedule; eesd = draft-then-verify rounds (the method the "
                          "paper compares against), both reported beside the two-stage path")
+    ap.add_argument("--exit-block", type=float, default=None, metavar="DAMP",
+                    help="use the transformer-layer early-exit head; DAMP scales its output projections "
+                         "(0 = identity block: the norm head's drafts at the block's cost)")
     ap.add_argument("--gamma", type=int, default=0, help="drafts per round of the eesd mode (0 = library default, 3)")
     ap.add_argument("--engine", default="streams", choices=["streams", "persistent"])
     ap.add_argument("--pipeline-streams", type=int, default=0, help="streams of the pipeline mode (0 = library default)")
@@ -194,6 +198,8 @@ def main():
         w = w.replace(damp=args.damp)
     if args.exit_layer is not None:
         w = w.replace(exit_layer=args.exit_layer)
+    if args.exit_block is not None:
+        w = w.replace(exit_block=True, exit_block_damp=args.exit_block)
     if args.prompt_len is not None:
         w = w.replace(prompt_len=args.prompt_len)
     if args.decode_len is not None:
@@ -313,7 +319,8 @@ def main():
         "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: {w.n_layers}-layer d={w.d_model} decoder ({w.dtype}), exit layer "
                                f"{w.exit_layer}, prompt {w.prompt_len}, decode {n} tokens, batch 1, damp {w.damp}, "
-                               f"exit head {w.exit_head}",
+                               f"exit head {w.exit_head}" + (f" behind a transformer layer (damp {w.exit_block_damp})"
+                                                              if w.exit_block else ""),
                    "mode": main_mode + (f" ({n_stages} stages of {w.exit_layer} layers, one stream per stage up to 4)"
                                         if main_mode == "pipeline" else " (draft stage + verify stage on two streams)"
                                         if main_mode == "overlap" else ""),

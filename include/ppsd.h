@@ -115,10 +115,15 @@ typedef struct {
                               512 positions, beyond that one per 512) */
   int32_t eesd_gamma;      /* PPSD_MODE_EESD: drafts per round, 1..4; 0 = default (3).  (gamma + 1) * d_model
                               floats must fit the LDS of a compute unit (150 KiB) */
-  int32_t reserved[1];     /* must be zero */
+  int32_t exit_block;      /* 1: the early-exit head is one more transformer layer of the model's own structure
+                              followed by the norm head (the head of the paper's main results, Sec. 5.4 "Impact of
+                              exit head").  Its tensors are entry n_layers of the per-layer arrays, it keeps its
+                              own KV rows (rolled back with those of layers 1..E), and its output feeds the exit
+                              head only.  Per-operation engine only, no time_kernels */
 } ppsd_config;
 
-/* DEVICE pointers, BORROWED.  Per-layer entries are HOST arrays of n_layers DEVICE pointers. */
+/* DEVICE pointers, BORROWED.  Per-layer entries are HOST arrays of n_layers DEVICE pointers
+ * (n_layers + 1 with exit_block: the early-exit block last). */
 typedef struct {
   const void *embed;        /* [vocab, d_model] storage dtype */
   const void *final_norm;   /* [d_model] fp32 */

@@ -30,7 +30,7 @@ class ppsd_config(C.Structure):
                [("rope_base", C.c_float), ("rms_eps", C.c_float), ("debug_logits", C.c_int32),
                 ("use_graph", C.c_int32), ("time_kernels", C.c_int32), ("engine", C.c_int32),
                 ("prefill_loop", C.c_int32), ("pipeline_streams", C.c_int32), ("tune_wgs_per_cu", C.c_int32),
-                ("tune_attn_split", C.c_int32), ("eesd_gamma", C.c_int32), ("reserved", C.c_int32 * 1)]
+                ("tune_attn_split", C.c_int32), ("eesd_gamma", C.c_int32), ("exit_block", C.c_int32)]
 
 
 class ppsd_buffers(C.Structure):
@@ -109,6 +109,7 @@ def make_config(shape, max_seq: int, mode: int, kv_page_tokens: int = 16, debug_
     cfg.tune_wgs_per_cu = int(tune_wgs_per_cu)
     cfg.tune_attn_split = int(tune_attn_split)
     cfg.eesd_gamma = int(eesd_gamma)
+    cfg.exit_block = int(bool(getattr(shape, "exit_block", False)))
     return cfg
 
 
@@ -165,7 +166,10 @@ class Session:
         self._arrays = {}
         for name, dt in (("attn_norm", torch.float32), ("wqkv", want), ("wo", want), ("mlp_norm", torch.float32),
                          ("wgu", want), ("wdown", want)):
-            arr = (C.c_void_p * shape.n_layers)(*[ptr(t, dt) for t in weights[name]])
+            n_entries = shape.n_layers + self.cfg.exit_block
+            if len(weights[name]) != n_entries:
+                raise PpsdError(-1, f"{name} has {len(weights[name])} entries, the configuration needs {n_entries}")
+            arr = (C.c_void_p * n_entries)(*[ptr(t, dt) for t in weights[name]])
             self._arrays[name] = arr
             setattr(b, name, C.cast(arr, C.POINTER(C.c_void_p)))
         b.workspace, b.workspace_bytes = self.workspace.data_ptr(), nbytes

@@ -105,7 +105,9 @@ bool valid_config(const ppsd_config *c, const char **why) {
     REJECT((size_t)B * xs_floats(esz, c->d_model) * 4 > kBatchLdsMax, "gamma + 1 input vectors of d_model floats exceed the LDS of a compute unit");
   }
   REJECT(c->tune_attn_split < 0 || (c->tune_attn_split > 0 && c->tune_attn_split < 64), "tune_attn_split must be 0 or >= 64");
-  for (int k = 0; k < 1; ++k) REJECT(c->reserved[k] != 0, "reserved fields must be zero");
+  REJECT(c->exit_block != 0 && c->exit_block != 1, "exit_block must be 0 or 1");
+  REJECT(c->exit_block && c->engine == PPSD_ENGINE_PERSISTENT, "the transformer-layer exit head runs on the per-operation engine only");
+  REJECT(c->exit_block && c->time_kernels, "time_kernels is not available with the transformer-layer exit head");
 #undef REJECT
   return true;
 }
@@ -166,7 +168,7 @@ Layout make_layout(const ppsd_config *c) {
   L.cand_b = take(8ull * nb * n_cand);
   L.sink = take(256);
   L.logits = take(4ull * c->debug_logits * c->vocab);
-  L.kv = take((size_t)c->n_layers * L.n_pages * c->n_kv_heads * 2 * c->kv_page_tokens * c->head_dim * es);
+  L.kv = take((size_t)(c->n_layers + c->exit_block) * L.n_pages * c->n_kv_heads * 2 * c->kv_page_tokens * c->head_dim * es);
   L.total = off;
   return L;
 }
@@ -327,6 +329,27 @@ void launch_stage(Launcher &L, int role, int lo, int hi, int stage, int xin_firs
                      from_embed && l == lo, xwork);
 }
 
+// The transformer-layer early-exit head (Sec. 5.4): entry n_layers of the per-layer weights, run on
+// the layer-E hidden state in slot xin; its output (slot xwork) feeds the exit head only.  With
+// kv_only just its K/V row is appended (positions whose draft nobody needs: the prompt, the last
+// draft of a draft-then-verify round) -- later drafts attend to it.
+template <typename WT>
+void launch_exit_block(Launcher &L, int role, int stage, int xin, int xwork, bool kv_only) {
+  ppsd_ctx *x = L.x;
+  const ppsd_config &c = x->cfg;
+  const int layer = c.n_layers;
+  if (!kv_only) {
+    launch_layer<WT>(L, role, layer, stage, xin, xwork, false, xwork);
+    return;
+  }
+  const int total_pairs = (c.n_heads + 2 * c.n_kv_heads) * (c.head_dim / 2);
+  L.before(kKQkv);
+  hipLaunchKernelGGL((k_qkv<WT>), dim3(x->gemv_grid(total_pairs)), dim3(kGBlock), x->xs_bytes(c.d_model), L.s, x->cm, role,
+                     layer, xin, 0, (const WT *)x->embed, (const float *)x->attn_norm[layer], (const WT *)x->wqkv[layer],
+                     at<float>(x, x->lay.q[stage]));
+  L.after();
+}
+
 // ---------------------------------------------------------------- draft-then-verify round
 // Workgroups of a batched kernel: as many as stay resident with `lds` bytes of staged input each.
 int batch_grid(const ppsd_ctx *x, int n_tasks, size_t lds, int wgs_per_cu) {
@@ -413,8 +436,9 @@ hipError_t enqueue_eesd_round(ppsd_ctx *x) {
   // the last draft, each left in its batch slot
   for (int j = 0; j <= g; ++j) {
     launch_stage<WT>(A, kEesdDraft0 + j, 0, c.exit_layer, 0, kXStageWork0, true, kXBatchIn0 + j, kXStageWork0);
+    if (c.exit_block) launch_exit_block<WT>(A, kEesdDraft0 + j, 0, kXBatchIn0 + j, kXStageWork0, j == g);
     if (j < g) {
-      launch_head<WT>(A, kEesdDraft0 + j, kXBatchIn0 + j, false);
+      launch_head<WT>(A, kEesdDraft0 + j, c.exit_block ? kXStageWork0 : kXBatchIn0 + j, false);
       A.before(kKCommit);
       hipLaunchKernelGGL(k_eesd_pick, dim3(1), dim3(kBlock), 0, A.s, x->cm, at<const float2>(x, x->lay.cand_exit), j);
       A.after();
@@ -465,7 +489,8 @@ hipError_t enqueue_step(ppsd_ctx *x, int mode, bool two_streams, bool timed) {
       const int xin = k == 0 ? work : kXBoundRead0 + k;
       const int xout = k == S - 1 ? work : kXBoundWrite0 + k + 1;
       launch_stage<WT>(Lk, kPipeStage0 + k, lo, hi, si, xin, k == 0, xout, work);
-      if (k == 0) launch_head<WT>(Lk, kPipeStage0, kXBoundWrite0 + 1, false);
+      if (k == 0 && c.exit_block) launch_exit_block<WT>(Lk, kPipeStage0, si, kXBoundWrite0 + 1, work, false);
+      if (k == 0) launch_head<WT>(Lk, kPipeStage0, c.exit_block ? work : kXBoundWrite0 + 1, false);
       if (k == S - 1) launch_head<WT>(Lk, kPipeStage0 + k, work, true);
       if (Lk.err != hipSuccess) return Lk.err;
     }
@@ -487,7 +512,8 @@ hipError_t enqueue_step(ppsd_ctx *x, int mode, bool two_streams, bool timed) {
   }
   // draft stage: layers 1..E + exit head; its last layer writes the other hExit buffer
   launch_stage<WT>(A, kDraft, 0, c.exit_layer, 0, kXDraft, true, kHExitNext);
-  launch_head<WT>(A, kDraft, kHExitNext, false);
+  if (c.exit_block) launch_exit_block<WT>(A, kDraft, 0, kHExitNext, kXDraft, false);
+  launch_head<WT>(A, kDraft, c.exit_block ? kXDraft : kHExitNext, false);
   // verify stage: layers E+1..N + LM head on the hidden state kept from the previous step
   launch_stage<WT>(B, kVerify, c.exit_layer, c.n_layers, 1, kHExitCur, false, kXVerify);
   launch_head<WT>(B, kVerify, kXVerify, true);
@@ -505,7 +531,13 @@ hipError_t enqueue_step(ppsd_ctx *x, int mode, bool two_streams, bool timed) {
 template <typename WT>
 hipError_t enqueue_prefill_pos(ppsd_ctx *x, bool last, bool timed) {
   Launcher A{x, x->sA, timed};
-  launch_stage<WT>(A, kPrefill, 0, x->cfg.n_layers, 0, kXDraft, true, kXDraft);
+  if (x->cfg.exit_block) {
+    launch_stage<WT>(A, kPrefill, 0, x->cfg.exit_layer, 0, kXDraft, true, kXDraft);
+    launch_exit_block<WT>(A, kPrefill, 0, kXDraft, kXDraft, true);
+    launch_stage<WT>(A, kPrefill, x->cfg.exit_layer, x->cfg.n_layers, 0, kXDraft, false, kXDraft);
+  } else {
+    launch_stage<WT>(A, kPrefill, 0, x->cfg.n_layers, 0, kXDraft, true, kXDraft);
+  }
   if (last) launch_head<WT>(A, kPrefill, kXDraft, true);
   launch_commit(A, last ? 3 : 2);
   return A.err;
@@ -683,6 +715,14 @@ int prefill_mfma(ppsd_ctx *x, int n_prompt) {
       pf_launch_gemm<kPfSwiglu>(x, g, f / 64);
       g.A = M; g.rs = nullptr; g.gain = nullptr; g.W = (const bf16_t *)x->wdown[l]; g.K = f;
       pf_launch_gemm<kPfResid>(x, g, d / kPfBN);
+      if (c.exit_block && l == c.exit_layer - 1) {
+        // K/V rows of the early-exit block for the prompt positions: its QKV projection on h^E
+        // (the q it also writes is overwritten by the next layer)
+        const int xl = c.n_layers;
+        hipLaunchKernelGGL(k_pf_rowscale, dim3((nv + waves - 1) / waves), dim3(kPfBlock), 0, x->sA, (const float *)X, d, nv, c.rms_eps, rs);
+        g.layer = xl; g.A = X; g.rs = rs; g.gain = (const float *)x->attn_norm[xl]; g.W = (const bf16_t *)x->wqkv[xl]; g.K = d;
+        pf_launch_gemm<kPfQkv>(x, g, qkv_heads);
+      }
       HIP_TRY(hipGetLastError());
     }
     if (c0 + nv == n_prompt)
@@ -732,7 +772,7 @@ int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *b, ppsd_ctx **
   if (b->workspace_bytes < lay.total)
     return fail(PPSD_ECAPACITY, "workspace has %zu bytes, %zu needed", b->workspace_bytes, lay.total);
   if ((uintptr_t)b->workspace % kAlign) return fail(PPSD_EARG, "workspace must be 256-byte aligned");
-  for (int l = 0; l < cfg->n_layers; ++l) {
+  for (int l = 0; l < cfg->n_layers + cfg->exit_block; ++l) {
     const void *ps[6] = {b->attn_norm[l], b->wqkv[l], b->wo[l], b->mlp_norm[l], b->wgu[l], b->wdown[l]};
     for (const void *p : ps) {
       if (!p) return fail(PPSD_EARG, "layer %d has a null weight pointer", l);
@@ -760,12 +800,12 @@ int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *b, ppsd_ctx **
   x->ws = (char *)b->workspace;
   x->embed = b->embed; x->final_norm = b->final_norm; x->lm_head = b->lm_head;
   x->exit_norm = b->exit_norm; x->exit_head = b->exit_head;
-  x->attn_norm.assign(b->attn_norm, b->attn_norm + cfg->n_layers);
-  x->wqkv.assign(b->wqkv, b->wqkv + cfg->n_layers);
-  x->wo.assign(b->wo, b->wo + cfg->n_layers);
-  x->mlp_norm.assign(b->mlp_norm, b->mlp_norm + cfg->n_layers);
-  x->wgu.assign(b->wgu, b->wgu + cfg->n_layers);
-  x->wdown.assign(b->wdown, b->wdown + cfg->n_layers);
+  x->attn_norm.assign(b->attn_norm, b->attn_norm + cfg->n_layers + cfg->exit_block);
+  x->wqkv.assign(b->wqkv, b->wqkv + cfg->n_layers + cfg->exit_block);
+  x->wo.assign(b->wo, b->wo + cfg->n_layers + cfg->exit_block);
+  x->mlp_norm.assign(b->mlp_norm, b->mlp_norm + cfg->n_layers + cfg->exit_block);
+  x->wgu.assign(b->wgu, b->wgu + cfg->n_layers + cfg->exit_block);
+  x->wdown.assign(b->wdown, b->wdown + cfg->n_layers + cfg->exit_block);
   x->sA = (hipStream_t)b->stream_draft;
   x->sB = (hipStream_t)b->stream_verify;
 
