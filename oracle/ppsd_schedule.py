@@ -63,6 +63,7 @@ class PPSDSession:
     full: bool = False
     h_exit: torch.Tensor = None     # h_t^E when full
     draft: int = -1                 # d_{t+1} when full
+    x_prompt: torch.Tensor = None   # the full model's hidden state behind the last prompt position
     stats: PPSDStats = field(default_factory=PPSDStats)
 
 
@@ -83,7 +84,7 @@ def prefill(dec: Decoder, prompt: Sequence[int], max_seq: int) -> PPSDSession:
         else:
             x = run_layers(dec, kv, dec.embed([tok])[0], pos, range(s.n_layers))
     tok0 = argmax_lowest(dec.head_logits(x, "lm"))
-    return PPSDSession(dec=dec, kv=kv, t=len(prompt), last_token=tok0, full=False)
+    return PPSDSession(dec=dec, kv=kv, t=len(prompt), last_token=tok0, full=False, x_prompt=x)
 
 
 def step(ss: PPSDSession, out: List[int]) -> None:
