@@ -120,6 +120,17 @@ typedef struct {
                               exit head").  Its tensors are entry n_layers of the per-layer arrays, it keeps its
                               own KV rows (rolled back with those of layers 1..E), and its output feeds the exit
                               head only.  Per-operation engine only, no time_kernels */
+  float   temperature;     /* 0: greedy heads (argmax), the default.  > 0 (>= 1e-4): stochastic verification
+                              (Sec. 3.1, Eq. 1-2) in PPSD_MODE_SERIAL / PPSD_MODE_OVERLAP -- the draft is sampled
+                              from softmax(exit logits / temperature) = p, accepted with probability
+                              min(1, q(d) / p(d)) against q = softmax(LM logits / temperature), and a rejected
+                              draft is replaced by a token from normalise(max(0, q - p)), so every committed token
+                              is q-distributed -- and plain sampling from q in PPSD_MODE_VANILLA and for token #0.
+                              Sampling is by inverse CDF in index order.  Per-operation engine only */
+  uint32_t sample_seed;    /* the uniform for (position, purpose) is the top 24 bits of splitmix64's output
+                              function applied to seed ^ position * 0xD1342543DE82EF95 ^ purpose *
+                              0xA0761D6478BD642F (64-bit wrapping), purpose = 0 draft, 1 acceptance,
+                              2 replacement, 3 plain sampling: a pure function of the three, whatever the schedule */
 } ppsd_config;
 
 /* DEVICE pointers, BORROWED.  Per-layer entries are HOST arrays of n_layers DEVICE pointers

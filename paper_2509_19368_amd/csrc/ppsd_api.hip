@@ -58,6 +58,7 @@ struct Layout {
   size_t layer_ptrs, bar, abort_flag, trace, cand_counts;
   size_t pf_x, pf_q, pf_ao, pf_m, pf_rs;   // MFMA prefill chunk buffers (0 bytes when not used)
   size_t qb, ab, mb, partials_b, counters_b, cand_b;   // batched verify pass (0 bytes unless PPSD_MODE_EESD)
+  size_t logits_lm, logits_exit, probs;                // sampling (0 bytes unless temperature > 0)
   bool pf;
   size_t total;
   int n_pages, n_splits, head_blocks;
@@ -105,6 +106,12 @@ bool valid_config(const ppsd_config *c, const char **why) {
     REJECT((size_t)B * xs_floats(esz, c->d_model) * 4 > kBatchLdsMax, "gamma + 1 input vectors of d_model floats exceed the LDS of a compute unit");
   }
   REJECT(c->tune_attn_split < 0 || (c->tune_attn_split > 0 && c->tune_attn_split < 64), "tune_attn_split must be 0 or >= 64");
+  REJECT(!(c->temperature >= 0.0f) || c->temperature > 1.0e4f, "temperature must be in [0, 1e4] (0 = greedy)");
+  REJECT(c->temperature > 0.0f && c->temperature < 1.0e-4f, "a positive temperature must be at least 1e-4");
+  REJECT(c->temperature > 0.0f && (c->mode == PPSD_MODE_PIPELINE || c->mode == PPSD_MODE_EESD),
+         "sampling (temperature > 0) is available in the vanilla and the two-stage modes");
+  REJECT(c->temperature > 0.0f && (c->engine != PPSD_ENGINE_STREAMS || c->time_kernels),
+         "sampling (temperature > 0) runs on the per-operation engine, without time_kernels");
   REJECT(c->exit_block != 0 && c->exit_block != 1, "exit_block must be 0 or 1");
   REJECT(c->exit_block && c->engine == PPSD_ENGINE_PERSISTENT, "the transformer-layer exit head runs on the per-operation engine only");
   REJECT(c->exit_block && c->time_kernels, "time_kernels is not available with the transformer-layer exit head");
@@ -166,6 +173,10 @@ Layout make_layout(const ppsd_config *c) {
   L.partials_b = take(4ull * nb * c->n_heads * kMaxSplits * (c->head_dim + 2));
   L.counters_b = take(4ull * nb * kCounterStride * c->n_kv_heads);
   L.cand_b = take(8ull * nb * n_cand);
+  const size_t nv = c->temperature > 0.0f ? (size_t)c->vocab : 0;
+  L.logits_lm = take(4ull * nv);
+  L.logits_exit = take(4ull * nv);
+  L.probs = take(4ull * 2 * nv);
   L.sink = take(256);
   L.logits = take(4ull * c->debug_logits * c->vocab);
   L.kv = take((size_t)(c->n_layers + c->exit_block) * L.n_pages * c->n_kv_heads * 2 * c->kv_page_tokens * c->head_dim * es);
@@ -300,15 +311,24 @@ void launch_head(Launcher &L, int role, int xin_sel, bool is_lm) {
   const ppsd_config &c = x->cfg;
   float2 *cand = at<float2>(x, is_lm ? x->lay.cand_lm : x->lay.cand_exit);
   float *logits = c.debug_logits > 0 ? at<float>(x, x->lay.logits) : nullptr;
+  float *full = c.temperature > 0.0f ? at<float>(x, is_lm ? x->lay.logits_lm : x->lay.logits_exit) : nullptr;
   L.before(kKHead);
   hipLaunchKernelGGL((k_head<WT>), dim3(x->cm.dm.head_blocks), dim3(kGBlock), x->xs_bytes(c.d_model), L.s,
                      x->cm, role, xin_sel, (const float *)(is_lm ? x->final_norm : x->exit_norm),
-                     (const WT *)(is_lm ? x->lm_head : x->exit_head), cand, logits, is_lm ? 1 : 0);
+                     (const WT *)(is_lm ? x->lm_head : x->exit_head), cand, logits, is_lm ? 1 : 0, full);
   L.after();
 }
 
 void launch_commit(Launcher &L, int kind) {
   ppsd_ctx *x = L.x;
+  if (x->cfg.temperature > 0.0f && kind != 2) {   // sampling: kinds 0 (vanilla), 1 (two-stage step), 3 (token #0)
+    L.before(kKCommit);
+    hipLaunchKernelGGL(k_commit_sample, dim3(1), dim3(kSBlock), 0, L.s, x->cm, kind, at<const float>(x, x->lay.logits_lm),
+                       at<const float>(x, x->lay.logits_exit), at<float>(x, x->lay.probs), 1.0f / x->cfg.temperature,
+                       (uint32_t)x->cfg.sample_seed, at<int32_t>(x, x->lay.out_tokens), at<int32_t>(x, x->lay.drafts));
+    L.after();
+    return;
+  }
   L.before(kKCommit);
   hipLaunchKernelGGL(k_commit, dim3(1), dim3(kBlock), 0, L.s, x->cm, kind, at<const float2>(x, x->lay.cand_lm),
                      at<const float2>(x, x->lay.cand_exit), at<int32_t>(x, x->lay.out_tokens),

@@ -102,7 +102,7 @@ int main(int argc, char **argv) {
   });
   run("k_head", (size_t)V * d * 2, [&](const bf16_t *w) {
     hipLaunchKernelGGL((k_head<bf16_t>), dim3(c.dm.head_blocks), dim3(kGBlock), (size_t)xs_floats(2, d) * 4, 0, c, (int)kVanilla, (int)kXDraft, gain,
-                       w, cand, (float *)nullptr, 1);
+                       w, cand, (float *)nullptr, 1, (float *)nullptr);
   });
   return 0;
 }

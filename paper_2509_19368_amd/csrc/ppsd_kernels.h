@@ -349,10 +349,12 @@ __global__ __launch_bounds__(kGBlock) void k_gate_up(Common c, int role, int xin
 // a8 / a9: head = RMSNorm + vocab projection + argmax (exit head and LM head share this kernel).
 // A task is two consecutive vocabulary rows.  Each workgroup reduces its rows to one
 // (value, index) candidate in cand[blockIdx.x]; the commit kernel finishes the reduction over
-// gridDim.x candidates.  logits_log != nullptr additionally stores the logits (parity harness).
+// gridDim.x candidates.  logits_log != nullptr additionally stores the logits (parity harness);
+// logits_out != nullptr receives all V logits of this head (sampling needs the distribution).
 template <typename WT>
 __global__ __launch_bounds__(kGBlock) void k_head(Common c, int role, int xin_sel, const float *gain,
-                                                  const WT *W, float2 *cand, float *logits_log, int is_lm) {
+                                                  const WT *W, float2 *cand, float *logits_log, int is_lm,
+                                                  float *logits_out) {
   extern __shared__ __align__(16) float xs[];
   __shared__ float red[kGWaves];
   __shared__ float bv[kGWaves];
@@ -389,6 +391,7 @@ __global__ __launch_bounds__(kGBlock) void k_head(Common c, int role, int xin_se
     if (better(s0, r, best, besti)) { best = s0; besti = r; }
     if (r + 1 < V && better(s1, r + 1, best, besti)) { best = s1; besti = r + 1; }
     if (lrow && lane == 0) { lrow[r] = s0; if (r + 1 < V) lrow[r + 1] = s1; }
+    if (logits_out && lane == 0) { logits_out[r] = s0; if (r + 1 < V) logits_out[r + 1] = s1; }
   });
   if (lane == 0) { bv[wave] = best; bi[wave] = besti; }
   __syncthreads();
@@ -551,6 +554,192 @@ __global__ __launch_bounds__(kBlock) void k_commit(Common c, int kind, const flo
   __shared__ float sv[kWavesPerBlock];
   __shared__ int si_[kWavesPerBlock];
   commit_step<kBlock>(c, kind, cand_lm, c.dm.head_blocks, cand_exit, c.dm.head_blocks, out_tokens, drafts_log, sv, si_);
+}
+
+// ------------------------------------------------------------------------------------------
+// Stochastic verification (Sec. 3.1, Eq. 1-2): sampled drafts, acceptance with probability
+// min(1, q(d) / p(d)), a rejected draft replaced by a token from normalise(max(0, q - p)).
+//
+// Random numbers are a pure function of (seed, position, purpose): the splitmix64 output function
+// on a key built from the three, reduced to a 24-bit fraction (exact in fp32), so the stream does
+// not depend on the schedule.
+constexpr int kSBlock = 1024;                        // threads of the sampling workgroup
+constexpr int kSWaves = kSBlock / kWave;
+enum Purpose : int { kPurDraft = 0, kPurAccept = 1, kPurResample = 2, kPurVanilla = 3 };
+
+__device__ __forceinline__ float uniform24(uint32_t seed, int pos, int purpose) {
+  unsigned long long z = (unsigned long long)seed ^ ((unsigned long long)pos * 0xD1342543DE82EF95ull) ^
+                         ((unsigned long long)purpose * 0xA0761D6478BD642Full);
+  z += 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  z ^= z >> 31;
+  return (float)(uint32_t)(z >> 40) * (1.0f / 16777216.0f);
+}
+
+// Workgroup-wide helpers of the sampling kernel (kSBlock threads; buf: kSWaves floats of LDS).
+__device__ __forceinline__ float sblock_max(float v, float *buf) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) buf[threadIdx.x >> 6] = v;
+  __syncthreads();
+  float m = buf[0];
+  for (int w = 1; w < kSWaves; ++w) m = fmaxf(m, buf[w]);
+  return m;
+}
+
+// Inverse-CDF sampling in index order over V non-negative weights wf(i): the first k with
+// sum_{i<=k} w_i > u * sum_i w_i.  Thread j owns the contiguous chunk [j*per, (j+1)*per); sums run
+// in index order inside a chunk and in thread order across chunks, and the threshold is taken
+// against the very total those sums give, so the decision is a deterministic function of the weights.
+// Returns the index in every thread; *total_out (if given) receives the total.  scan: kSBlock floats of LDS.
+template <typename WF>
+__device__ __forceinline__ int sample_index(WF &&wf, int V, float u, float *scan, int *s_pick, float *total_out) {
+  const int per = (V + kSBlock - 1) / kSBlock;
+  const int lo = threadIdx.x * per, hi = min(V, lo + per);
+  float mine = 0.f;
+  for (int i = lo; i < hi; ++i) mine += wf(i);
+  __syncthreads();
+  scan[threadIdx.x] = mine;
+  __syncthreads();
+  if (threadIdx.x == 0) {                       // exclusive scan in thread order (1024 adds: negligible)
+    float run = 0.f;
+    for (int j = 0; j < kSBlock; ++j) { const float v = scan[j]; scan[j] = run; run += v; }
+    scan[kSBlock] = run;
+    *s_pick = -1;
+  }
+  __syncthreads();
+  const float total = scan[kSBlock];
+  const float thr = u * total;
+  const float before = scan[threadIdx.x];
+  const float after = threadIdx.x + 1 < kSBlock ? scan[threadIdx.x + 1] : total;
+  if (mine > 0.f && before <= thr && after > thr) {   // exactly one thread: the prefix sums are monotone
+    float run = before;
+    int k = -1;
+    for (int i = lo; i < hi; ++i) {
+      run += wf(i);
+      if (run > thr) { k = i; break; }
+    }
+    if (k < 0) {                                 // rounding: the chunk's own sum fell short; its last positive weight
+      for (int i = hi - 1; i >= lo; --i) if (wf(i) > 0.f) { k = i; break; }
+    }
+    *s_pick = k;
+  }
+  __syncthreads();
+  int k = *s_pick;
+  if (k < 0) {                                   // u * total rounded up to the total: the last positive weight
+    if (threadIdx.x == 0) {
+      int last = 0;
+      for (int i = V - 1; i >= 0; --i) if (wf(i) > 0.f) { last = i; break; }
+      *s_pick = last;
+    }
+    __syncthreads();
+    k = *s_pick;
+  }
+  if (total_out) *total_out = total;
+  __syncthreads();
+  return k;
+}
+
+// One step's decision with sampling.  kind: 0 vanilla (token ~ q), 1 two-stage PPSD step,
+// 3 last prefill position (token #0 ~ q).  logits_lm / logits_exit: V floats each, written by the
+// heads of this step.  probs: [2][V], the distribution each in-flight draft was sampled from
+// (buffer st->cur & 1 belongs to the draft being verified, the other receives the new draft's).
+__global__ __launch_bounds__(kSBlock) void k_commit_sample(Common c, int kind, const float *logits_lm,
+                                                           const float *logits_exit, float *probs, float inv_temp,
+                                                           uint32_t seed, int32_t *out_tokens, int32_t *drafts_log) {
+  __shared__ float scan[kSBlock + 1];
+  __shared__ float buf[kSWaves];
+  __shared__ int s_pick;
+  DevState *st = c.st;
+  const int V = c.dm.V;
+  if (kind == 3) {
+    if (!(st->prefill_pos < st->prefill_len)) return;
+  } else if (!(st->n_out < st->target)) return;
+
+  auto softmax_weights = [&](const float *lg, float &mx) {
+    float m = -INFINITY;
+    for (int i = threadIdx.x; i < V; i += kSBlock) m = fmaxf(m, lg[i]);
+    mx = sblock_max(m, buf);
+  };
+
+  if (kind == 0 || kind == 3) {
+    float mq;
+    softmax_weights(logits_lm, mq);
+    const int pos = kind == 3 ? st->prefill_len : st->t + 1;        // the position the token will occupy
+    const int tok = sample_index([&](int i) { return __expf((logits_lm[i] - mq) * inv_temp); }, V,
+                                 uniform24(seed, pos, kPurVanilla), scan, &s_pick, nullptr);
+    if (threadIdx.x == 0) {
+      if (kind == 3) {
+        st->prefill_pos += 1;
+        st->t = st->prefill_len; st->last_token = tok; st->full = 0; st->gen_count = 1;
+        drafts_log[0] = -1;
+      } else {
+        out_tokens[st->n_out] = tok;
+        drafts_log[st->gen_count] = -1;
+        st->n_out += 1; st->gen_count += 1; st->t += 1; st->last_token = tok;
+        st->stats[0] += 1;
+      }
+    }
+    return;
+  }
+
+  // ---- two-stage PPSD step
+  const int full = st->full;
+  const int cur = st->cur & 1;
+  float *p_next = probs + (size_t)(cur ^ 1) * V;
+  const float *p_cur = probs + (size_t)cur * V;
+  // the draft stage always ran: its distribution, kept for the verification one step later, and its draft
+  float mp;
+  softmax_weights(logits_exit, mp);
+  float sp;
+  const int pos_d = (full ? st->t + 1 : st->t) + 1;                  // the position the new draft is for
+  const int d_next = sample_index([&](int i) { return __expf((logits_exit[i] - mp) * inv_temp); }, V,
+                                  uniform24(seed, pos_d, kPurDraft), scan, &s_pick, &sp);
+  for (int i = threadIdx.x; i < V; i += kSBlock) p_next[i] = __expf((logits_exit[i] - mp) * inv_temp) / sp;
+
+  int tok = -1, ok = 0;
+  const int d = st->draft;
+  if (full) {
+    const int pos = st->t + 1;                                         // the position being decided
+    float mq;
+    softmax_weights(logits_lm, mq);
+    // total of the target's weights, summed the way sample_index sums
+    float sq;
+    (void)sample_index([&](int i) { return __expf((logits_lm[i] - mq) * inv_temp); }, V, 0.f, scan, &s_pick, &sq);
+    const float qd = __expf((logits_lm[d] - mq) * inv_temp) / sq;
+    const float pd = p_cur[d];
+    ok = uniform24(seed, pos, kPurAccept) * pd <= qd;
+    if (ok) {
+      tok = d;
+    } else {
+      auto resid = [&](int i) { return fmaxf(0.f, __expf((logits_lm[i] - mq) * inv_temp) / sq - p_cur[i]); };
+      float sr;
+      tok = sample_index(resid, V, uniform24(seed, pos, kPurResample), scan, &s_pick, &sr);
+      if (!(sr > 0.f))                                               // q == p to rounding: take the token from q
+        tok = sample_index([&](int i) { return __expf((logits_lm[i] - mq) * inv_temp); }, V,
+                           uniform24(seed, pos, kPurResample), scan, &s_pick, nullptr);
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    if (!full) {
+      st->draft = d_next; st->full = 1; st->cur ^= 1; st->stats[5] += 1;
+    } else {
+      out_tokens[st->n_out] = tok;
+      drafts_log[st->gen_count] = d;
+      st->n_out += 1; st->gen_count += 1;
+      st->stats[0] += 1; st->stats[1] += 1; st->stats[4] += 1;
+      if (ok) {
+        st->stats[2] += 1; st->draft = d_next; st->cur ^= 1;
+      } else {
+        st->stats[3] += 1; st->stats[6] += 1; st->full = 0;
+      }
+      st->t += 1;
+      st->last_token = tok;
+    }
+  }
 }
 
 // Host-requested state edits (tiny, one thread): new prefill / new decode target.
