@@ -165,6 +165,9 @@ def main():
     ap.add_argument("--exit-block", type=float, default=None, metavar="DAMP",
                     help="use the transformer-layer early-exit head; DAMP scales its output projections "
                          "(0 = identity block: the norm head's drafts at the block's cost)")
+    ap.add_argument("--temperature", type=float, default=0.0,
+                    help="> 0: stochastic verification (sampled drafts, Eq. 2) in the vanilla / serial / overlap modes")
+    ap.add_argument("--sample-seed", type=int, default=2509)
     ap.add_argument("--gamma", type=int, default=0, help="drafts per round of the eesd mode (0 = library default, 3)")
     ap.add_argument("--engine", default="streams", choices=["streams", "persistent"])
     ap.add_argument("--pipeline-streams", type=int, default=0, help="streams of the pipeline mode (0 = library default)")
@@ -233,10 +236,13 @@ def main():
             continue
         if mode == P.MODE_EESD and (engine != P.ENGINE_STREAMS or 4 * 4 * w.d_model > 150 * 1024):
             continue
+        if args.temperature > 0 and mode in (P.MODE_PIPELINE, P.MODE_EESD):
+            continue
         ss = P.Session(w, W, max_seq=max_seq, mode=mode, engine=engine, prefill_loop=args.prefill_loop,
                        pipeline_streams=args.pipeline_streams if mode == P.MODE_PIPELINE else 0,
                        tune_wgs_per_cu=args.wgs_per_cu, tune_attn_split=args.attn_split,
-                       eesd_gamma=args.gamma if mode == P.MODE_EESD else 0)
+                       eesd_gamma=args.gamma if mode == P.MODE_EESD else 0,
+                       temperature=args.temperature, sample_seed=args.sample_seed)
         times, st, toks = run_generations(ss, prompt, n, args.steps, args.warmup, torch)
         prefill_ms = min(ss.prefill_ms)
         ss.close()
@@ -247,7 +253,7 @@ def main():
     # vanilla and the PPSD schedules run the same kernels per token: their streams must be identical.  The
     # batched verify pass of the eesd mode adds the down-projection in column slabs (another rounding
     # order), so on bf16 models its stream may leave the others at a near-tie; that is reported.
-    exact = {k: v for k, v in streams.items() if k != "eesd"}
+    exact = {k: v for k, v in streams.items() if k != "eesd" and not (args.temperature > 0 and k == "vanilla")}
     if len(exact) > 1:
         first = next(iter(exact.values()))
         if any(s != first for s in exact.values()):
@@ -324,7 +330,9 @@ def main():
                    "mode": main_mode + (f" ({n_stages} stages of {w.exit_layer} layers, one stream per stage up to 4)"
                                         if main_mode == "pipeline" else " (draft stage + verify stage on two streams)"
                                         if main_mode == "overlap" else ""),
-                   "engine": args.engine, "tokens_per_step": n},
+                   "engine": args.engine, "tokens_per_step": n,
+                   **({"temperature": args.temperature, "sample_seed": args.sample_seed,
+                       "verification": "stochastic (Eq. 2)"} if args.temperature > 0 else {})},
         "acceptance_rate": alpha,
         "ms_per_token": r["ms_per_token"],
         "modes": {k: {"tokens_per_s": v["tokens_per_s"], "ms_per_token": v["ms_per_token"],
