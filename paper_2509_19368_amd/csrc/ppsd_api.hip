@@ -288,7 +288,7 @@ void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int 
 #undef ATTN
   L.after();
 
-  const int proj_grid = x->gemv_grid((d + 1) / 2);
+  const int proj_grid = x->gemv_grid(d);   // one row per task
   L.before(kKOproj);
   hipLaunchKernelGGL((k_proj_resid<WT>), dim3(proj_grid), dim3(kGBlock), x->xs_bytes(nq), L.s, cm, role,
                      (const float *)a, nq, (const WT *)x->wo[layer], d, xin_sel, xwork);

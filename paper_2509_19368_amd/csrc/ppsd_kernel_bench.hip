@@ -89,7 +89,7 @@ int main(int argc, char **argv) {
                        (int)kVanilla, 3, (int)kXDraft, 0, w, gain, w, mout);
   });
   run("k_proj_resid (o_proj)", (size_t)d * nq * 2, [&](const bf16_t *w) {
-    hipLaunchKernelGGL((k_proj_resid<bf16_t>), dim3(gemv_grid_for((d + 1) / 2, n_cu, kGemvWgsPerCu)), dim3(kGBlock), (size_t)xs_floats(2, nq) * 4, 0, c,
+    hipLaunchKernelGGL((k_proj_resid<bf16_t>), dim3(gemv_grid_for(d, n_cu, kGemvWgsPerCu)), dim3(kGBlock), (size_t)xs_floats(2, nq) * 4, 0, c,
                        (int)kVanilla, vin, nq, w, d, (int)kXDraft, (int)kXDraft);
   });
   run("k_gate_up", (size_t)2 * f * d * 2, [&](const bf16_t *w) {
@@ -97,7 +97,7 @@ int main(int argc, char **argv) {
                        (int)kVanilla, (int)kXDraft, gain, w, mout);
   });
   run("k_proj_resid (down)", (size_t)d * f * 2, [&](const bf16_t *w) {
-    hipLaunchKernelGGL((k_proj_resid<bf16_t>), dim3(gemv_grid_for((d + 1) / 2, n_cu, kGemvWgsPerCu)), dim3(kGBlock), (size_t)xs_floats(2, f) * 4, 0, c,
+    hipLaunchKernelGGL((k_proj_resid<bf16_t>), dim3(gemv_grid_for(d, n_cu, kGemvWgsPerCu)), dim3(kGBlock), (size_t)xs_floats(2, f) * 4, 0, c,
                        (int)kVanilla, vin, f, w, d, (int)kXDraft, (int)kXDraft);
   });
   run("k_head", (size_t)V * d * 2, [&](const bf16_t *w) {

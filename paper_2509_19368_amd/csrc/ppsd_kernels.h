@@ -286,7 +286,11 @@ __global__ __launch_bounds__(kGBlock) void k_attn(Common c, int role, int layer,
 
 // ------------------------------------------------------------------------------------------
 // a5 / a7: out[r] = resid[r] + W[r,:] . vin   (o_proj and down_proj with the residual add fused).
-// A task is two consecutive rows.  Dynamic LDS = C floats.
+// A task is ONE row (a trip = four column blocks of it): these matrices have few rows (d), and with
+// two rows per wave only 8 waves per CU would be streaming; one row per wave gives 16 (measured on the
+// 7B shapes: o_proj 10.3 -> 8.7 us, down 21.1 -> 18.7 us).  Per row the products are added in the same
+// order as in the two-row form.  Dynamic LDS = C floats, padded to whole column blocks.
+constexpr int kProjTripBlocks = 4;
 template <typename WT>
 __global__ __launch_bounds__(kGBlock) void k_proj_resid(Common c, int role, const float *vin, int C,
                                                         const WT *W, int n_rows, int resid_sel, int out_sel) {
@@ -295,23 +299,32 @@ __global__ __launch_bounds__(kGBlock) void k_proj_resid(Common c, int role, cons
   in.issue(vin, C);                       // the input buffer's address never depends on the state
   const StageIn si = stage_in(c, role);
   if (!si.active) return;
+  constexpr int KB = kProjTripBlocks;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int n_tasks = (n_rows + 1) >> 1;
   const int gw = blockIdx.x * kGWaves + wave, tw = gridDim.x * kGWaves;
-  const WT *rows[kTripRows];
-  auto set_rows = [&](int task) {
-    rows[0] = W + (size_t)(2 * task) * C;
-    rows[1] = W + (size_t)min(2 * task + 1, n_rows - 1) * C;
-  };
-  Trip<WT, kTripRows, kTripBlocks> trip;
-  if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(C), C); }
+  const int nblk = col_blocks<WT>(C);
+  const WT *rows[1];
+  Trip<WT, 1, KB> trip;
+  if (gw < n_rows) { rows[0] = W + (size_t)gw * C; trip_load<WT, 1, KB>(trip, rows, 0, nblk, C); }
   in.template finish<WT>(C, xs);
   const float *resid = xslot(c, resid_sel);
   float *out = xslot(c, out_sel);
-  gemv_tasks<WT>(trip, rows, gw, n_tasks, tw, C, xs, set_rows, [&](int task, float s0, float s1) {
-    const int r = 2 * task + lane;
-    if (lane < 2 && r < n_rows) out[r] = resid[r] + (lane == 0 ? s0 : s1);
-  });
+  for (int task = gw; task < n_rows;) {
+    float acc[1] = {0.f};
+    const int next = task + tw;
+    for (int cb = 0; cb < nblk; cb += KB) {
+      trip_consume<WT, 1, KB>(trip, xs, cb, C, acc);
+      if (cb + KB < nblk) {
+        trip_load<WT, 1, KB>(trip, rows, cb + KB, nblk, C);
+      } else if (next < n_rows) {
+        rows[0] = W + (size_t)next * C;
+        trip_load<WT, 1, KB>(trip, rows, 0, nblk, C);
+      }
+    }
+    const float s0 = wave_sum(acc[0]);
+    if (lane == 0) out[task] = resid[task] + s0;
+    task = next;
+  }
 }
 
 // ------------------------------------------------------------------------------------------
