@@ -24,11 +24,11 @@ HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE (scaled by reference
 # dispatches of known size), 7B shapes: profiles/weight_streaming_kernels_7B_shapes_pmc.md
 MEASURED_TRAFFIC_BYTES = {
-    ("C2", "gate_up"): 88246.2 * 2048 + 43.2 * 1024,
-    ("C2", "qkv"): 49344.5 * 2048 + 48.0 * 1024,
-    ("C2", "head"): 128191.4 * 2048 + 32.0 * 1024,
-    ("C2", "o_proj"): 16515.5 * 2048 + 16.0 * 1024,
-    ("C2", "down"): 44273.4 * 2048 + 16.0 * 1024,
+    ("C2", "gate_up"): 88234.7 * 2048 + 43.1 * 1024,
+    ("C2", "qkv"): 49335.5 * 2048 + 48.0 * 1024,
+    ("C2", "head"): 128177.9 * 2048 + 20.8 * 1024,
+    ("C2", "o_proj"): 16513.5 * 2048 + 16.0 * 1024,
+    ("C2", "down"): 44277.2 * 2048 + 16.0 * 1024,
 }
 
 
@@ -295,16 +295,21 @@ def main():
         ss.close()
         ctx_t = w.prompt_len + 1 + min(n, 32) / 2.0
         kb = kernel_bytes(w, ctx_t)
+        # an interval between two events holds one kernel and one event; the event's own cost, measured
+        # live on the same stream (events back to back, no kernel), is taken off
+        ev_us = kt.pop("event_overhead_us")
         ktimes = {}
         for k, v in kt.items():
             if v["launches"] and k in kb:
-                us = v["total_us"] / v["launches"]
-                ktimes[k] = dict(avg_us=us, launches=v["launches"], bytes=kb[k], gbps=kb[k] / us / 1e3)
+                raw = v["total_us"] / v["launches"]
+                us = raw - ev_us
+                ktimes[k] = dict(avg_us=us, avg_interval_us=raw, launches=v["launches"], bytes=kb[k], gbps=kb[k] / us / 1e3)
         dom = max((k for k in ktimes), key=lambda k: ktimes[k]["avg_us"] * ktimes[k]["launches"])
         roofline = dict(bound="hbm", kernel=dom, achieved=ktimes[dom]["gbps"], peak=HBM_PEAK_GBPS, unit="GB/s",
                         frac=ktimes[dom]["gbps"] / HBM_PEAK_GBPS,
                         traffic=MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
-                        avg_launch_us=ktimes[dom]["avg_us"], bytes_per_launch=ktimes[dom]["bytes"])
+                        avg_launch_us=ktimes[dom]["avg_us"], bytes_per_launch=ktimes[dom]["bytes"],
+                        event_interval_us=ktimes[dom]["avg_interval_us"], event_overhead_us=ev_us)
 
     # bytes the schedule really moved per committed token (wasted drafts included)
     moved_per_token = None

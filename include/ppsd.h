@@ -99,7 +99,7 @@ typedef struct {
                               tokens (token #0 = the one prefill returns) for ppsd_read_logits */
   int32_t use_graph;       /* 1: replay one captured HIP graph per step; 0: launch kernels directly */
   int32_t time_kernels;    /* 1: profiling mode -- direct launches on one stream with a HIP event
-                              pair around every kernel, totals via ppsd_kernel_times (slow) */
+                              between consecutive kernels, totals via ppsd_kernel_times (slow) */
   int32_t engine;          /* PPSD_ENGINE_*: how a step is executed on the GPU */
   int32_t prefill_loop;    /* 0: prefill on the matrix cores (MFMA GEMMs over chunks of the prompt) when the
                               configuration allows it (bf16, head_dim 128, d_model % 128 == 0,
@@ -179,8 +179,11 @@ typedef struct {
 
 #define PPSD_N_KERNEL_KINDS 7   /* qkv, attention, o_proj, gate_up, down, head, commit */
 typedef struct {
-  double  total_us[PPSD_N_KERNEL_KINDS];  /* sum of event-measured durations of ACTIVE launches */
+  double  total_us[PPSD_N_KERNEL_KINDS];  /* sum of event-to-event intervals around ACTIVE launches */
   int64_t launches[PPSD_N_KERNEL_KINDS];
+  double  event_overhead_us;              /* what one event adds to such an interval, measured on the same stream
+                                             at the first profiled step: empty kernels with an event after each
+                                             against empty kernels back to back.  Included in total_us */
 } ppsd_kernel_times_t;
 
 /* Bytes of workspace a context with this configuration needs.  0 if cfg is invalid. */

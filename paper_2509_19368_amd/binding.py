@@ -49,7 +49,7 @@ class ppsd_stats_t(C.Structure):
 
 
 class ppsd_kernel_times_t(C.Structure):
-    _fields_ = [("total_us", C.c_double * 7), ("launches", C.c_int64 * 7)]
+    _fields_ = [("total_us", C.c_double * 7), ("launches", C.c_int64 * 7), ("event_overhead_us", C.c_double)]
 
 
 _lib = None
@@ -217,7 +217,9 @@ class Session:
     def kernel_times(self) -> dict:
         kt = ppsd_kernel_times_t()
         _check(self.lib.ppsd_kernel_times(self._ctx, C.byref(kt)))
-        return {k: {"total_us": kt.total_us[i], "launches": kt.launches[i]} for i, k in enumerate(KERNEL_KINDS)}
+        out = {k: {"total_us": kt.total_us[i], "launches": kt.launches[i]} for i, k in enumerate(KERNEL_KINDS)}
+        out["event_overhead_us"] = kt.event_overhead_us
+        return out
 
     def trace_request(self, step: int, workgroup: int = 0):
         _check(self.lib.ppsd_trace_request(self._ctx, step, workgroup))

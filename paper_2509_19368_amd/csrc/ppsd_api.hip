@@ -230,32 +230,41 @@ namespace {
 
 template <typename T> T *at(ppsd_ctx *x, size_t off) { return reinterpret_cast<T *>(x->ws + off); }
 
-// Launch helper: in profiling mode brackets the kernel with an event pair.
+// Launch helper.  In profiling mode (all launches on one stream) one event is recorded at the start
+// of the step and one after every kernel: kernel i lasted from event i to event i + 1.  A single
+// event between two kernels keeps what the measurement adds to a launch near 1 us (an event pair
+// around every launch added 2-3 us).
 struct Launcher {
   ppsd_ctx *x;
   hipStream_t s;
   bool timed;
   hipError_t err = hipSuccess;
 
+  void need_event(size_t idx) {
+    while (err == hipSuccess && x->tk_events.size() <= idx) {
+      hipEvent_t e;
+      err = hipEventCreate(&e);
+      if (err == hipSuccess) x->tk_events.push_back(e);
+    }
+  }
   void before(int kind) {
     if (!timed || err != hipSuccess) return;
-    if (x->tk_used + 2 > x->tk_events.size()) {
-      for (int k = 0; k < 2; ++k) {
-        hipEvent_t e;
-        err = hipEventCreate(&e);
-        if (err != hipSuccess) return;
-        x->tk_events.push_back(e);
-      }
+    if (x->tk_used == 0) {
+      need_event(0);
+      if (err != hipSuccess) return;
+      err = hipEventRecord(x->tk_events[0], s);
+      x->tk_used = 1;
     }
-    x->tk_kinds.resize(x->tk_events.size() / 2);
-    x->tk_kinds[x->tk_used / 2] = kind;
-    err = hipEventRecord(x->tk_events[x->tk_used], s);
+    x->tk_kinds.resize(x->tk_used);
+    x->tk_kinds[x->tk_used - 1] = kind;
   }
   void after() {
     if (err == hipSuccess) err = hipGetLastError();
     if (!timed || err != hipSuccess) return;
-    err = hipEventRecord(x->tk_events[x->tk_used + 1], s);
-    x->tk_used += 2;
+    need_event(x->tk_used);
+    if (err != hipSuccess) return;
+    err = hipEventRecord(x->tk_events[x->tk_used], s);
+    x->tk_used += 1;
   }
 };
 
@@ -586,16 +595,16 @@ int capture(ppsd_ctx *x, hipGraphExec_t *out, F &&body) {
   return PPSD_OK;
 }
 
-// Drains the event pairs recorded in profiling mode into the per-kind totals.  A launch whose
+// Drains the events recorded in profiling mode into the per-kind totals.  A launch whose
 // stage was idle lasts a few microseconds and would distort the averages; those are skipped by
 // the caller passing which kinds were active (all launches in serial profiling steps are
 // counted only if the step's stage ran, see decode loop).
 int drain_kernel_events(ppsd_ctx *x, const std::vector<char> *active_mask) {
-  for (size_t k = 0; k + 1 < x->tk_used; k += 2) {
+  for (size_t k = 0; k + 1 < x->tk_used; ++k) {
     float ms = 0.f;
     HIP_TRY(hipEventElapsedTime(&ms, x->tk_events[k], x->tk_events[k + 1]));
-    if (active_mask && !(*active_mask)[k / 2]) continue;
-    const int kind = x->tk_kinds[k / 2];
+    if (active_mask && !(*active_mask)[k]) continue;
+    const int kind = x->tk_kinds[k];
     x->ktimes.total_us[kind] += 1000.0 * ms;
     x->ktimes.launches[kind] += 1;
   }
@@ -1009,6 +1018,33 @@ int ppsd_decode(ppsd_ctx *x, int32_t n_tokens, int32_t *out_tokens, int32_t *n_w
       rc = read_state(x);
       if (rc != PPSD_OK) return rc;
     } else if (timed) {
+      if (x->ktimes.event_overhead_us == 0.0) {
+        // what an event adds between two launches: 64 empty kernels with an event after each, against
+        // 64 empty kernels back to back
+        Launcher cal{x, x->sA, true};
+        const int n_cal = 64;
+        cal.need_event(n_cal);
+        if (cal.err != hipSuccess) return fail(PPSD_EHIP, "hipEventCreate: %s", hipGetErrorString(cal.err));
+        float with_ev = 0.f, without = 0.f;
+        for (int pass = 0; pass < 2; ++pass) {      // the first pass warms the kernel up
+          HIP_TRY(hipStreamSynchronize(x->sA));
+          HIP_TRY(hipEventRecord(x->tk_events[0], x->sA));
+          for (int k = 1; k <= n_cal; ++k) {
+            hipLaunchKernelGGL(k_nop, dim3(1), dim3(64), 0, x->sA, (int *)nullptr);
+            HIP_TRY(hipEventRecord(x->tk_events[k], x->sA));
+          }
+          HIP_TRY(hipStreamSynchronize(x->sA));
+          HIP_TRY(hipEventElapsedTime(&with_ev, x->tk_events[0], x->tk_events[n_cal]));
+          HIP_TRY(hipEventRecord(x->tk_events[0], x->sA));
+          for (int k = 1; k <= n_cal; ++k) hipLaunchKernelGGL(k_nop, dim3(1), dim3(64), 0, x->sA, (int *)nullptr);
+          HIP_TRY(hipEventRecord(x->tk_events[1], x->sA));
+          HIP_TRY(hipStreamSynchronize(x->sA));
+          HIP_TRY(hipEventElapsedTime(&without, x->tk_events[0], x->tk_events[1]));
+        }
+        HIP_TRY(hipGetLastError());
+        const double ev = 1000.0 * (with_ev - without) / n_cal;
+        x->ktimes.event_overhead_us = ev > 1e-3 ? ev : 1e-3;
+      }
       // one step at a time so idle launches can be told apart from active ones
       int rc = read_state(x);
       if (rc != PPSD_OK) return rc;
@@ -1017,7 +1053,7 @@ int ppsd_decode(ppsd_ctx *x, int32_t n_tokens, int32_t *out_tokens, int32_t *n_w
       x->steps_launched += 1;
       rc = read_state(x);
       if (rc != PPSD_OK) return rc;
-      std::vector<char> mask(x->tk_used / 2, 1);
+      std::vector<char> mask(x->tk_used > 0 ? x->tk_used - 1 : 0, 1);
       if (c.mode != PPSD_MODE_VANILLA && !was_full) {
         // draft-only step: the verify stage's launches (after the draft stage's 5E+1) were idle
         const size_t draft_launches = 5u * c.exit_layer + 1;

@@ -771,6 +771,9 @@ __global__ void k_begin_decode(DevState *st, int n_tokens) {
   if (threadIdx.x == 0 && blockIdx.x == 0) { st->n_out = 0; st->target = n_tokens; }
 }
 
+// Does nothing (measurement support: what a launch, and an event between two launches, cost).
+__global__ void k_nop(int *p) { if (p == (int *)1) *p = 0; }
+
 // Streaming-read probe: each thread sums 16-byte loads over a grid-stride range.
 __global__ __launch_bounds__(kBlock) void k_read_probe(const uint4 *buf, size_t n_vec, uint32_t *sink) {
   uint32_t acc = 0;
