@@ -162,6 +162,8 @@ def main():
     ap.add_argument("--modes", default="vanilla,serial,overlap,pipeline,eesd",
                     help="pipeline = the full ceil(N/E)-stage schedule; eesd = draft-then-verify rounds (the method the "
                          "paper compares against), both reported beside the two-stage path")
+    ap.add_argument("--exit-head", default=None, choices=["tied", "independent", "blend"],
+                    help="override the workload's exit-head initialisation (independent: acceptance near 0)")
     ap.add_argument("--exit-block", type=float, default=None, metavar="DAMP",
                     help="use the transformer-layer early-exit head; DAMP scales its output projections "
                          "(0 = identity block: the norm head's drafts at the block's cost)")
@@ -201,6 +203,8 @@ def main():
         w = w.replace(damp=args.damp)
     if args.exit_layer is not None:
         w = w.replace(exit_layer=args.exit_layer)
+    if args.exit_head is not None:
+        w = w.replace(exit_head=args.exit_head, exit_beta=1.0 if args.exit_head == "blend" else 0.0)
     if args.exit_block is not None:
         w = w.replace(exit_block=True, exit_block_damp=args.exit_block)
     if args.prompt_len is not None:
@@ -247,8 +251,10 @@ def main():
         prefill_ms = min(ss.prefill_ms)
         ss.close()
         total = sum(times)
+        ts = sorted(times)
         res[name] = dict(tokens_per_s=args.steps * n / total, ms_per_generation=1e3 * total / args.steps,
-                         ms_per_token=1e3 * total / (args.steps * n), stats=st, prefill_ms=prefill_ms)
+                         ms_per_token=1e3 * total / (args.steps * n), stats=st, prefill_ms=prefill_ms,
+                         ms_per_generation_min=1e3 * ts[0], ms_per_generation_median=1e3 * ts[len(ts) // 2])
         streams[name] = toks
     # vanilla and the PPSD schedules run the same kernels per token: their streams must be identical.  The
     # batched verify pass of the eesd mode adds the down-projection in column slabs (another rounding
@@ -319,6 +325,12 @@ def main():
                            + st["committed"] * ab["head"]) / st["committed"]
     elif alpha is not None:
         moved_per_token = ab["accept_step"] + (1 - alpha) * ab["reject_extra"]
+    # what a pure streaming read reaches on this chip (the library's probe kernel over 4 GiB, 10 launches)
+    probe = torch.empty(4 << 30, dtype=torch.uint8, device="cuda").fill_(0x3c)
+    probe_ms = P.hbm_read_probe(probe, iters=10)
+    stream_gbps = probe.numel() / probe_ms / 1e6
+    del probe
+    distinct = len(set(next(iter(streams.values())))) if streams else None
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_oracle_baseline(w, W, prompt, torch)
@@ -358,6 +370,10 @@ def main():
         "hbm_frac_per_committed_token": r["tokens_per_s"] * ab["vanilla"] / (HBM_PEAK_GBPS * 1e9),
         "hbm_frac_vanilla": (res["vanilla"]["tokens_per_s"] * ab["vanilla"] / (HBM_PEAK_GBPS * 1e9))
         if "vanilla" in res else None,
+        "hbm_stream_read_ceiling_gbps": stream_gbps,
+        "frac_of_stream_read_ceiling_per_moved_byte": moved_per_token and r["tokens_per_s"] * moved_per_token / (stream_gbps * 1e9),
+        "distinct_tokens_in_stream": distinct,
+        "ms_per_generation_min": r["ms_per_generation_min"], "ms_per_generation_median": r["ms_per_generation_median"],
         "hbm_frac_per_moved_byte": moved_per_token and r["tokens_per_s"] * moved_per_token / (HBM_PEAK_GBPS * 1e9),
         "prefill": {"ms": r["prefill_ms"], "tokens_per_s": w.prompt_len / r["prefill_ms"] * 1e3,
                     "path": "looped decode kernels" if args.prefill_loop else "MFMA GEMMs in chunks of 512 positions (when eligible)"},

@@ -1155,10 +1155,13 @@ int ppsd_hbm_read_probe(const void *buf, size_t bytes, void *stream, int32_t ite
   if (!s_sink) HIP_TRY(hipHostMalloc((void **)&s_sink, 64, hipHostMallocDefault));
   sink = s_sink;
   const size_t n_vec = bytes / 16;
-  const int blocks = 256 * 8;
-  hipLaunchKernelGGL(k_read_probe, dim3(blocks), dim3(kBlock), 0, s, (const uint4 *)buf, n_vec, sink);   // warm-up
+  int dev = 0, n_cu = 0;
+  HIP_TRY(hipGetDevice(&dev));
+  HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+  const int blocks = n_cu;                  // one resident workgroup per compute unit
+  hipLaunchKernelGGL(k_read_probe, dim3(blocks), dim3(kGBlock), 0, s, (const uint4 *)buf, n_vec, sink);   // warm-up
   HIP_TRY(hipEventRecord(e0, s));
-  for (int k = 0; k < iters; ++k) hipLaunchKernelGGL(k_read_probe, dim3(blocks), dim3(kBlock), 0, s, (const uint4 *)buf, n_vec, sink);
+  for (int k = 0; k < iters; ++k) hipLaunchKernelGGL(k_read_probe, dim3(blocks), dim3(kGBlock), 0, s, (const uint4 *)buf, n_vec, sink);
   HIP_TRY(hipEventRecord(e1, s));
   HIP_TRY(hipStreamSynchronize(s));
   HIP_TRY(hipGetLastError());

@@ -63,7 +63,7 @@ int main(int argc, char **argv) {
   // reference dispatches for counter scaling
   {
     const size_t gib = (size_t)1 << 30;
-    hipLaunchKernelGGL(k_read_probe, dim3(2048), dim3(kBlock), 0, 0, (const uint4 *)W, gib / 16, (uint32_t *)(ws + (50 << 20)));
+    hipLaunchKernelGGL(k_read_probe, dim3(n_cu), dim3(kGBlock), 0, 0, (const uint4 *)W, gib / 16, (uint32_t *)(ws + (50 << 20)));
     hipLaunchKernelGGL(k_copy16, dim3(4096), dim3(256), 0, 0, (const uint4 *)W, (uint4 *)(W + 2 * gib), gib / 16);
     CK(hipDeviceSynchronize());
     printf("reference dispatches: k_read_probe reads 1 GiB; k_copy16 reads 1 GiB and writes 1 GiB\n");
