@@ -9,7 +9,7 @@
 #include <cstdio>
 #include <cstdlib>
 
-#include "ppsd_kernels.h"
+#include "ppsd_batch.h"
 
 using namespace ppsd;
 
@@ -104,5 +104,45 @@ int main(int argc, char **argv) {
     hipLaunchKernelGGL((k_head<bf16_t>), dim3(c.dm.head_blocks), dim3(kGBlock), (size_t)xs_floats(2, d) * 4, 0, c, (int)kVanilla, (int)kXDraft, gain,
                        w, cand, (float *)nullptr, 1, (float *)nullptr);
   });
+
+  // the batched verify pass of draft-then-verify rounds, four tokens (same matrices, streamed once)
+  constexpr int B = 4;
+  const int lds_cap = 150 * 1024;
+  CK(hipFuncSetAttribute((const void *)k_qkv_b<bf16_t, B>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cap));
+  CK(hipFuncSetAttribute((const void *)k_gate_up_b<bf16_t, B>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cap));
+  CK(hipFuncSetAttribute((const void *)k_head_b<bf16_t, B>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cap));
+  CK(hipFuncSetAttribute((const void *)k_proj_resid_b<bf16_t, B>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cap));
+  if ((size_t)B * xs_floats(2, d) * 4 > (size_t)lds_cap) { printf("batched kernels skipped: %d x d_model floats exceed the LDS\n", B); return 0; }
+  auto bgrid = [&](int n_tasks, size_t lds, int per_cu) {
+    int fit = (int)((160 * 1024) / (lds + 1024));
+    if (fit < 1) fit = 1;
+    return gemv_grid_for(n_tasks, n_cu, fit < per_cu ? fit : per_cu);
+  };
+  float *vb = (float *)(ws + (44 << 20)), *mb = (float *)(ws + (46 << 20));
+  float2 *candb = (float2 *)(ws + (48 << 20));
+  const size_t lds_d = (size_t)B * xs_floats(2, d) * 4;
+  run("k_qkv_b<4>", (size_t)qkv_rows * d * 2, [&](const bf16_t *w) {
+    hipLaunchKernelGGL((k_qkv_b<bf16_t, B>), dim3(bgrid(qkv_rows / 2, lds_d, kGemvWgsPerCu)), dim3(kGBlock), lds_d, 0, c, 3,
+                       (int)kXBatchInSlot0, gain, w, vb);
+  });
+  run("k_gate_up_b<4>", (size_t)2 * f * d * 2, [&](const bf16_t *w) {
+    hipLaunchKernelGGL((k_gate_up_b<bf16_t, B>), dim3(bgrid(f, lds_d, kGateUpWgsPerCu)), dim3(kGBlock), lds_d, 0, c,
+                       (int)kXBatchWorkSlot0, gain, w, mb);
+  });
+  run("k_proj_resid_b<4> (down)", (size_t)d * f * 2, [&](const bf16_t *w) {
+    const int n_slabs = (int)(((size_t)B * f * 4 + 65535) / 65536);
+    const int Cs = ((f + n_slabs - 1) / n_slabs + 511) / 512 * 512;
+    for (int c0 = 0; c0 < f; c0 += Cs) {
+      const int wd = f - c0 < Cs ? f - c0 : Cs;
+      const size_t lds = (size_t)B * xs_floats(2, wd) * 4;
+      hipLaunchKernelGGL((k_proj_resid_b<bf16_t, B>), dim3(bgrid((d + 1) / 2, lds, kGemvWgsPerCu)), dim3(kGBlock), lds, 0, c,
+                         (const float *)mb, f, c0, wd, w, d, (int)kXBatchWorkSlot0, (int)kXBatchWorkSlot0);
+    }
+  });
+  run("k_head_b<4>", (size_t)V * d * 2, [&](const bf16_t *w) {
+    hipLaunchKernelGGL((k_head_b<bf16_t, B>), dim3(c.dm.head_blocks), dim3(kGBlock), lds_d, 0, c, (int)kXBatchWorkSlot0, gain, w,
+                       candb, (float *)nullptr);
+  });
+  CK(hipGetLastError());
   return 0;
 }
