@@ -144,59 +144,112 @@ __device__ __forceinline__ void attn_unit(const Common &c, const int32_t *ptab, 
     for (int k = 0; k < N; ++k) acc[g][k] = 0.f;
   }
 
-  constexpr int U = 4;   // positions in flight per group
-  for (int p0 = start + grp; p0 < end; p0 += U * GPB) {
-    uint4 ku[U], vu[U];
-    bool ok[U];
+  // A block = U positions per group (U * GPB per workgroup).  The next block's K/V rows are loaded
+  // before the current block is used, so a wave's arithmetic runs under its own loads; within a
+  // block the running maximum is raised once and the accumulators rescaled once.
+  constexpr int U = 4;
+  uint4 ku[U], vu[U], kn[U], vn[U];
+  auto load_block = [&](int p0, uint4 (&kk)[U], uint4 (&vv)[U]) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int p = p0 + u * GPB;
-      ok[u] = p < end;
-      const int pc = ok[u] ? p : p0;
+      const int pc = p < end ? p : (p0 < end ? p0 : start);     // an in-range row; its result is masked out
       const WT *kr = kv_row<WT>(c, ptab, layer, pc, kvh, 0) + j * N;
-      ku[u] = *(const uint4 *)kr;
-      vu[u] = *(const uint4 *)(kr + (size_t)m.page_tokens * HD);
+      kk[u] = *(const uint4 *)kr;
+      vv[u] = *(const uint4 *)(kr + (size_t)m.page_tokens * HD);
+    }
+  };
+  int p0 = start + grp;
+  if (start < end) load_block(p0, ku, vu);
+  // the trip count is the same for every group of the workgroup (no barrier inside, but uniform per wave)
+  for (int b0 = start; b0 < end; b0 += U * GPB, p0 += U * GPB) {
+    const bool more = b0 + U * GPB < end;
+    if (more) load_block(p0 + U * GPB, kn, vn);
+    float sc[G][U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float kf[N];
+      Pack<WT>::unpack(ku[u], kf);
+      const bool ok = p0 + u * GPB < end;
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float sdot = 0.f;
+#pragma unroll
+        for (int k = 0; k < N; ++k) sdot = fmaf(qr[g][k], kf[k], sdot);
+#pragma unroll
+        for (int o = GS / 2; o > 0; o >>= 1) sdot += __shfl_xor(sdot, o, kWave);
+        sc[g][u] = ok ? sdot : kNegBig;
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float mn = mx[g];
+#pragma unroll
+      for (int u = 0; u < U; ++u) mn = fmaxf(mn, sc[g][u]);
+      const float corr = __expf(mx[g] - mn);
+      mx[g] = mn;
+      l[g] *= corr;
+#pragma unroll
+      for (int k = 0; k < N; ++k) acc[g][k] *= corr;
+#pragma unroll
+      for (int u = 0; u < U; ++u) sc[g][u] = p0 + u * GPB < end ? __expf(sc[g][u] - mn) : 0.f;
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float kf[N], vf[N];
-      Pack<WT>::unpack(ku[u], kf);
+      float vf[N];
       Pack<WT>::unpack(vu[u], vf);
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        float s = 0.f;
+        l[g] += sc[g][u];
 #pragma unroll
-        for (int k = 0; k < N; ++k) s = fmaf(qr[g][k], kf[k], s);
-#pragma unroll
-        for (int o = GS / 2; o > 0; o >>= 1) s += __shfl_xor(s, o, kWave);
-        if (ok[u]) {
-          const float mn = fmaxf(mx[g], s);
-          const float corr = __expf(mx[g] - mn);
-          const float pe = __expf(s - mn);
-          l[g] = l[g] * corr + pe;
-#pragma unroll
-          for (int k = 0; k < N; ++k) acc[g][k] = fmaf(pe, vf[k], acc[g][k] * corr);
-          mx[g] = mn;
-        }
+        for (int k = 0; k < N; ++k) acc[g][k] = fmaf(sc[g][u], vf[k], acc[g][k]);
       }
+    }
+    if (more) {
+#pragma unroll
+      for (int u = 0; u < U; ++u) { ku[u] = kn[u]; vu[u] = vn[u]; }
     }
   }
 
-  // merge the position groups of this workgroup
+  // merge the groups of a wave through shuffles (same lane j of every group holds the same dims),
+  // then the waves of the workgroup through LDS, both in fixed order
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float *rec = merge + (grp * G + g) * REC;
-    if (j == 0) { rec[0] = mx[g]; rec[1] = l[g]; }
+  for (int o = GS; o < kWave; o <<= 1) {
 #pragma unroll
-    for (int k = 0; k < N; ++k) rec[2 + j * N + k] = acc[g][k];
+    for (int g = 0; g < G; ++g) {
+      const float m2 = __shfl_xor(mx[g], o, kWave);
+      const float l2 = __shfl_xor(l[g], o, kWave);
+      const float M = fmaxf(mx[g], m2);
+      const float w1 = __expf(mx[g] - M), w2 = __expf(m2 - M);
+      l[g] = l[g] * w1 + l2 * w2;
+#pragma unroll
+      for (int k = 0; k < N; ++k) {
+        const float a2 = __shfl_xor(acc[g][k], o, kWave);
+        acc[g][k] = acc[g][k] * w1 + a2 * w2;
+      }
+      mx[g] = M;
+    }
+  }
+  constexpr int NW = BLOCK / kWave;
+  const int wave = tid >> 6;
+  if ((tid & 63) < GS) {                    // the wave's first group writes the wave's record
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float *rec = merge + (wave * G + g) * REC;
+      if (j == 0) { rec[0] = mx[g]; rec[1] = l[g]; }
+#pragma unroll
+      for (int k = 0; k < N; ++k) rec[2 + j * N + k] = acc[g][k];
+    }
   }
   __syncthreads();
   for (int o = tid; o < G * HD; o += BLOCK) {
     const int g = o / HD, dim = o % HD;
     float M = kNegBig;
-    for (int r = 0; r < GPB; ++r) M = fmaxf(M, merge[(r * G + g) * REC]);
+#pragma unroll
+    for (int r = 0; r < NW; ++r) M = fmaxf(M, merge[(r * G + g) * REC]);
     float L = 0.f, A = 0.f;
-    for (int r = 0; r < GPB; ++r) {
+#pragma unroll
+    for (int r = 0; r < NW; ++r) {
       const float *rec = merge + (r * G + g) * REC;
       const float w = __expf(rec[0] - M);
       L = fmaf(rec[1], w, L);
