@@ -146,3 +146,97 @@ def vanilla_sample_decode(dec: Decoder, prompt: Sequence[int], n_new: int, tempe
             tok = sample(softmax_t(dec.head_logits(x, "lm"), temperature), uniform(seed, pos + 1, VANILLA))
             out.append(tok); seq.append(tok)
     return out
+
+
+# ----------------------------------------------------------------------------
+# Stochastic verification in the full ceil(N/E)-stage schedule (Sec. 4.1-4.2, Alg. 1 with sampling)
+# ----------------------------------------------------------------------------
+# Stage 0 samples one draft per tick from the early-exit head's distribution and keeps that
+# distribution until the draft's check token arrives S-1 ticks later; the last stage's
+# distribution q decides by Eq. (2); a rejected draft is replaced by a token from
+# normalise(max(0, q - p)) and everything in flight is flushed.  Because the uniforms are keyed by
+# position and purpose, and every draft that reaches verification was made from accepted tokens
+# only, the committed stream is the one the two-stage schedule commits with the same seed.
+from .ppsd_schedule import PipelineSession, PipelineStats, pipeline_prefill, stage_ranges   # noqa: E402
+
+
+@dataclass
+class StochasticPipelineSession:
+    base: PipelineSession
+    temperature: float
+    seed: int
+    p_at: dict = field(default_factory=dict)        # position -> distribution its draft was sampled from
+
+
+def stochastic_pipeline_prefill(dec: Decoder, prompt: Sequence[int], max_seq: int, temperature: float,
+                                seed: int) -> StochasticPipelineSession:
+    base = pipeline_prefill(dec, prompt, max_seq)
+    two = prefill(dec, prompt, max_seq)
+    q = softmax_t(dec.head_logits(two.x_prompt, "lm"), temperature)
+    tok0 = sample(q, uniform(seed, len(prompt), VANILLA))
+    base.last_token = tok0
+    base.tok0 = tok0
+    return StochasticPipelineSession(base=base, temperature=temperature, seed=seed)
+
+
+def stochastic_pipeline_tick(sp: StochasticPipelineSession, out: List[int]) -> None:
+    ss, T, seed = sp.base, sp.temperature, sp.seed
+    dec, kv = ss.dec, ss.kv
+    S = len(ss.stages)
+    st = ss.stats
+    st.ticks += 1
+    produced = [None] * S
+    draft_next = None
+    for k in range(S):
+        if not ss.valid[k]:
+            continue
+        st.stage_runs += 1
+        x_in = dec.embed([ss.tok0])[0] if k == 0 else ss.hidden[k]
+        if k == 0:
+            ss.token_at[ss.pos[0]] = ss.tok0
+        for l in list(ss.stages[k]) + ([dec.s.n_layers] if k == 0 and dec.has_exit_block else []):
+            if kv.len[l] > ss.pos[k]:
+                kv.len[l] = ss.pos[k]
+        produced[k] = run_layers(dec, kv, x_in, ss.pos[k], ss.stages[k])
+        if k == 0:
+            p_new = softmax_t(exit_logits(dec, kv, produced[0], ss.pos[0]), T)
+            sp.p_at[ss.pos[0] + 1] = p_new
+            draft_next = sample(p_new, uniform(seed, ss.pos[0] + 1, DRAFT))
+    flush = False
+    if ss.valid[S - 1]:
+        q = softmax_t(dec.head_logits(produced[S - 1], "lm"), T)
+        p = ss.pos[S - 1] + 1
+        d = ss.token_at[p]
+        tok, ok = spec_verify(sp.p_at[p], q, d, uniform(seed, p, ACCEPT), uniform(seed, p, RESAMPLE))
+        st.committed += 1; st.drafts_compared += 1
+        out.append(tok)
+        ss.compared.append(d)
+        ss.t, ss.last_token = p, tok
+        if ok:
+            st.accepted += 1
+        else:
+            st.rejected += 1
+            flush = True
+    if flush:
+        st.flushed_tokens += sum(1 for x in ss.token_at if x >= ss.t)
+        ss.token_at = {}
+        sp.p_at = {}
+        ss.valid = [True] + [False] * (S - 1)
+        ss.pos = [ss.t] + [0] * (S - 1)
+        ss.tok0 = ss.last_token
+        return
+    for k in range(S - 1, 0, -1):
+        ss.valid[k] = ss.valid[k - 1]
+        ss.pos[k] = ss.pos[k - 1]
+        ss.hidden[k] = produced[k - 1]
+    ss.pos[0] += 1
+    ss.tok0 = draft_next
+    ss.token_at = {x: tk for x, tk in ss.token_at.items() if x > ss.t}
+    sp.p_at = {x: pv for x, pv in sp.p_at.items() if x > ss.t}
+
+
+def stochastic_pipeline_decode(sp: StochasticPipelineSession, n_tokens: int) -> List[int]:
+    out: List[int] = []
+    while len(out) < n_tokens:
+        stochastic_pipeline_tick(sp, out)
+    return out

@@ -126,3 +126,23 @@ def test_stochastic_schedule_bookkeeping_and_rollback(tiny_shape):
     assert ST.stochastic_decode(s2, 40) == toks
     s3 = ST.stochastic_prefill(dec, prompt, 80, 1.0, seed=6)
     assert ST.stochastic_decode(s3, 40) != toks
+
+
+def test_pipeline_schedule_commits_the_two_stage_stream_under_sampling(tiny_shape):
+    """Uniforms are keyed by position and purpose and every verified draft was made from accepted tokens,
+    so the number of stages cannot change the committed stream, the compared drafts or the outcomes."""
+    for E, n_layers in ((1, 3), (2, 5), (1, 4)):
+        w = tiny_shape.replace(exit_layer=E, n_layers=n_layers, decode_len=30, exit_head="blend", exit_beta=1.0)
+        W = S.make_weights(w)
+        W["lm_head"], W["exit_head"] = W["lm_head"] * 30.0, W["exit_head"] * 30.0
+        dec = O.Decoder(w, W)
+        prompt = S.make_prompt(w)
+        a = ST.stochastic_prefill(dec, prompt, 80, 0.9, seed=21)
+        ta = [a.last_token] + ST.stochastic_decode(a, 30)
+        b = ST.stochastic_pipeline_prefill(dec, prompt, 80, 0.9, seed=21)
+        tb = [b.base.last_token] + ST.stochastic_pipeline_decode(b, 30)
+        assert ta == tb and a.compared == b.base.compared
+        assert (a.stats.accepted, a.stats.rejected) == (b.base.stats.accepted, b.base.stats.rejected)
+        assert 0 < a.stats.accepted < 30
+        n_stages = -(-n_layers // E)
+        assert b.base.stats.flushed_tokens == (n_stages - 1) * b.base.stats.rejected
