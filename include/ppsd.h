@@ -121,7 +121,7 @@ typedef struct {
                               own KV rows (rolled back with those of layers 1..E), and its output feeds the exit
                               head only.  Per-operation engine only, no time_kernels */
   float   temperature;     /* 0: greedy heads (argmax), the default.  > 0 (>= 1e-4): stochastic verification
-                              (Sec. 3.1, Eq. 1-2) in PPSD_MODE_SERIAL / PPSD_MODE_OVERLAP -- the draft is sampled
+                              (Sec. 3.1, Eq. 1-2) in PPSD_MODE_SERIAL / OVERLAP / PIPELINE -- the draft is sampled
                               from softmax(exit logits / temperature) = p, accepted with probability
                               min(1, q(d) / p(d)) against q = softmax(LM logits / temperature), and a rejected
                               draft is replaced by a token from normalise(max(0, q - p)), so every committed token

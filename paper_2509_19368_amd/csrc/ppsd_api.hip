@@ -108,8 +108,8 @@ bool valid_config(const ppsd_config *c, const char **why) {
   REJECT(c->tune_attn_split < 0 || (c->tune_attn_split > 0 && c->tune_attn_split < 64), "tune_attn_split must be 0 or >= 64");
   REJECT(!(c->temperature >= 0.0f) || c->temperature > 1.0e4f, "temperature must be in [0, 1e4] (0 = greedy)");
   REJECT(c->temperature > 0.0f && c->temperature < 1.0e-4f, "a positive temperature must be at least 1e-4");
-  REJECT(c->temperature > 0.0f && (c->mode == PPSD_MODE_PIPELINE || c->mode == PPSD_MODE_EESD),
-         "sampling (temperature > 0) is available in the vanilla and the two-stage modes");
+  REJECT(c->temperature > 0.0f && c->mode == PPSD_MODE_EESD,
+         "sampling (temperature > 0) is available in the vanilla, two-stage and pipeline modes");
   REJECT(c->temperature > 0.0f && (c->engine != PPSD_ENGINE_STREAMS || c->time_kernels),
          "sampling (temperature > 0) runs on the per-operation engine, without time_kernels");
   REJECT(c->exit_block != 0 && c->exit_block != 1, "exit_block must be 0 or 1");
@@ -176,7 +176,7 @@ Layout make_layout(const ppsd_config *c) {
   const size_t nv = c->temperature > 0.0f ? (size_t)c->vocab : 0;
   L.logits_lm = take(4ull * nv);
   L.logits_exit = take(4ull * nv);
-  L.probs = take(4ull * 2 * nv);
+  L.probs = take(4ull * (c->mode == PPSD_MODE_PIPELINE ? kMaxStages : 2) * nv);
   L.sink = take(256);
   L.logits = take(4ull * c->debug_logits * c->vocab);
   L.kv = take((size_t)(c->n_layers + c->exit_block) * L.n_pages * c->n_kv_heads * 2 * c->kv_page_tokens * c->head_dim * es);
@@ -330,7 +330,7 @@ void launch_head(Launcher &L, int role, int xin_sel, bool is_lm) {
 
 void launch_commit(Launcher &L, int kind) {
   ppsd_ctx *x = L.x;
-  if (x->cfg.temperature > 0.0f && kind != 2) {   // sampling: kinds 0 (vanilla), 1 (two-stage step), 3 (token #0)
+  if (x->cfg.temperature > 0.0f && kind != 2) {   // sampling: kinds 0 (vanilla), 1 (two-stage step), 3 (token #0), 4 (tick)
     L.before(kKCommit);
     hipLaunchKernelGGL(k_commit_sample, dim3(1), dim3(kSBlock), 0, L.s, x->cm, kind, at<const float>(x, x->lay.logits_lm),
                        at<const float>(x, x->lay.logits_exit), at<float>(x, x->lay.probs), 1.0f / x->cfg.temperature,

@@ -709,9 +709,10 @@ __device__ __forceinline__ int sample_index(WF &&wf, int V, float u, float *scan
 }
 
 // One step's decision with sampling.  kind: 0 vanilla (token ~ q), 1 two-stage PPSD step,
-// 3 last prefill position (token #0 ~ q).  logits_lm / logits_exit: V floats each, written by the
-// heads of this step.  probs: [2][V], the distribution each in-flight draft was sampled from
-// (buffer st->cur & 1 belongs to the draft being verified, the other receives the new draft's).
+// 3 last prefill position (token #0 ~ q), 4 one tick of the full pipeline schedule.  logits_lm /
+// logits_exit: V floats each, written by the heads of this step.  probs: the distribution each
+// in-flight draft was sampled from -- kind 1: [2][V], buffer st->cur & 1 belongs to the draft being
+// verified, the other receives the new draft's; kind 4: [kMaxStages][V], indexed by position.
 __global__ __launch_bounds__(kSBlock) void k_commit_sample(Common c, int kind, const float *logits_lm,
                                                            const float *logits_exit, float *probs, float inv_temp,
                                                            uint32_t seed, int32_t *out_tokens, int32_t *drafts_log) {
@@ -741,6 +742,8 @@ __global__ __launch_bounds__(kSBlock) void k_commit_sample(Common c, int kind, c
         st->prefill_pos += 1;
         st->t = st->prefill_len; st->last_token = tok; st->full = 0; st->gen_count = 1;
         drafts_log[0] = -1;
+        for (int k = 0; k < kMaxStages; ++k) { st->pl_valid[k] = 0; st->pl_pos[k] = 0; }
+        st->pl_valid[0] = 1; st->pl_pos[0] = st->prefill_len; st->pl_tok0 = tok; st->pl_par = 0;
       } else {
         out_tokens[st->n_out] = tok;
         drafts_log[st->gen_count] = -1;
@@ -751,24 +754,41 @@ __global__ __launch_bounds__(kSBlock) void k_commit_sample(Common c, int kind, c
     return;
   }
 
-  // ---- two-stage PPSD step
-  const int full = st->full;
-  const int cur = st->cur & 1;
-  float *p_next = probs + (size_t)(cur ^ 1) * V;
-  const float *p_cur = probs + (size_t)cur * V;
-  // the draft stage always ran: its distribution, kept for the verification one step later, and its draft
+  // ---- a PPSD step: two-stage (kind 1) or one tick of the full pipeline schedule (kind 4).
+  // ran_verify: the last stage produced the full model's distribution for position pos, whose draft d
+  // was sampled from p_cur; the first stage always ran and produced the distribution for position pos_d.
+  const int S = c.dm.n_stages;
+  int ran_verify, pos, pos_d, d;
+  const float *p_cur;
+  float *p_next;
+  if (kind == 1) {
+    const int cur = st->cur & 1;
+    ran_verify = st->full;
+    pos = st->t + 1;
+    pos_d = (ran_verify ? st->t + 1 : st->t) + 1;
+    d = st->draft;
+    p_cur = probs + (size_t)cur * V;
+    p_next = probs + (size_t)(cur ^ 1) * V;
+  } else {
+    const int pos0 = st->pl_pos[0];
+    if (threadIdx.x == 0) st->pl_tok_at[pos0 & (kTokRing - 1)] = st->pl_tok0;   // the token stage 0 used this tick
+    __syncthreads();
+    ran_verify = st->pl_valid[S - 1];
+    pos = st->pl_pos[S - 1] + 1;
+    pos_d = pos0 + 1;
+    d = st->pl_tok_at[pos & (kTokRing - 1)];
+    p_cur = probs + (size_t)(pos & (kMaxStages - 1)) * V;        // kept since the tick that drafted position pos
+    p_next = probs + (size_t)(pos_d & (kMaxStages - 1)) * V;
+  }
   float mp;
   softmax_weights(logits_exit, mp);
   float sp;
-  const int pos_d = (full ? st->t + 1 : st->t) + 1;                  // the position the new draft is for
   const int d_next = sample_index([&](int i) { return __expf((logits_exit[i] - mp) * inv_temp); }, V,
                                   uniform24(seed, pos_d, kPurDraft), scan, &s_pick, &sp);
   for (int i = threadIdx.x; i < V; i += kSBlock) p_next[i] = __expf((logits_exit[i] - mp) * inv_temp) / sp;
 
   int tok = -1, ok = 0;
-  const int d = st->draft;
-  if (full) {
-    const int pos = st->t + 1;                                         // the position being decided
+  if (ran_verify) {
     float mq;
     softmax_weights(logits_lm, mq);
     // total of the target's weights, summed the way sample_index sums
@@ -789,8 +809,9 @@ __global__ __launch_bounds__(kSBlock) void k_commit_sample(Common c, int kind, c
     }
   }
   __syncthreads();
-  if (threadIdx.x == 0) {
-    if (!full) {
+  if (threadIdx.x != 0) return;
+  if (kind == 1) {
+    if (!ran_verify) {
       st->draft = d_next; st->full = 1; st->cur ^= 1; st->stats[5] += 1;
     } else {
       out_tokens[st->n_out] = tok;
@@ -805,6 +826,39 @@ __global__ __launch_bounds__(kSBlock) void k_commit_sample(Common c, int kind, c
       st->t += 1;
       st->last_token = tok;
     }
+    return;
+  }
+  // kind 4: the tick's bookkeeping, as in the greedy commit
+  int n_ran = 0;
+  for (int k = 0; k < S; ++k) n_ran += st->pl_valid[k] ? 1 : 0;
+  st->stats[8] += 1;
+  st->stats[9] += n_ran;
+  if (n_ran > 1) st->stats[4] += 1; else st->stats[5] += 1;
+  const int pos0 = st->pl_pos[0];
+  bool flush = false;
+  if (ran_verify) {
+    out_tokens[st->n_out] = tok;
+    drafts_log[st->gen_count] = d;
+    st->n_out += 1; st->gen_count += 1;
+    st->stats[0] += 1; st->stats[1] += 1;
+    st->t = pos; st->last_token = tok;
+    if (ok) {
+      st->stats[2] += 1;
+    } else {
+      st->stats[3] += 1; st->stats[6] += 1;
+      st->stats[10] += pos0 - pos + 1;
+      flush = true;
+    }
+  }
+  if (flush) {
+    for (int k = 1; k < S; ++k) st->pl_valid[k] = 0;
+    st->pl_pos[0] = st->t;
+    st->pl_tok0 = tok;
+  } else {
+    for (int k = S - 1; k > 0; --k) { st->pl_valid[k] = st->pl_valid[k - 1]; st->pl_pos[k] = st->pl_pos[k - 1]; }
+    st->pl_pos[0] = pos0 + 1;
+    st->pl_tok0 = d_next;
+    st->pl_par ^= 1;
   }
 }
 

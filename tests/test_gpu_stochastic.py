@@ -102,6 +102,19 @@ def test_sampled_streams_equal_the_simulator(P, w, T):
     assert (st["accepted"], st["rejected"], st["steps_draft_only"], st["kv_rollbacks"]) == \
            (ss.stats.accepted, ss.stats.rejected, ss.stats.steps_draft_only, ss.stats.kv_rollbacks)
     assert 0 < st["accepted"] < n
+    # the full pipeline schedule draws the same numbers at the same positions: same stream, drafts, outcomes
+    S_ = -(-w.n_layers // w.exit_layer)
+    sp = ST.stochastic_pipeline_prefill(dec, prompt, len(prompt) + n + S_ + 2, T, seed)
+    pwant = [sp.base.last_token] + ST.stochastic_pipeline_decode(sp, n)
+    assert pwant == want
+    pr = P.Session(w, Wg, max_seq=len(prompt) + 1 + n + S_, mode=P.MODE_PIPELINE, temperature=T, sample_seed=seed)
+    ptoks = [pr.ppsd_prefill(prompt)] + pr.ppsd_decode(n)
+    pst, pdr = pr.ppsd_stats(), pr.read_drafts(0, n + 1)
+    pr.close()
+    assert ptoks == want and pdr == [-1] + sp.base.compared
+    assert (pst["accepted"], pst["rejected"], pst["pipeline_ticks"], pst["stage_runs"], pst["flushed_tokens"]) == \
+           (sp.base.stats.accepted, sp.base.stats.rejected, sp.base.stats.ticks, sp.base.stats.stage_runs,
+            sp.base.stats.flushed_tokens)
     v = _run(P, w, Wg, prompt, n, P.MODE_VANILLA, T, seed)
     assert v["tokens"] == ST.vanilla_sample_decode(dec, prompt, n + 1, T, seed)
     assert _run(P, w, Wg, prompt, n, P.MODE_OVERLAP, T, seed + 1)["tokens"] != r["tokens"]
