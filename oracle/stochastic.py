@@ -240,3 +240,72 @@ def stochastic_pipeline_decode(sp: StochasticPipelineSession, n_tokens: int) -> 
     while len(out) < n_tokens:
         stochastic_pipeline_tick(sp, out)
     return out
+
+
+# ----------------------------------------------------------------------------
+# Stochastic verification in draft-then-verify rounds: Eq. (1)-(2) as stated, gamma drafts per round
+# ----------------------------------------------------------------------------
+# Each of the gamma drafts is sampled from the early-exit head's distribution given the drafts
+# before it (Eq. 1); the full model's distributions for the same positions come from one batched
+# pass; the drafts are checked in order by Eq. (2), the first rejected one is replaced by a token
+# from normalise(max(0, q - p)) and the rest discarded; if all are accepted one more token is
+# sampled from the full model's distribution for the next position (Sec. 3.1).
+from .eesd_schedule import EESDSession, eesd_prefill   # noqa: E402
+
+
+def stochastic_eesd_prefill(dec: Decoder, prompt: Sequence[int], max_seq: int, gamma: int, temperature: float,
+                            seed: int) -> EESDSession:
+    ss = eesd_prefill(dec, prompt, max_seq, gamma)
+    two = prefill(dec, prompt, max_seq)
+    q = softmax_t(dec.head_logits(two.x_prompt, "lm"), temperature)
+    ss.last_token = sample(q, uniform(seed, len(prompt), VANILLA))
+    return ss
+
+
+def stochastic_eesd_round(ss: EESDSession, out: List[int], limit: int, temperature: float, seed: int) -> None:
+    dec, kv, s, g, T = ss.dec, ss.kv, ss.dec.s, ss.gamma, temperature
+    draft_layers, verify_layers = range(0, s.exit_layer), range(s.exit_layer, s.n_layers)
+    t = ss.t
+    x: List[int] = [ss.last_token]
+    h: List[torch.Tensor] = []
+    p: List[torch.Tensor] = []
+    for j in range(g):
+        h.append(run_layers(dec, kv, dec.embed([x[j]])[0], t + j, draft_layers))
+        p.append(softmax_t(exit_logits(dec, kv, h[j], t + j), T))
+        x.append(sample(p[j], uniform(seed, t + j + 1, DRAFT)))
+    h.append(run_layers(dec, kv, dec.embed([x[g]])[0], t + g, draft_layers))
+    if dec.has_exit_block:
+        exit_logits(dec, kv, h[g], t + g)
+    q = [softmax_t(dec.head_logits(run_layers(dec, kv, h[j], t + j, verify_layers), "lm"), T) for j in range(g + 1)]
+    toks: List[int] = []
+    n = 0
+    while n < g:
+        pos = t + n + 1
+        tok, ok = spec_verify(p[n], q[n], x[n + 1], uniform(seed, pos, ACCEPT), uniform(seed, pos, RESAMPLE))
+        toks.append(tok)
+        if not ok:
+            break
+        n += 1
+    if n == g:                                  # every draft accepted: the full model's own token follows
+        toks.append(sample(q[g], uniform(seed, t + g + 1, VANILLA)))
+    st = ss.stats
+    st.rounds += 1
+    st.layer_reads += (g + 1) * len(draft_layers) + len(verify_layers)
+    st.drafts_compared += min(g, n + 1)
+    st.accepted += n
+    st.rejected += 1 if n < g else 0
+    k = min(n + 1, limit)
+    for i in range(k):
+        out.append(toks[i])
+        ss.compared.append(x[i + 1] if i < g else -1)
+    st.committed += k
+    ss.t = t + k
+    ss.last_token = toks[k - 1]
+    kv.truncate(range(len(kv.len)), ss.t)
+
+
+def stochastic_eesd_decode(ss: EESDSession, n_tokens: int, temperature: float, seed: int) -> List[int]:
+    out: List[int] = []
+    while len(out) < n_tokens:
+        stochastic_eesd_round(ss, out, n_tokens - len(out), temperature, seed)
+    return out

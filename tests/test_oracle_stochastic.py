@@ -146,3 +146,38 @@ def test_pipeline_schedule_commits_the_two_stage_stream_under_sampling(tiny_shap
         assert 0 < a.stats.accepted < 30
         n_stages = -(-n_layers // E)
         assert b.base.stats.flushed_tokens == (n_stages - 1) * b.base.stats.rejected
+
+
+def test_sampled_rounds_reduce_to_the_greedy_rounds_at_low_temperature(tiny_shape):
+    from oracle import eesd_schedule as EE
+    w = tiny_shape.replace(decode_len=20)
+    W = S.make_weights(w)
+    dec = O.Decoder(w, W)
+    prompt = S.make_prompt(w)
+    for gamma in (1, 3):
+        g = EE.eesd_prefill(dec, prompt, 64, gamma)
+        gt = [g.last_token] + EE.eesd_decode(g, 20)
+        s = ST.stochastic_eesd_prefill(dec, prompt, 64, gamma, 1e-4, seed=4)
+        st = [s.last_token] + ST.stochastic_eesd_decode(s, 20, 1e-4, seed=4)
+        assert st == gt and s.stats == g.stats and s.compared == g.compared
+
+
+def test_sampled_rounds_follow_the_position_keyed_decisions(tiny_shape):
+    """Up to the first round in which every draft is accepted (whose extra token is a plain sample), the
+    stream is the one the two-stage schedule commits with the same seed: same distributions, same uniforms."""
+    w = tiny_shape.replace(decode_len=30, exit_head="blend", exit_beta=1.0)
+    W = S.make_weights(w)
+    W["lm_head"], W["exit_head"] = W["lm_head"] * 30.0, W["exit_head"] * 30.0
+    dec = O.Decoder(w, W)
+    prompt = S.make_prompt(w)
+    a = ST.stochastic_prefill(dec, prompt, 80, 0.9, seed=21)
+    ta = [a.last_token] + ST.stochastic_decode(a, 30)
+    for gamma in (2, 4):
+        e = ST.stochastic_eesd_prefill(dec, prompt, 80, gamma, 0.9, seed=21)
+        te = [e.last_token] + ST.stochastic_eesd_decode(e, 30, 0.9, seed=21)
+        first_bonus = next((i for i, c in enumerate(e.compared) if c == -1), len(e.compared))
+        assert te[: first_bonus + 1] == ta[: first_bonus + 1]
+        assert e.compared[:first_bonus] == a.compared[:first_bonus]
+        st = e.stats
+        assert st.committed == 30 and st.rejected > 0 and st.accepted > 0
+        assert e.kv.len == [e.t] * w.n_layers
