@@ -168,7 +168,7 @@ def main():
                     help="use the transformer-layer early-exit head; DAMP scales its output projections "
                          "(0 = identity block: the norm head's drafts at the block's cost)")
     ap.add_argument("--temperature", type=float, default=0.0,
-                    help="> 0: stochastic verification (sampled drafts, Eq. 2); the eesd mode stays greedy and is skipped")
+                    help="> 0: stochastic verification (sampled drafts, Eq. 2) in every mode")
     ap.add_argument("--sample-seed", type=int, default=2509)
     ap.add_argument("--gamma", type=int, default=0, help="drafts per round of the eesd mode (0 = library default, 3)")
     ap.add_argument("--engine", default="streams", choices=["streams", "persistent"])
@@ -239,8 +239,6 @@ def main():
         if mode == P.MODE_PIPELINE and (engine != P.ENGINE_STREAMS or n_stages > 16):
             continue
         if mode == P.MODE_EESD and (engine != P.ENGINE_STREAMS or 4 * 4 * w.d_model > 150 * 1024):
-            continue
-        if args.temperature > 0 and mode == P.MODE_EESD:
             continue
         ss = P.Session(w, W, max_seq=max_seq, mode=mode, engine=engine, prefill_loop=args.prefill_loop,
                        pipeline_streams=args.pipeline_streams if mode == P.MODE_PIPELINE else 0,

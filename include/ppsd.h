@@ -121,11 +121,12 @@ typedef struct {
                               own KV rows (rolled back with those of layers 1..E), and its output feeds the exit
                               head only.  Per-operation engine only, no time_kernels */
   float   temperature;     /* 0: greedy heads (argmax), the default.  > 0 (>= 1e-4): stochastic verification
-                              (Sec. 3.1, Eq. 1-2) in PPSD_MODE_SERIAL / OVERLAP / PIPELINE -- the draft is sampled
+                              (Sec. 3.1, Eq. 1-2) in PPSD_MODE_SERIAL / OVERLAP / PIPELINE / EESD -- the draft is sampled
                               from softmax(exit logits / temperature) = p, accepted with probability
                               min(1, q(d) / p(d)) against q = softmax(LM logits / temperature), and a rejected
                               draft is replaced by a token from normalise(max(0, q - p)), so every committed token
-                              is q-distributed -- and plain sampling from q in PPSD_MODE_VANILLA and for token #0.
+                              is q-distributed -- and plain sampling from q in PPSD_MODE_VANILLA, for token #0 and
+                              for the token behind a fully accepted draft-then-verify round.
                               Sampling is by inverse CDF in index order.  Per-operation engine only */
   uint32_t sample_seed;    /* the uniform for (position, purpose) is the top 24 bits of splitmix64's output
                               function applied to seed ^ position * 0xD1342543DE82EF95 ^ purpose *

@@ -59,6 +59,7 @@ struct Layout {
   size_t pf_x, pf_q, pf_ao, pf_m, pf_rs;   // MFMA prefill chunk buffers (0 bytes when not used)
   size_t qb, ab, mb, partials_b, counters_b, cand_b;   // batched verify pass (0 bytes unless PPSD_MODE_EESD)
   size_t logits_lm, logits_exit, probs;                // sampling (0 bytes unless temperature > 0)
+  size_t logits_b, probs_e;                            // sampling in draft-then-verify rounds
   bool pf;
   size_t total;
   int n_pages, n_splits, head_blocks;
@@ -108,8 +109,6 @@ bool valid_config(const ppsd_config *c, const char **why) {
   REJECT(c->tune_attn_split < 0 || (c->tune_attn_split > 0 && c->tune_attn_split < 64), "tune_attn_split must be 0 or >= 64");
   REJECT(!(c->temperature >= 0.0f) || c->temperature > 1.0e4f, "temperature must be in [0, 1e4] (0 = greedy)");
   REJECT(c->temperature > 0.0f && c->temperature < 1.0e-4f, "a positive temperature must be at least 1e-4");
-  REJECT(c->temperature > 0.0f && c->mode == PPSD_MODE_EESD,
-         "sampling (temperature > 0) is available in the vanilla, two-stage and pipeline modes");
   REJECT(c->temperature > 0.0f && (c->engine != PPSD_ENGINE_STREAMS || c->time_kernels),
          "sampling (temperature > 0) runs on the per-operation engine, without time_kernels");
   REJECT(c->exit_block != 0 && c->exit_block != 1, "exit_block must be 0 or 1");
@@ -177,6 +176,9 @@ Layout make_layout(const ppsd_config *c) {
   L.logits_lm = take(4ull * nv);
   L.logits_exit = take(4ull * nv);
   L.probs = take(4ull * (c->mode == PPSD_MODE_PIPELINE ? kMaxStages : 2) * nv);
+  const size_t nve = c->mode == PPSD_MODE_EESD ? nv : 0;
+  L.logits_b = take(4ull * kMaxBatch * nve);
+  L.probs_e = take(4ull * kMaxGamma * nve);
   L.sink = take(256);
   L.logits = take(4ull * c->debug_logits * c->vocab);
   L.kv = take((size_t)(c->n_layers + c->exit_block) * L.n_pages * c->n_kv_heads * 2 * c->kv_page_tokens * c->head_dim * es);
@@ -439,9 +441,10 @@ void launch_verify_batch(Launcher &L) {
     launch_proj_b<WT, B>(L, kKDown, mb, f, (const WT *)x->wdown[l], kXBatchWorkSlot0, kXBatchWorkSlot0);
   }
   float *logits = c.debug_logits > 0 ? at<float>(x, x->lay.logits) : nullptr;
+  float *full = c.temperature > 0.0f ? at<float>(x, x->lay.logits_b) : nullptr;
   L.before(kKHead);
   hipLaunchKernelGGL((k_head_b<WT, B>), dim3(cm.dm.head_blocks), dim3(kGBlock), lds_d, L.s, cm, kXBatchWorkSlot0,
-                     (const float *)x->final_norm, (const WT *)x->lm_head, at<float2>(x, x->lay.cand_b), logits);
+                     (const float *)x->final_norm, (const WT *)x->lm_head, at<float2>(x, x->lay.cand_b), logits, full);
   L.after();
 }
 
@@ -469,7 +472,11 @@ hipError_t enqueue_eesd_round(ppsd_ctx *x) {
     if (j < g) {
       launch_head<WT>(A, kEesdDraft0 + j, c.exit_block ? kXStageWork0 : kXBatchIn0 + j, false);
       A.before(kKCommit);
-      hipLaunchKernelGGL(k_eesd_pick, dim3(1), dim3(kBlock), 0, A.s, x->cm, at<const float2>(x, x->lay.cand_exit), j);
+      if (c.temperature > 0.0f)
+        hipLaunchKernelGGL(k_eesd_pick_sample, dim3(1), dim3(kSBlock), 0, A.s, x->cm, at<const float>(x, x->lay.logits_exit),
+                           at<float>(x, x->lay.probs_e), j, 1.0f / c.temperature, (uint32_t)c.sample_seed);
+      else
+        hipLaunchKernelGGL(k_eesd_pick, dim3(1), dim3(kBlock), 0, A.s, x->cm, at<const float2>(x, x->lay.cand_exit), j);
       A.after();
     }
   }
@@ -480,8 +487,13 @@ hipError_t enqueue_eesd_round(ppsd_ctx *x) {
     default: launch_verify_batch<WT, 5>(A); break;
   }
   A.before(kKCommit);
-  hipLaunchKernelGGL(k_eesd_commit, dim3(1), dim3(kBlock), 0, A.s, x->cm, at<const float2>(x, x->lay.cand_b),
-                     at<int32_t>(x, x->lay.out_tokens), at<int32_t>(x, x->lay.drafts), g);
+  if (c.temperature > 0.0f)
+    hipLaunchKernelGGL(k_eesd_commit_sample, dim3(1), dim3(kSBlock), 0, A.s, x->cm, at<const float>(x, x->lay.logits_b),
+                       at<const float>(x, x->lay.probs_e), at<int32_t>(x, x->lay.out_tokens), at<int32_t>(x, x->lay.drafts), g,
+                       1.0f / c.temperature, (uint32_t)c.sample_seed);
+  else
+    hipLaunchKernelGGL(k_eesd_commit, dim3(1), dim3(kBlock), 0, A.s, x->cm, at<const float2>(x, x->lay.cand_b),
+                       at<int32_t>(x, x->lay.out_tokens), at<int32_t>(x, x->lay.drafts), g);
   A.after();
   return A.err;
 }

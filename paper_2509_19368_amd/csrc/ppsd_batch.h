@@ -276,10 +276,11 @@ __global__ __launch_bounds__(kGBlock) void k_gate_up_b(Common c, int x_slot0, co
 }
 
 // LM head of B tokens: one (value, index) candidate per workgroup and token in
-// cand[b * kMaxWorkgroups + blockIdx.x].  Logit rows (parity harness): row = tokens committed so far + b.
+// cand[b * kMaxWorkgroups + blockIdx.x].  Logit rows (parity harness): row = tokens committed so far + b;
+// logits_out != nullptr receives all logits as [B][V].
 template <typename WT, int B>
 __global__ __launch_bounds__(kGBlock) void k_head_b(Common c, int x_slot0, const float *gain, const WT *W, float2 *cand,
-                                                    float *logits_log) {
+                                                    float *logits_log, float *logits_out) {
   extern __shared__ __align__(16) float xs[];
   __shared__ float red[kGWaves];
   __shared__ float bv[kGWaves][B];
@@ -318,6 +319,10 @@ __global__ __launch_bounds__(kGBlock) void k_head_b(Common c, int x_slot0, const
         lrow[r] = s[0][b];
         if (r + 1 < V) lrow[r + 1] = s[1][b];
       }
+      if (logits_out && lane == 0) {           // sampling needs the whole distribution of every token
+        logits_out[(size_t)b * V + r] = s[0][b];
+        if (r + 1 < V) logits_out[(size_t)b * V + r + 1] = s[1][b];
+      }
     }
   });
   if (lane == 0) {
@@ -343,6 +348,97 @@ __global__ __launch_bounds__(kBlock) void k_eesd_pick(Common c, const float2 *ca
   if (!(st->n_out < st->target)) return;
   const int tok = reduce_candidates<kBlock>(cand_exit, c.dm.head_blocks, sv, si_);
   if (threadIdx.x == 0) st->ee_draft[j + 1] = tok;
+}
+
+// Stochastic rounds (Sec. 3.1, Eq. 1-2 as stated: gamma sampled drafts, checked in order).
+// After draft step j: p_j = softmax(exit logits / T) is kept in probs_e[j] and draft x_{j+1} ~ p_j
+// becomes the token of step j + 1.
+__global__ __launch_bounds__(kSBlock) void k_eesd_pick_sample(Common c, const float *logits_exit, float *probs_e, int j,
+                                                              float inv_temp, uint32_t seed) {
+  __shared__ float scan[kSBlock + 1];
+  __shared__ float buf[kSWaves];
+  __shared__ int s_pick;
+  DevState *st = c.st;
+  if (!(st->n_out < st->target)) return;
+  const int V = c.dm.V;
+  float m = -INFINITY;
+  for (int i = threadIdx.x; i < V; i += kSBlock) m = fmaxf(m, logits_exit[i]);
+  const float mp = sblock_max(m, buf);
+  float sp;
+  const int d = sample_index([&](int i) { return __expf((logits_exit[i] - mp) * inv_temp); }, V,
+                             uniform24(seed, st->t + j + 1, kPurDraft), scan, &s_pick, &sp);
+  float *pj = probs_e + (size_t)j * V;
+  for (int i = threadIdx.x; i < V; i += kSBlock) pj[i] = __expf((logits_exit[i] - mp) * inv_temp) / sp;
+  if (threadIdx.x == 0) st->ee_draft[j + 1] = d;
+}
+
+// End of a stochastic round.  logits_b: [gamma + 1][V] from the batched LM head (row j: the full
+// model's logits for position t + j + 1).  Draft x_{j+1} is accepted iff u * p_j(x) <= q_j(x); the
+// first rejected one is replaced by a token from max(0, q_j - p_j); if all are accepted one more
+// token is sampled from q_gamma.  Commit and rollback as in the greedy round.
+__global__ __launch_bounds__(kSBlock) void k_eesd_commit_sample(Common c, const float *logits_b, const float *probs_e,
+                                                                int32_t *out_tokens, int32_t *drafts_log, int gamma,
+                                                                float inv_temp, uint32_t seed) {
+  __shared__ float scan[kSBlock + 1];
+  __shared__ float buf[kSWaves];
+  __shared__ int s_pick;
+  __shared__ int s_tok[kMaxBatch];
+  DevState *st = c.st;
+  if (!(st->n_out < st->target)) return;
+  const int V = c.dm.V;
+  const int t = st->t;
+  int n = 0;
+  bool stopped = false;
+  while (n < gamma && !stopped) {
+    const float *lg = logits_b + (size_t)n * V;
+    const float *pj = probs_e + (size_t)n * V;
+    const int pos = t + n + 1;
+    const int d = st->ee_draft[n + 1];
+    float m = -INFINITY;
+    for (int i = threadIdx.x; i < V; i += kSBlock) m = fmaxf(m, lg[i]);
+    const float mq = sblock_max(m, buf);
+    float sq;
+    (void)sample_index([&](int i) { return __expf((lg[i] - mq) * inv_temp); }, V, 0.f, scan, &s_pick, &sq);
+    const float qd = __expf((lg[d] - mq) * inv_temp) / sq;
+    const bool ok = uniform24(seed, pos, kPurAccept) * pj[d] <= qd;
+    int tok = d;
+    if (!ok) {
+      auto resid = [&](int i) { return fmaxf(0.f, __expf((lg[i] - mq) * inv_temp) / sq - pj[i]); };
+      float sr;
+      tok = sample_index(resid, V, uniform24(seed, pos, kPurResample), scan, &s_pick, &sr);
+      if (!(sr > 0.f))
+        tok = sample_index([&](int i) { return __expf((lg[i] - mq) * inv_temp); }, V, uniform24(seed, pos, kPurResample),
+                           scan, &s_pick, nullptr);
+      stopped = true;
+    }
+    if (threadIdx.x == 0) s_tok[n] = tok;
+    if (ok) ++n;
+  }
+  if (n == gamma) {                             // every draft accepted: the full model's own token follows
+    const float *lg = logits_b + (size_t)gamma * V;
+    float m = -INFINITY;
+    for (int i = threadIdx.x; i < V; i += kSBlock) m = fmaxf(m, lg[i]);
+    const float mq = sblock_max(m, buf);
+    const int tok = sample_index([&](int i) { return __expf((lg[i] - mq) * inv_temp); }, V,
+                                 uniform24(seed, t + gamma + 1, kPurVanilla), scan, &s_pick, nullptr);
+    if (threadIdx.x == 0) s_tok[gamma] = tok;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    st->stats[11] += 1;
+    st->stats[1] += n + 1 < gamma ? n + 1 : gamma;
+    st->stats[2] += n;
+    if (n < gamma) { st->stats[3] += 1; st->stats[6] += 1; }
+    const int room = st->target - st->n_out;
+    const int k = n + 1 < room ? n + 1 : room;
+    for (int i = 0; i < k; ++i) {
+      out_tokens[st->n_out + i] = s_tok[i];
+      drafts_log[st->gen_count + i] = i < gamma ? st->ee_draft[i + 1] : -1;
+    }
+    st->n_out += k; st->gen_count += k; st->stats[0] += k;
+    st->t += k;
+    st->last_token = s_tok[k - 1];
+  }
 }
 
 // End of a round: the full model's tokens v_0..v_gamma, the accepted prefix, the commit.

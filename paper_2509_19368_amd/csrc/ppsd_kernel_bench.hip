@@ -141,7 +141,7 @@ int main(int argc, char **argv) {
   });
   run("k_head_b<4>", (size_t)V * d * 2, [&](const bf16_t *w) {
     hipLaunchKernelGGL((k_head_b<bf16_t, B>), dim3(c.dm.head_blocks), dim3(kGBlock), lds_d, 0, c, (int)kXBatchWorkSlot0, gain, w,
-                       candb, (float *)nullptr);
+                       candb, (float *)nullptr, (float *)nullptr);
   });
   CK(hipGetLastError());
   return 0;

@@ -185,3 +185,26 @@ def test_committed_tokens_follow_the_target_distribution(P):
     got = sum(a for _, a in obs) / n
     assert abs(got - alpha) < 4.0 * math.sqrt(alpha * (1 - alpha) / n) + 0.01, (got, alpha)
     assert 0.15 < alpha < 0.95
+
+
+@pytest.mark.parametrize("gamma", [1, 3, 4])
+def test_sampled_draft_then_verify_rounds_equal_the_simulator(P, gamma):
+    """Eq. (1)-(2) as stated: gamma sampled drafts per round, checked in order against one batched pass."""
+    for w in SHAPES:
+        W = S.make_weights(w)
+        W["lm_head"], W["exit_head"] = W["lm_head"] * 20.0, W["exit_head"] * 20.0
+        prompt = S.make_prompt(w)
+        n = w.decode_len
+        dec = O.Decoder(w, W)
+        T, seed = 0.8, 4321
+        es = ST.stochastic_eesd_prefill(dec, prompt, len(prompt) + n + gamma + 2, gamma, T, seed)
+        want = [es.last_token] + ST.stochastic_eesd_decode(es, n, T, seed)
+        ss = P.Session(w, to_device(W, "cuda"), max_seq=len(prompt) + 1 + n + gamma, mode=P.MODE_EESD, eesd_gamma=gamma,
+                       temperature=T, sample_seed=seed)
+        toks = [ss.ppsd_prefill(prompt)] + ss.ppsd_decode(n)
+        st, drafts = ss.ppsd_stats(), ss.read_drafts(0, n + 1)
+        ss.close()
+        assert toks == want and drafts == [-1] + es.compared
+        assert (st["eesd_rounds"], st["accepted"], st["rejected"], st["drafts_compared"]) == \
+               (es.stats.rounds, es.stats.accepted, es.stats.rejected, es.stats.drafts_compared)
+        assert st["accepted"] > 0 and st["rejected"] > 0
