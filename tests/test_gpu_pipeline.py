@@ -193,3 +193,26 @@ def test_pipeline_full_size_7b_is_bitwise_the_vanilla_stream(P):
     assert st["pipeline_ticks"] == (S_ - 1) + n + (S_ - 1) * rej_before_last
     assert st["flushed_tokens"] == (S_ - 1) * st["rejected"]
     assert 0 < st["rejected"] < n
+
+
+@pytest.mark.parametrize("name,prompt_len,n", [("C4", 48, 10), ("C5", 600, 8)], ids=["13B", "8B_GQA_long_context"])
+def test_big_shapes_pipeline_and_rounds_against_vanilla(P, name, prompt_len, n):
+    """13B and 8B-GQA shapes (two attention splits on the latter): the S-stage schedule must commit vanilla
+    mode's stream bit for bit; draft-then-verify rounds (column slabs in the down-projection) stay within
+    2e-3 of vanilla mode's logits on the common prefix."""
+    w = S.WORKLOADS[name].replace(prompt_len=prompt_len, decode_len=n)
+    Wg = S.make_weights(w, device="cuda")
+    prompt = S.make_prompt(w)
+    v = _run(P, w, Wg, prompt, [n], P.MODE_VANILLA, max_seq=prompt_len + n + 8)
+    a = _run(P, w, Wg, prompt, [n], P.MODE_PIPELINE, max_seq=prompt_len + n + 8)
+    assert a["tokens"] == v["tokens"] and torch.equal(a["logits"], v["logits"])
+    st = a["stats"][-1]
+    assert st["committed"] == n and st["flushed_tokens"] == (_n_stages(w) - 1) * st["rejected"]
+    e = _run(P, w, Wg, prompt, [n], P.MODE_EESD, max_seq=prompt_len + n + 8, eesd_gamma=3)
+    same = 0
+    while same <= n and e["tokens"][same] == v["tokens"][same]:
+        same += 1
+    assert same >= 2
+    scale = v["logits"].abs().max(dim=1).values
+    assert ((e["logits"][:same] - v["logits"][:same]).abs().max(dim=1).values / scale[:same]).max().item() < 2e-3
+    assert e["stats"][-1]["committed"] == n
