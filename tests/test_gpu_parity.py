@@ -350,3 +350,43 @@ def test_matrix_core_prefill_matches_oracle_and_looped_prefill(P, prompt_len):
         same += 1
     assert same >= 1
     assert diff[:same].max().item() < 2e-3, diff
+
+
+def test_widest_supported_shape(P):
+    """The staging capacity limits: d_model 8192 and d_ffn 16384 (64 KB of LDS per staged vector), 64 heads.
+    Every schedule must commit vanilla mode's stream bit for bit (draft-then-verify: the batched pass needs
+    column slabs here, so it is held to the oracle instead), and the oracle protocol must hold."""
+    w = S.Workload("wide", n_layers=2, exit_layer=1, d_model=8192, n_heads=64, n_kv_heads=64, head_dim=128, d_ffn=16384,
+                   vocab=1031, dtype="bf16", damp=0.2, seed=77, prompt_len=5, decode_len=7)
+    Wg = S.make_weights(w, device="cuda")
+    prompt = S.make_prompt(w)
+    n = w.decode_len
+    runs = {}
+    for name, mode in (("vanilla", P.MODE_VANILLA), ("overlap", P.MODE_OVERLAP), ("pipeline", P.MODE_PIPELINE),
+                       ("eesd", P.MODE_EESD)):
+        ss = P.Session(w, Wg, max_seq=len(prompt) + n + 6, mode=mode, debug_logits=n + 1, eesd_gamma=3)
+        toks = [ss.ppsd_prefill(prompt)] + ss.ppsd_decode(n)
+        runs[name] = (toks, ss.read_logits(0, n + 1))
+        ss.close()
+    for name in ("overlap", "pipeline"):
+        assert runs[name][0] == runs["vanilla"][0] and torch.equal(runs[name][1], runs["vanilla"][1]), name
+    W = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in Wg.items()}
+    del Wg
+    torch.cuda.empty_cache()
+    dec = O.Decoder(w, W)
+    for name in ("vanilla", "eesd"):
+        check_against_teacher_forced_oracle(dec, prompt, runs[name][0], runs[name][1], REL_TOL_BF16)
+
+
+def test_empty_decode_and_single_token_prompt(P):
+    w = S.WORKLOADS["C1"]
+    Wg = to_device(S.make_weights(w), "cuda")
+    ss = P.Session(w, Wg, max_seq=8, mode=P.MODE_OVERLAP)
+    t0 = ss.ppsd_prefill([7])
+    assert ss.ppsd_decode(0) == []
+    a = ss.ppsd_decode(2)
+    assert ss.ppsd_decode(0) == []
+    b = ss.ppsd_decode(2)
+    ss.close()
+    dec = O.Decoder(w, S.make_weights(w))
+    assert [t0] + a + b == O.greedy_decode(dec, [7], 5).tokens
