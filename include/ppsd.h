@@ -101,7 +101,7 @@ typedef struct {
   int32_t time_kernels;    /* 1: profiling mode -- direct launches on one stream with a HIP event
                               between consecutive kernels, totals via ppsd_kernel_times (slow) */
   int32_t engine;          /* PPSD_ENGINE_*: how a step is executed on the GPU */
-  int32_t prefill_loop;    /* 0: prefill on the matrix cores (MFMA GEMMs over chunks of the prompt) when the
+  int32_t prefill_loop;    /* 0: prefill on the matrix cores (MFMA GEMMs over chunks of the prompt, see prefill_chunk) when the
                               configuration allows it (bf16, head_dim 128, d_model % 128 == 0,
                               d_ffn % 64 == 0), else the loop below; 1: always run the prompt through the
                               decode kernels one position at a time */
@@ -132,6 +132,9 @@ typedef struct {
                               function applied to seed ^ position * 0xD1342543DE82EF95 ^ purpose *
                               0xA0761D6478BD642F (64-bit wrapping), purpose = 0 draft, 1 acceptance,
                               2 replacement, 3 plain sampling: a pure function of the three, whatever the schedule */
+  int32_t prefill_chunk;   /* positions the matrix-core prefill takes through the layers at a time: 0 = default
+                              (the whole prompt capacity max_seq, 2048 at most), else a multiple of 128 in
+                              128..2048.  Sizes the chunk buffers inside the workspace */
 } ppsd_config;
 
 /* DEVICE pointers, BORROWED.  Per-layer entries are HOST arrays of n_layers DEVICE pointers

@@ -3,6 +3,7 @@
 // optionally replayed from a captured HIP graph) and the decode loop.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -56,7 +57,8 @@ struct Layout {
   size_t state, prompt, out_tokens, drafts, page_table, rope_cos, rope_sin, xbuf;
   size_t q[kMaxStreams], a[kMaxStreams], mbuf[kMaxStreams], partials[kMaxStreams], counters[kMaxStreams], cand_lm, cand_exit, sink, logits, kv;
   size_t layer_ptrs, bar, abort_flag, trace, cand_counts;
-  size_t pf_x, pf_q, pf_ao, pf_m, pf_rs;   // MFMA prefill chunk buffers (0 bytes when not used)
+  size_t pf_x, pf_q, pf_ao, pf_ah, pf_al, pf_mh, pf_ml, pf_part;   // MFMA prefill chunk buffers (0 bytes when not used)
+  int pf_chunk;          // positions per prefill chunk
   size_t qb, ab, mb, partials_b, counters_b, cand_b;   // batched verify pass (0 bytes unless PPSD_MODE_EESD)
   size_t logits_lm, logits_exit, probs;                // sampling (0 bytes unless temperature > 0)
   size_t logits_b, probs_e;                            // sampling in draft-then-verify rounds
@@ -92,6 +94,8 @@ bool valid_config(const ppsd_config *c, const char **why) {
   REJECT(c->engine != PPSD_ENGINE_STREAMS && c->engine != PPSD_ENGINE_PERSISTENT, "engine must be 0 or 1");
   REJECT(c->engine == PPSD_ENGINE_PERSISTENT && c->time_kernels, "time_kernels needs the per-operation engine");
   REJECT(c->prefill_loop != 0 && c->prefill_loop != 1, "prefill_loop must be 0 or 1");
+  REJECT(c->prefill_chunk != 0 && (c->prefill_chunk < kPfBM || c->prefill_chunk > kPfChunkMax || c->prefill_chunk % kPfBM),
+         "prefill_chunk must be 0 or a multiple of 128 in 128..2048");
   if (c->mode == PPSD_MODE_PIPELINE) {
     REJECT(c->engine != PPSD_ENGINE_STREAMS, "the full pipeline schedule runs on the per-operation engine only");
     REJECT(c->time_kernels, "time_kernels is not available with the full pipeline schedule");
@@ -159,12 +163,25 @@ Layout make_layout(const ppsd_config *c) {
   L.cand_counts = take(256);
   L.trace = take(8ull * kTraceSlots * kTracePhases);
   L.pf = pf_eligible(c);
-  const size_t pc = L.pf ? kPfChunk : 0;
+  // a chunk covers the whole prompt when max_seq allows, 2048 positions at most
+  L.pf_chunk = !L.pf ? 0 : c->prefill_chunk ? c->prefill_chunk : std::min(kPfChunkMax, (c->max_seq + kPfBM - 1) / kPfBM * kPfBM);
+  const size_t pc = (size_t)L.pf_chunk;
+  const size_t wide = std::max((size_t)c->d_model, nq);
   L.pf_x = take(4ull * pc * c->d_model);
   L.pf_q = take(4ull * pc * nq);
   L.pf_ao = take(4ull * pc * nq);
-  L.pf_m = take(4ull * pc * c->d_ffn);
-  L.pf_rs = take(4ull * pc);
+  L.pf_ah = take(2ull * pc * wide);
+  L.pf_al = take(2ull * pc * wide);
+  L.pf_mh = take(2ull * pc * c->d_ffn);
+  L.pf_ml = take(2ull * pc * c->d_ffn);
+  size_t part = 0;       // the largest split-K partial-sum buffer any chunk length can ask for
+  for (int nv = kPfBM; nv <= L.pf_chunk; nv += kPfBM) {
+    part = std::max(part, pf_partial_floats(pf_plan(nv, (int)(nq + 2ull * c->n_kv_heads * c->head_dim), c->d_model)));
+    part = std::max(part, pf_partial_floats(pf_plan(nv, c->d_model, (int)nq)));
+    part = std::max(part, pf_partial_floats(pf_plan(nv, 2 * c->d_ffn, c->d_model)));
+    part = std::max(part, pf_partial_floats(pf_plan(nv, c->d_model, c->d_ffn)));
+  }
+  L.pf_part = take(4ull * part);
   const size_t nb = c->mode == PPSD_MODE_EESD ? kMaxBatch : 0;
   L.qb = take(4ull * nb * nq);
   L.ab = take(4ull * nb * nq);
@@ -723,46 +740,57 @@ int mega_setup(ppsd_ctx *x) {
 }
 
 // ---------------------------------------------------------------- matrix-core prefill
+// One projection of a chunk: the GEMM over g.n_valid positions and n_cols output columns, then, when K
+// was split, the kernel that adds the partial tiles and runs the epilogue.
 template <int EPI>
-void pf_launch_gemm(ppsd_ctx *x, const PfGemm &g, int n_tiles_n) {
-  const dim3 grid(n_tiles_n, (g.n_valid + kPfBM - 1) / kPfBM);
-  hipLaunchKernelGGL((k_pf_gemm<EPI>), grid, dim3(kPfBlock), 0, x->sA, x->cm, g);
+void pf_launch_gemm(ppsd_ctx *x, PfGemm g, int n_cols) {
+  const PfPlan pl = pf_plan(g.n_valid, n_cols, g.K);
+  g.tiles_m = pl.tiles_m; g.tiles_n = pl.tiles_n; g.splits = pl.splits;
+  g.part = at<float>(x, x->lay.pf_part);
+  const int n_groups = (pl.tiles_n + kPfXcds - 1) / kPfXcds;
+  hipLaunchKernelGGL((k_pf_gemm<EPI>), dim3(kPfXcds * pl.tiles_m * pl.splits * n_groups), dim3(kPfBlock), 0, x->sA, x->cm, g);
+  if (pl.splits > 1)
+    hipLaunchKernelGGL((k_pf_reduce<EPI>), dim3(pl.tiles_n, (g.n_valid + kPfBlock / 32 - 1) / (kPfBlock / 32)), dim3(kPfBlock), 0,
+                       x->sA, x->cm, g);
 }
 
 int prefill_mfma(ppsd_ctx *x, int n_prompt) {
   const ppsd_config &c = x->cfg;
   const int d = c.d_model, f = c.d_ffn, nq = c.n_heads * c.head_dim;
-  const int qkv_heads = c.n_heads + 2 * c.n_kv_heads, G = c.n_heads / c.n_kv_heads;
+  const int qkv_cols = (c.n_heads + 2 * c.n_kv_heads) * c.head_dim, G = c.n_heads / c.n_kv_heads;
   float *X = at<float>(x, x->lay.pf_x), *Q = at<float>(x, x->lay.pf_q), *AO = at<float>(x, x->lay.pf_ao);
-  float *M = at<float>(x, x->lay.pf_m), *rs = at<float>(x, x->lay.pf_rs);
-  const int waves = kPfBlock / kWave;
-  for (int c0 = 0; c0 < n_prompt; c0 += kPfChunk) {
-    const int nv = n_prompt - c0 < kPfChunk ? n_prompt - c0 : kPfChunk;
+  bf16_t *Ah = at<bf16_t>(x, x->lay.pf_ah), *Al = at<bf16_t>(x, x->lay.pf_al);
+  bf16_t *Mh = at<bf16_t>(x, x->lay.pf_mh), *Ml = at<bf16_t>(x, x->lay.pf_ml);
+  const int waves = kPfBlock / kWave, chunk = x->lay.pf_chunk;
+  for (int c0 = 0; c0 < n_prompt; c0 += chunk) {
+    const int nv = n_prompt - c0 < chunk ? n_prompt - c0 : chunk;
+    const dim3 sgrid((nv + waves - 1) / waves);
     hipLaunchKernelGGL(k_pf_embed, dim3(nv), dim3(kPfBlock), 0, x->sA, (const bf16_t *)x->embed, x->cm.prompt, c0, nv, d, X);
     for (int l = 0; l < c.n_layers; ++l) {
       PfGemm g{};
-      g.n_valid = nv; g.c0 = c0; g.layer = l; g.X = X; g.Q = Q; g.M = M;
-      hipLaunchKernelGGL(k_pf_rowscale, dim3((nv + waves - 1) / waves), dim3(kPfBlock), 0, x->sA, (const float *)X, d, nv, c.rms_eps, rs);
-      g.A = X; g.rs = rs; g.gain = (const float *)x->attn_norm[l]; g.W = (const bf16_t *)x->wqkv[l]; g.K = d;
-      pf_launch_gemm<kPfQkv>(x, g, qkv_heads);
+      g.n_valid = nv; g.c0 = c0; g.layer = l; g.X = X; g.Q = Q; g.Mh = Mh; g.Ml = Ml; g.Ah = Ah; g.Al = Al;
+      hipLaunchKernelGGL(k_pf_split, sgrid, dim3(kPfBlock), 0, x->sA, (const float *)X, d, nv, (const float *)x->attn_norm[l], c.rms_eps, Ah, Al);
+      g.W = (const bf16_t *)x->wqkv[l]; g.K = d;
+      pf_launch_gemm<kPfQkv>(x, g, qkv_cols);
       const dim3 agrid(c.n_kv_heads, nv);
       if (G == 1) hipLaunchKernelGGL((k_pf_attn<1>), agrid, dim3(kPfBlock), 0, x->sA, x->cm, l, c0, (const float *)Q, AO);
       else if (G == 2) hipLaunchKernelGGL((k_pf_attn<2>), agrid, dim3(kPfBlock), 0, x->sA, x->cm, l, c0, (const float *)Q, AO);
       else hipLaunchKernelGGL((k_pf_attn<4>), agrid, dim3(kPfBlock), 0, x->sA, x->cm, l, c0, (const float *)Q, AO);
-      g.A = AO; g.rs = nullptr; g.gain = nullptr; g.W = (const bf16_t *)x->wo[l]; g.K = nq;
-      pf_launch_gemm<kPfResid>(x, g, d / kPfBN);
-      hipLaunchKernelGGL(k_pf_rowscale, dim3((nv + waves - 1) / waves), dim3(kPfBlock), 0, x->sA, (const float *)X, d, nv, c.rms_eps, rs);
-      g.A = X; g.rs = rs; g.gain = (const float *)x->mlp_norm[l]; g.W = (const bf16_t *)x->wgu[l]; g.K = d;
-      pf_launch_gemm<kPfSwiglu>(x, g, f / 64);
-      g.A = M; g.rs = nullptr; g.gain = nullptr; g.W = (const bf16_t *)x->wdown[l]; g.K = f;
-      pf_launch_gemm<kPfResid>(x, g, d / kPfBN);
+      hipLaunchKernelGGL(k_pf_split, sgrid, dim3(kPfBlock), 0, x->sA, (const float *)AO, nq, nv, (const float *)nullptr, 0.0f, Ah, Al);
+      g.W = (const bf16_t *)x->wo[l]; g.K = nq;
+      pf_launch_gemm<kPfResid>(x, g, d);
+      hipLaunchKernelGGL(k_pf_split, sgrid, dim3(kPfBlock), 0, x->sA, (const float *)X, d, nv, (const float *)x->mlp_norm[l], c.rms_eps, Ah, Al);
+      g.W = (const bf16_t *)x->wgu[l]; g.K = d;
+      pf_launch_gemm<kPfSwiglu>(x, g, 2 * f);
+      g.Ah = Mh; g.Al = Ml; g.W = (const bf16_t *)x->wdown[l]; g.K = f;
+      pf_launch_gemm<kPfResid>(x, g, d);
       if (c.exit_block && l == c.exit_layer - 1) {
         // K/V rows of the early-exit block for the prompt positions: its QKV projection on h^E
         // (the q it also writes is overwritten by the next layer)
         const int xl = c.n_layers;
-        hipLaunchKernelGGL(k_pf_rowscale, dim3((nv + waves - 1) / waves), dim3(kPfBlock), 0, x->sA, (const float *)X, d, nv, c.rms_eps, rs);
-        g.layer = xl; g.A = X; g.rs = rs; g.gain = (const float *)x->attn_norm[xl]; g.W = (const bf16_t *)x->wqkv[xl]; g.K = d;
-        pf_launch_gemm<kPfQkv>(x, g, qkv_heads);
+        hipLaunchKernelGGL(k_pf_split, sgrid, dim3(kPfBlock), 0, x->sA, (const float *)X, d, nv, (const float *)x->attn_norm[xl], c.rms_eps, Ah, Al);
+        g.layer = xl; g.Ah = Ah; g.Al = Al; g.W = (const bf16_t *)x->wqkv[xl]; g.K = d;
+        pf_launch_gemm<kPfQkv>(x, g, qkv_cols);
       }
       HIP_TRY(hipGetLastError());
     }

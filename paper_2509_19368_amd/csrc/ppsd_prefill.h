@@ -1,58 +1,112 @@
-// Prefill on the matrix cores: the prompt is processed in chunks of kPfChunk positions; inside a
-// chunk every projection is a dense [positions x K] x [K x N] contraction and runs on MFMA
-// (v_mfma_f32_32x32x8_bf16_1k), with the layer's element-wise work fused into the GEMM epilogues
+// Prefill on the matrix cores: the prompt is processed in chunks of up to kPfChunkMax positions;
+// inside a chunk every projection is a dense [positions x K] x [K x N] contraction and runs on MFMA
+// (v_mfma_f32_32x32x16_bf16), with the layer's element-wise work fused into the GEMM epilogues
 // (rotary + KV append, residual add, SwiGLU).  bf16 storage, head_dim 128.
 //
-// Precision: weights enter at their stored bf16 values; the fp32 activations are split on the fly
-// into a bf16 high part and a bf16 low part (a = hi + lo up to 2^-17 relative) and both parts are
-// multiplied, so the products carry fp32-grade activations like the decode path's FMA chains, and
-// the accumulators are fp32.  Decode attention over the chunk's queries reuses attn_unit.
+// Precision: weights enter at their stored bf16 values; the fp32 activations are split, once per
+// projection input, into a bf16 high part and a bf16 low part (a = hi + lo up to 2^-17 relative)
+// and both parts are multiplied, so the products carry fp32-grade activations like the decode
+// path's FMA chains, and the accumulators are fp32.  Attention over the chunk's queries reuses
+// attn_unit.
+//
+// The GEMM: 128 x 128 output tile per workgroup, K step 32, 4 waves x (32 positions x 128
+// features).  LDS holds two stages of (A high, A low, W) tiles, rows padded to 80 bytes so that the
+// 16-byte operand reads of 16 consecutive rows fall on distinct banks; the tiles two K steps ahead
+// travel in registers while the current ones are multiplied, one barrier per K step.  Few output
+// tiles (short prompts) are split along K over several workgroups, whose partial tiles a second
+// kernel adds in a fixed order before the epilogue, so results do not depend on timing.
+// Workgroup ids map to tiles so that all tiles of one weight row block run on one XCD (ids go
+// round-robin over the 8 XCDs): each weight tile is fetched from HBM into one L2 only.
 #pragma once
 
 #include "ppsd_kernels.h"
 
 namespace ppsd {
 
-constexpr int kPfChunk = 512;    // positions per prefill chunk
-constexpr int kPfBM = 128;       // positions per GEMM tile (4 waves x 32)
-constexpr int kPfBN = 128;       // output features per GEMM tile (4 MFMA tiles of 32)
-constexpr int kPfBK = 32;        // K step
-constexpr int kPfLd = kPfBK + 4; // LDS row pitch in bf16 elements (72 bytes)
+constexpr int kPfChunkMax = 2048;   // positions per prefill chunk, at most
+constexpr int kPfBM = 128;          // positions per GEMM tile (4 waves x 32)
+constexpr int kPfBN = 128;          // output features per GEMM tile (4 MFMA tiles of 32)
+constexpr int kPfBK = 32;           // K step (2 MFMA k-blocks of 16)
+constexpr int kPfPitch = kPfBK + 8; // LDS row pitch in bf16 elements (80 bytes)
 constexpr int kPfBlock = 256;
+constexpr int kPfXcds = 8;
+constexpr int kPfTargetWgs = 512;   // K is split until about this many workgroups exist
+constexpr int kPfMaxSplit = 8;
+constexpr int kPfMinSteps = 4;      // K steps per split, at least
 
-typedef short bf16x4_t __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 enum PfEpilogue : int { kPfQkv = 0, kPfResid = 1, kPfSwiglu = 2 };
 
+struct PfPlan { int tiles_m, tiles_n, splits; };
+
+// How a [n_valid x n_cols] output with inner length K is cut into workgroups.
+inline PfPlan pf_plan(int n_valid, int n_cols, int K) {
+  PfPlan p;
+  p.tiles_m = (n_valid + kPfBM - 1) / kPfBM;
+  p.tiles_n = n_cols / kPfBN;
+  const int tiles = p.tiles_m * p.tiles_n, steps = K / kPfBK;
+  int s = 1;
+  if (tiles < kPfTargetWgs) s = (kPfTargetWgs + tiles - 1) / tiles;
+  if (s > kPfMaxSplit) s = kPfMaxSplit;
+  if (s > steps / kPfMinSteps) s = steps / kPfMinSteps;
+  p.splits = s < 1 ? 1 : s;
+  return p;
+}
+// Floats of partial-sum storage the plan needs (0 when K is not split).
+inline size_t pf_partial_floats(const PfPlan &p) {
+  return p.splits > 1 ? (size_t)p.splits * p.tiles_m * kPfBM * p.tiles_n * kPfBN : 0;
+}
+
 struct PfGemm {
-  const float *A;        // [chunk][K] fp32 activations
-  const float *rs;       // [chunk] 1/sqrt(mean(x^2)+eps) per position, or nullptr (no norm)
-  const float *gain;     // [K] norm gain, with rs
+  const bf16_t *Ah, *Al; // [chunk][K] high and low parts of the activations
   const bf16_t *W;       // [N_total][K] row-major
   int K;
   int n_valid;           // positions in this chunk
   int c0;                // first position of the chunk
   int layer;
+  int tiles_m, tiles_n, splits;
+  float *part;           // [splits][tiles_m*128][tiles_n*128] partial sums, when splits > 1
   // epilogue targets
   float *X;              // kPfResid: X[p][n] += C (row pitch d)
   float *Q;              // kPfQkv: rotated queries [chunk][n_h*hd]
-  float *M;              // kPfSwiglu: [chunk][f]
+  bf16_t *Mh, *Ml;       // kPfSwiglu: [chunk][f], high and low parts
 };
 
-// rs[p] = 1/sqrt(mean(X[p]^2) + eps); one wave per position.
-__global__ __launch_bounds__(kPfBlock) void k_pf_rowscale(const float *X, int d, int n_valid, float eps, float *rs) {
+__device__ __forceinline__ void split_bf16(float v, bf16_t &hi, bf16_t &lo) {
+  hi = float_to_bf16_rne(v);
+  lo = float_to_bf16_rne(v - Pack<bf16_t>::to_float(hi));
+}
+
+// hi/lo[p][:] = split(src[p][:] * (gain ? gain[:] / sqrt(mean(src[p]^2) + eps) : 1)); one wave per position.
+__global__ __launch_bounds__(kPfBlock) void k_pf_split(const float *src, int K, int n_valid, const float *gain, float eps,
+                                                      bf16_t *hi, bf16_t *lo) {
   const int p = blockIdx.x * (kPfBlock / kWave) + (threadIdx.x >> 6);
   if (p >= n_valid) return;
   const int lane = threadIdx.x & 63;
-  const float *x = X + (size_t)p * d;
-  float ss = 0.f;
-  for (int i = lane * 4; i < d; i += kWave * 4) {
-    const float4 v = *(const float4 *)(x + i);
-    ss = fmaf(v.x, v.x, ss); ss = fmaf(v.y, v.y, ss); ss = fmaf(v.z, v.z, ss); ss = fmaf(v.w, v.w, ss);
+  const float *x = src + (size_t)p * K;
+  float rs = 1.0f;
+  if (gain) {
+    float ss = 0.f;
+    for (int i = lane * 4; i < K; i += kWave * 4) {
+      const float4 v = *(const float4 *)(x + i);
+      ss = fmaf(v.x, v.x, ss); ss = fmaf(v.y, v.y, ss); ss = fmaf(v.z, v.z, ss); ss = fmaf(v.w, v.w, ss);
+    }
+    ss = wave_sum(ss);
+    rs = 1.0f / sqrtf(ss / (float)K + eps);
   }
-  ss = wave_sum(ss);
-  if (lane == 0) rs[p] = 1.0f / sqrtf(ss / (float)d + eps);
+  for (int i = lane * 4; i < K; i += kWave * 4) {
+    float4 v = *(const float4 *)(x + i);
+    if (gain) {
+      const float4 gg = *(const float4 *)(gain + i);
+      v.x *= rs * gg.x; v.y *= rs * gg.y; v.z *= rs * gg.z; v.w *= rs * gg.w;
+    }
+    bf16_t h[4], l[4];
+    split_bf16(v.x, h[0], l[0]); split_bf16(v.y, h[1], l[1]); split_bf16(v.z, h[2], l[2]); split_bf16(v.w, h[3], l[3]);
+    *(uint2 *)(hi + (size_t)p * K + i) = make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16));
+    *(uint2 *)(lo + (size_t)p * K + i) = make_uint2((uint32_t)l[0] | ((uint32_t)l[1] << 16), (uint32_t)l[2] | ((uint32_t)l[3] << 16));
+  }
 }
 
 // X[p][:] = Emb[prompt[c0 + p]][:] as fp32.
@@ -64,29 +118,89 @@ __global__ __launch_bounds__(kPfBlock) void k_pf_embed(const bf16_t *embed, cons
   for (int i = threadIdx.x * 4; i < d; i += kPfBlock * 4) *(float4 *)(X + (size_t)p * d + i) = load4_as_float(row + i);
 }
 
-// One 128 x 128 output tile per workgroup.  grid = (N tiles, position tiles).
-// Tile row r of the weight operand is W row:  plain: tile_n*128 + r;
-// kPfSwiglu: r < 64 -> gate row tile_n*64 + r, else up row f + tile_n*64 + (r - 64), so that a
-// lane finds gate_i in MFMA tile j and up_i in tile j + 2, exactly like the rotary pair (i, i + 64).
+// What happens to the four values v[nt] = C[p][tile column nt*32 + col] of one output tile row.
+// Tile column r is weight row:  plain: tile_n*128 + r;  kPfSwiglu: r < 64 -> gate row tile_n*64 + r,
+// else up row f + tile_n*64 + (r - 64), so that gate_i sits in v[nt] and up_i in v[nt + 2], exactly
+// like the rotary pair (i, i + 64) of a head in kPfQkv.
+template <int EPI>
+__device__ __forceinline__ void pf_epilogue(const Common &c, const PfGemm &g, int tile_n, int p, int col, const float (&v)[4]) {
+  const Dims &m = c.dm;
+  if (EPI == kPfResid) {
+    float *xr = g.X + (size_t)p * m.d + tile_n * kPfBN + col;
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) xr[nt * 32] += v[nt];
+  } else if (EPI == kPfSwiglu) {
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+      const float gt = v[nt], up = v[nt + 2];
+      const size_t at = (size_t)p * m.f + tile_n * 64 + nt * 32 + col;
+      split_bf16(gt / (1.0f + __expf(-gt)) * up, g.Mh[at], g.Ml[at]);
+    }
+  } else {   // kPfQkv: tile_n is the head
+    const int h = tile_n, pos = g.c0 + p, half = m.hd >> 1;
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) {
+      const int i = nt * 32 + col;
+      float lo = v[nt], hi = v[nt + 2];
+      if (h < m.n_h + m.n_kv) {
+        const float cs = c.rope_cos[(size_t)pos * half + i], sn = c.rope_sin[(size_t)pos * half + i];
+        const float rlo = lo * cs - hi * sn, rhi = hi * cs + lo * sn;
+        lo = rlo; hi = rhi;
+      }
+      if (h < m.n_h) {
+        float *qr = g.Q + (size_t)p * (m.n_h * m.hd) + h * m.hd;
+        qr[i] = lo; qr[i + half] = hi;
+      } else {
+        const int which = (h < m.n_h + m.n_kv) ? 0 : 1;
+        const int kvh = which ? h - m.n_h - m.n_kv : h - m.n_h;
+        bf16_t *dst = kv_row<bf16_t>(c, c.page_table, g.layer, pos, kvh, which);
+        dst[i] = float_to_bf16_rne(lo); dst[i + half] = float_to_bf16_rne(hi);
+      }
+    }
+  }
+}
+
+struct PfRegs { uint4 ah0, ah1, al0, al1, w0, w1; };   // one K step of the three tiles, this thread's share
+
+// One 128 x 128 output tile (or one K range of it) per workgroup; 1-D grid of
+// 8 * tiles_m * splits * ceil(tiles_n / 8) workgroups.
 template <int EPI>
 __global__ __launch_bounds__(kPfBlock) void k_pf_gemm(Common c, PfGemm g) {
-  __shared__ __attribute__((aligned(16))) bf16_t sAh[kPfBM * kPfLd];
-  __shared__ __attribute__((aligned(16))) bf16_t sAl[kPfBM * kPfLd];
-  __shared__ __attribute__((aligned(16))) bf16_t sW[kPfBN * kPfLd];
+  __shared__ __attribute__((aligned(16))) bf16_t lds[2][3][kPfBM * kPfPitch];
   const Dims &m = c.dm;
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
-  const int tile_n = blockIdx.x, tile_m = blockIdx.y;
-  const int K = g.K;
+  // id -> (XCD, then position tile fastest, then K range, then weight row block)
+  const int xcd = blockIdx.x % kPfXcds, local = blockIdx.x / kPfXcds;
+  const int tile_m = local % g.tiles_m, rest = local / g.tiles_m;
+  const int split = rest % g.splits, tile_n = (rest / g.splits) * kPfXcds + xcd;
+  if (tile_n >= g.tiles_n) return;
+  const int K = g.K, steps = K / kPfBK;
+  const int step0 = (int)((long long)steps * split / g.splits), nk = (int)((long long)steps * (split + 1) / g.splits) - step0;
 
-  // staging assignment: thread t handles tile row t/2, 16 consecutive k at (t%2)*16
-  const int srow = tid >> 1, scol = (tid & 1) * 16;
-  const int prow = min(tile_m * kPfBM + srow, g.n_valid - 1);            // clamped position row
-  const float *a_src = g.A + (size_t)prow * K + scol;
-  const float a_rs = g.rs ? g.rs[prow] : 1.0f;
-  int wrow;
-  if (EPI == kPfSwiglu) wrow = srow < 64 ? tile_n * 64 + srow : m.f + tile_n * 64 + (srow - 64);
-  else wrow = tile_n * kPfBN + srow;
-  const bf16_t *w_src = g.W + (size_t)wrow * K + scol;
+  // staging: thread t moves, per tile, the 16-byte vector (t % 4) of rows t/4 and t/4 + 64
+  const int srow = tid >> 2, svec = (tid & 3) * 8;
+  const int prow0 = min(tile_m * kPfBM + srow, g.n_valid - 1), prow1 = min(tile_m * kPfBM + srow + 64, g.n_valid - 1);   // clamped
+  int wrow0, wrow1;
+  if (EPI == kPfSwiglu) { wrow0 = tile_n * 64 + srow; wrow1 = m.f + tile_n * 64 + srow; }
+  else { wrow0 = tile_n * kPfBN + srow; wrow1 = wrow0 + 64; }
+  const size_t koff = (size_t)step0 * kPfBK + svec;
+  const bf16_t *ah_src0 = g.Ah + (size_t)prow0 * K + koff, *ah_src1 = g.Ah + (size_t)prow1 * K + koff;
+  const bf16_t *al_src0 = g.Al + (size_t)prow0 * K + koff, *al_src1 = g.Al + (size_t)prow1 * K + koff;
+  const bf16_t *w_src0 = g.W + (size_t)wrow0 * K + koff, *w_src1 = g.W + (size_t)wrow1 * K + koff;
+  auto gload = [&](int kt) {
+    const int off = kt * kPfBK;
+    PfRegs r;
+    r.ah0 = *(const uint4 *)(ah_src0 + off); r.ah1 = *(const uint4 *)(ah_src1 + off);
+    r.al0 = *(const uint4 *)(al_src0 + off); r.al1 = *(const uint4 *)(al_src1 + off);
+    r.w0 = *(const uint4 *)(w_src0 + off); r.w1 = *(const uint4 *)(w_src1 + off);
+    return r;
+  };
+  const int s_at0 = srow * kPfPitch + svec, s_at1 = (srow + 64) * kPfPitch + svec;
+  auto lstore = [&](const PfRegs r, int st) {
+    *(uint4 *)(&lds[st][0][s_at0]) = r.ah0; *(uint4 *)(&lds[st][0][s_at1]) = r.ah1;
+    *(uint4 *)(&lds[st][1][s_at0]) = r.al0; *(uint4 *)(&lds[st][1][s_at1]) = r.al1;
+    *(uint4 *)(&lds[st][2][s_at0]) = r.w0; *(uint4 *)(&lds[st][2][s_at1]) = r.w1;
+  };
 
   f32x16_t acc[4];
 #pragma unroll
@@ -94,95 +208,78 @@ __global__ __launch_bounds__(kPfBlock) void k_pf_gemm(Common c, PfGemm g) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[nt][v] = 0.f;
 
-  const int a_row = wave * 32 + (lane & 31);   // A-operand row of this lane inside the tile
-  const int kq = 4 * (lane >> 5);              // k offset of this lane inside an MFMA k-block of 8
+  // MFMA operand of a lane: row lane % 32 of its 32-row block, 8 consecutive k at 8 * (lane / 32)
+  const int a_at = (wave * 32 + (lane & 31)) * kPfPitch + 8 * (lane >> 5);
+  const int b_at = (lane & 31) * kPfPitch + 8 * (lane >> 5);
+  auto compute = [&](int st) {
+#pragma unroll
+    for (int kk = 0; kk < kPfBK / 16; ++kk) {
+      const bf16x8_t ah = *(const bf16x8_t *)(&lds[st][0][a_at + kk * 16]);
+      const bf16x8_t al = *(const bf16x8_t *)(&lds[st][1][a_at + kk * 16]);
+      bf16x8_t b[4];
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) b[nt] = *(const bf16x8_t *)(&lds[st][2][b_at + nt * 32 * kPfPitch + kk * 16]);
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, b[nt], acc[nt], 0, 0, 0);
+#pragma unroll
+      for (int nt = 0; nt < 4; ++nt) acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, b[nt], acc[nt], 0, 0, 0);
+    }
+  };
 
-  for (int k0 = 0; k0 < K; k0 += kPfBK) {
-    // ---- global -> registers
-    float4 av[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) av[e] = *(const float4 *)(a_src + k0 + 4 * e);
-    const uint4 w0 = *(const uint4 *)(w_src + k0);
-    const uint4 w1 = *(const uint4 *)(w_src + k0 + 8);
-    if (g.rs) {
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float4 gg = *(const float4 *)(g.gain + k0 + scol + 4 * e);
-        av[e].x *= a_rs * gg.x; av[e].y *= a_rs * gg.y; av[e].z *= a_rs * gg.z; av[e].w *= a_rs * gg.w;
-      }
-    }
-    __syncthreads();   // previous step's MFMA reads are done
-    // ---- registers -> LDS (activation split into bf16 high and low parts)
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const float vals[4] = {av[e].x, av[e].y, av[e].z, av[e].w};
-      bf16_t hi[4], lo[4];
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        hi[q] = float_to_bf16_rne(vals[q]);
-        lo[q] = float_to_bf16_rne(vals[q] - Pack<bf16_t>::to_float(hi[q]));
-      }
-      *(uint2 *)(sAh + srow * kPfLd + scol + 4 * e) = make_uint2((uint32_t)hi[0] | ((uint32_t)hi[1] << 16), (uint32_t)hi[2] | ((uint32_t)hi[3] << 16));
-      *(uint2 *)(sAl + srow * kPfLd + scol + 4 * e) = make_uint2((uint32_t)lo[0] | ((uint32_t)lo[1] << 16), (uint32_t)lo[2] | ((uint32_t)lo[3] << 16));
-    }
-    *(uint2 *)(sW + srow * kPfLd + scol) = make_uint2(w0.x, w0.y);
-    *(uint2 *)(sW + srow * kPfLd + scol + 4) = make_uint2(w0.z, w0.w);
-    *(uint2 *)(sW + srow * kPfLd + scol + 8) = make_uint2(w1.x, w1.y);
-    *(uint2 *)(sW + srow * kPfLd + scol + 12) = make_uint2(w1.z, w1.w);
+  // stage s holds K step kt when kt % 2 == s; r0/r1 carry the steps after it (indices clamped to
+  // the last step: the surplus loads and stores at the end touch valid memory and are never read)
+  PfRegs r0 = gload(0), r1 = gload(min(1, nk - 1));
+  lstore(r0, 0);
+  __syncthreads();
+  // the scheduling fences keep the order  issue loads -> multiply -> store the older loads,  which is
+  // what leaves a load two K steps of time to arrive
+  for (int kt = 0; kt + 2 <= nk; kt += 2) {
+    r0 = gload(min(kt + 2, nk - 1));
+    __builtin_amdgcn_sched_barrier(0);
+    compute(0);
+    __builtin_amdgcn_sched_barrier(0);
+    lstore(r1, 1);
     __syncthreads();
-    // ---- MFMA over the K step
-#pragma unroll
-    for (int kk = 0; kk < kPfBK / 8; ++kk) {
-      const bf16x4_t ah = *(const bf16x4_t *)(sAh + a_row * kPfLd + kk * 8 + kq);
-      const bf16x4_t al = *(const bf16x4_t *)(sAl + a_row * kPfLd + kk * 8 + kq);
-#pragma unroll
-      for (int nt = 0; nt < 4; ++nt) {
-        const bf16x4_t b = *(const bf16x4_t *)(sW + (nt * 32 + (lane & 31)) * kPfLd + kk * 8 + kq);
-        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(ah, b, acc[nt], 0, 0, 0);
-        acc[nt] = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(al, b, acc[nt], 0, 0, 0);
-      }
-    }
+    r1 = gload(min(kt + 3, nk - 1));
+    __builtin_amdgcn_sched_barrier(0);
+    compute(1);
+    __builtin_amdgcn_sched_barrier(0);
+    lstore(r0, 0);
+    __syncthreads();
   }
+  if (nk & 1) compute(0);
 
-  // ---- epilogue.  acc[nt][v]: tile row wave*32 + 8*(v/4) + 4*(lane/32) + v%4, tile column nt*32 + lane%32
+  // acc[nt][v]: tile row wave*32 + 8*(v/4) + 4*(lane/32) + v%4, tile column nt*32 + lane%32
   const int col = lane & 31;
+  const size_t ncols = (size_t)g.tiles_n * kPfBN, mpad = (size_t)g.tiles_m * kPfBM;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
     const int p = tile_m * kPfBM + wave * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
     if (p >= g.n_valid) continue;
-    if (EPI == kPfResid) {
-      float *xr = g.X + (size_t)p * m.d + tile_n * kPfBN;
+    if (g.splits > 1) {
+      float *dst = g.part + ((size_t)split * mpad + p) * ncols + (size_t)tile_n * kPfBN + col;
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt) xr[nt * 32 + col] += acc[nt][v];
-    } else if (EPI == kPfSwiglu) {
-#pragma unroll
-      for (int nt = 0; nt < 2; ++nt) {
-        const float gt = acc[nt][v], up = acc[nt + 2][v];
-        g.M[(size_t)p * m.f + tile_n * 64 + nt * 32 + col] = gt / (1.0f + __expf(-gt)) * up;
-      }
-    } else {   // kPfQkv: tile_n is the head; rotation pair (i, i + 64) = MFMA tiles (nt, nt + 2)
-      const int h = tile_n, pos = g.c0 + p, half = m.hd >> 1;
-#pragma unroll
-      for (int nt = 0; nt < 2; ++nt) {
-        const int i = nt * 32 + col;
-        float lo = acc[nt][v], hi = acc[nt + 2][v];
-        if (h < m.n_h + m.n_kv) {
-          const float cs = c.rope_cos[(size_t)pos * half + i], sn = c.rope_sin[(size_t)pos * half + i];
-          const float rlo = lo * cs - hi * sn, rhi = hi * cs + lo * sn;
-          lo = rlo; hi = rhi;
-        }
-        if (h < m.n_h) {
-          float *qr = g.Q + (size_t)p * (m.n_h * m.hd) + h * m.hd;
-          qr[i] = lo; qr[i + half] = hi;
-        } else {
-          const int which = (h < m.n_h + m.n_kv) ? 0 : 1;
-          const int kvh = which ? h - m.n_h - m.n_kv : h - m.n_h;
-          bf16_t *dst = kv_row<bf16_t>(c, c.page_table, g.layer, pos, kvh, which);
-          dst[i] = float_to_bf16_rne(lo); dst[i + half] = float_to_bf16_rne(hi);
-        }
-      }
+      for (int nt = 0; nt < 4; ++nt) dst[nt * 32] = acc[nt][v];
+    } else {
+      const float vals[4] = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
+      pf_epilogue<EPI>(c, g, tile_n, p, col, vals);
     }
   }
+}
+
+// Adds the K ranges' partial tiles in range order and runs the epilogue; grid (tiles_n, ceil(n_valid / 8)).
+template <int EPI>
+__global__ __launch_bounds__(kPfBlock) void k_pf_reduce(Common c, PfGemm g) {
+  const int tile_n = blockIdx.x, p = blockIdx.y * (kPfBlock / 32) + (threadIdx.x >> 5), col = threadIdx.x & 31;
+  if (p >= g.n_valid) return;
+  const size_t ncols = (size_t)g.tiles_n * kPfBN, mpad = (size_t)g.tiles_m * kPfBM;
+  float v[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int s = 0; s < g.splits; ++s) {
+    const float *src = g.part + ((size_t)s * mpad + p) * ncols + (size_t)tile_n * kPfBN + col;
+#pragma unroll
+    for (int nt = 0; nt < 4; ++nt) v[nt] += src[nt * 32];
+  }
+  pf_epilogue<EPI>(c, g, tile_n, p, col, v);
 }
 
 // Attention of the chunk's queries: one workgroup per (KV head, query position), keys 0..position.

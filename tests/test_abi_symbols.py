@@ -34,10 +34,12 @@ def test_config_validation_runs_on_the_host():
     cfg = make_config(S.WORKLOADS["C2"], 400, P.MODE_OVERLAP)
     n = P.ppsd_workspace_bytes(cfg)
     kv = 32 * 25 * 32 * 2 * 16 * 128 * 2          # layers * pages * kv heads * (K,V) * slots * hd * bytes
-    # besides the KV pool: ~46 MiB of prompt-chunk buffers of the matrix-core prefill (512 positions x
-    # (d + 2 * n_heads * head_dim + d_ffn) floats), 4.3 MiB of attention split partials (4 stream sets x
-    # 32 heads x 64 splits x 130 floats) and under 2 MiB of activations and tables
-    pf = 4 * 512 * (4096 + 2 * 4096 + 11008)
+    # besides the KV pool: the prompt-chunk buffers of the matrix-core prefill (a chunk of 512 positions
+    # at max_seq 400: fp32 residual, queries and attention output; bf16 high + low parts of one
+    # projection input and of the SwiGLU output; split-K partial sums, largest for the QKV projection
+    # of a full chunk, 2 K ranges x 512 x 12288 floats), 4.3 MiB of attention split partials (4 stream
+    # sets x 32 heads x 64 splits x 130 floats) and under 2 MiB of activations and tables
+    pf = 4 * 512 * 3 * 4096 + 2 * 2 * 512 * (4096 + 11008) + 4 * 2 * 512 * 12288
     assert kv + pf < n < kv + pf + (8 << 20)
     cfg.mode = P.MODE_PIPELINE
     assert P.ppsd_workspace_bytes(cfg) == n           # the schedule does not change the layout

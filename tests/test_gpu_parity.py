@@ -322,21 +322,33 @@ def test_c5_shape_gqa_long_context_parity(P):
     _big_shape_parity(P, S.WORKLOADS["C5"].replace(prompt_len=600, decode_len=6), 6)
 
 
-@pytest.mark.parametrize("prompt_len", [200, 700], ids=["one_chunk_ragged", "two_chunks"])
-def test_matrix_core_prefill_matches_oracle_and_looped_prefill(P, prompt_len):
-    """Prefill through the MFMA GEMMs (chunks of 512 positions) against the oracle and against the
-    decode kernels looped over the prompt: same first token and decode stream under the bf16 protocol,
+PF_SHAPES = {
+    # K = 256 and 704: every projection is split along K (few output tiles)
+    "pf": S.Workload("pf", n_layers=3, exit_layer=1, d_model=256, n_heads=2, n_kv_heads=1, head_dim=128, d_ffn=704,
+                     vocab=777, dtype="bf16", damp=0.2, seed=31, prompt_len=1, decode_len=10),
+    # K = 128 for QKV, attention output and gate/up: too short to split, the epilogue runs inside the GEMM
+    "pf128": S.Workload("pf128", n_layers=2, exit_layer=1, d_model=128, n_heads=1, n_kv_heads=1, head_dim=128, d_ffn=320,
+                        vocab=515, dtype="bf16", damp=0.2, seed=32, prompt_len=1, decode_len=10),
+}
+
+
+@pytest.mark.parametrize("shape,prompt_len,chunk", [("pf", 200, 0), ("pf", 700, 512), ("pf", 700, 0), ("pf128", 300, 0),
+                                                    ("pf128", 300, 128)],
+                         ids=["one_chunk_ragged", "two_chunks", "six_position_tiles", "unsplit_k", "unsplit_k_three_chunks"])
+def test_matrix_core_prefill_matches_oracle_and_looped_prefill(P, shape, prompt_len, chunk):
+    """Prefill through the MFMA GEMMs (one or several chunks of positions) against the oracle and against
+    the decode kernels looped over the prompt: same first token and decode stream under the bf16 protocol,
     and logits of the two prefill paths within 2e-3 of each other (both carry fp32-grade activations;
     what differs is summation order and the bf16 rounding of K/V computed from slightly different sums)."""
-    w = S.Workload("pf", n_layers=3, exit_layer=1, d_model=256, n_heads=2, n_kv_heads=1, head_dim=128, d_ffn=704,
-                   vocab=777, dtype="bf16", damp=0.2, seed=31, prompt_len=prompt_len, decode_len=10)
+    w = PF_SHAPES[shape].replace(prompt_len=prompt_len)
     W = S.make_weights(w)
     prompt = S.make_prompt(w)
     dec = O.Decoder(w, W)
     Wg = to_device(W, "cuda")
     runs = []
     for loop in (False, True):
-        ss = P.Session(w, Wg, max_seq=prompt_len + 12, mode=P.MODE_OVERLAP, debug_logits=11, prefill_loop=loop)
+        ss = P.Session(w, Wg, max_seq=prompt_len + 12, mode=P.MODE_OVERLAP, debug_logits=11, prefill_loop=loop,
+                       prefill_chunk=chunk)
         toks = [ss.ppsd_prefill(prompt)] + ss.ppsd_decode(10)
         logits = ss.read_logits(0, 11)
         ss.close()
@@ -350,6 +362,31 @@ def test_matrix_core_prefill_matches_oracle_and_looped_prefill(P, prompt_len):
         same += 1
     assert same >= 1
     assert diff[:same].max().item() < 2e-3, diff
+
+
+def test_matrix_core_prefill_in_chunks_of_different_sizes(P):
+    """The same prompt in one chunk and in chunks of 128 and 256 positions.  A chunk's GEMM rows do not
+    interact and attention reads the KV pages, so only the K ranges of the split GEMMs (chosen from the
+    number of position tiles) differ: the logits agree to rounding order, 2e-3 of their scale, on the
+    common prefix of the decode streams."""
+    w = PF_SHAPES["pf"].replace(prompt_len=333)
+    Wg = S.make_weights(w, device="cuda")
+    prompt = S.make_prompt(w)
+    outs = []
+    for chunk in (0, 128, 256):
+        ss = P.Session(w, Wg, max_seq=333 + 12, mode=P.MODE_VANILLA, debug_logits=11, prefill_chunk=chunk)
+        toks = [ss.ppsd_prefill(prompt)] + ss.ppsd_decode(10)
+        outs.append((toks, ss.read_logits(0, 11)))
+        ss.close()
+    scale = outs[0][1].abs().max(dim=1).values
+    for toks, logits in outs[1:]:
+        same = 0
+        while same < 11 and toks[same] == outs[0][0][same]:
+            same += 1
+        assert same >= 1
+        assert ((logits - outs[0][1]).abs().max(dim=1).values / scale)[:same].max().item() < 2e-3
+    with pytest.raises(P.PpsdError):
+        P.Session(w, Wg, max_seq=345, prefill_chunk=100)
 
 
 def test_widest_supported_shape(P):
