@@ -754,6 +754,16 @@ void pf_launch_gemm(ppsd_ctx *x, PfGemm g, int n_cols) {
                        x->sA, x->cm, g);
 }
 
+// Attention of a chunk's queries (group sizes 1, 2, 4: what valid_config admits).
+void pf_launch_attn(ppsd_ctx *x, int l, int c0, int nv, const float *Q, float *AO) {
+  const ppsd_config &c = x->cfg;
+  const int G = c.n_heads / c.n_kv_heads, qp = kPfBM / G;
+  const dim3 grid(c.n_kv_heads, (nv + qp - 1) / qp);
+  if (G == 1) hipLaunchKernelGGL((k_pf_flash<1>), grid, dim3(kPfBlock), 0, x->sA, x->cm, l, c0, nv, Q, AO);
+  else if (G == 2) hipLaunchKernelGGL((k_pf_flash<2>), grid, dim3(kPfBlock), 0, x->sA, x->cm, l, c0, nv, Q, AO);
+  else hipLaunchKernelGGL((k_pf_flash<4>), grid, dim3(kPfBlock), 0, x->sA, x->cm, l, c0, nv, Q, AO);
+}
+
 int prefill_mfma(ppsd_ctx *x, int n_prompt) {
   const ppsd_config &c = x->cfg;
   const int d = c.d_model, f = c.d_ffn, nq = c.n_heads * c.head_dim;
@@ -772,10 +782,7 @@ int prefill_mfma(ppsd_ctx *x, int n_prompt) {
       hipLaunchKernelGGL(k_pf_split, sgrid, dim3(kPfBlock), 0, x->sA, (const float *)X, d, nv, (const float *)x->attn_norm[l], c.rms_eps, Ah, Al);
       g.W = (const bf16_t *)x->wqkv[l]; g.K = d;
       pf_launch_gemm<kPfQkv>(x, g, qkv_cols);
-      const dim3 agrid(c.n_kv_heads, nv);
-      if (G == 1) hipLaunchKernelGGL((k_pf_attn<1>), agrid, dim3(kPfBlock), 0, x->sA, x->cm, l, c0, (const float *)Q, AO);
-      else if (G == 2) hipLaunchKernelGGL((k_pf_attn<2>), agrid, dim3(kPfBlock), 0, x->sA, x->cm, l, c0, (const float *)Q, AO);
-      else hipLaunchKernelGGL((k_pf_attn<4>), agrid, dim3(kPfBlock), 0, x->sA, x->cm, l, c0, (const float *)Q, AO);
+      pf_launch_attn(x, l, c0, nv, Q, AO);
       hipLaunchKernelGGL(k_pf_split, sgrid, dim3(kPfBlock), 0, x->sA, (const float *)AO, nq, nv, (const float *)nullptr, 0.0f, Ah, Al);
       g.W = (const bf16_t *)x->wo[l]; g.K = nq;
       pf_launch_gemm<kPfResid>(x, g, d);

@@ -6,8 +6,8 @@
 // Precision: weights enter at their stored bf16 values; the fp32 activations are split, once per
 // projection input, into a bf16 high part and a bf16 low part (a = hi + lo up to 2^-17 relative)
 // and both parts are multiplied, so the products carry fp32-grade activations like the decode
-// path's FMA chains, and the accumulators are fp32.  Attention over the chunk's queries reuses
-// attn_unit.
+// path's FMA chains, and the accumulators are fp32.  Attention over the chunk's queries is a
+// flash-style MFMA kernel of its own (k_pf_flash).
 //
 // The GEMM: 128 x 128 output tile per workgroup, K step 32, 4 waves x (32 positions x 128
 // features).  LDS holds two stages of (A high, A low, W) tiles, rows padded to 80 bytes so that the
@@ -74,9 +74,23 @@ struct PfGemm {
   bf16_t *Mh, *Ml;       // kPfSwiglu: [chunk][f], high and low parts
 };
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+// Two floats to packed bf16, round to nearest even (one v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t pack_bf16x2(float a, float b) {
+  const f32x2_t v = {a, b};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+// (a, b) = hi + lo with both parts bf16; returns the packed pairs.
+__device__ __forceinline__ void split_bf16x2(float a, float b, uint32_t &hi, uint32_t &lo) {
+  hi = pack_bf16x2(a, b);
+  lo = pack_bf16x2(a - __uint_as_float(hi << 16), b - __uint_as_float(hi & 0xffff0000u));
+}
 __device__ __forceinline__ void split_bf16(float v, bf16_t &hi, bf16_t &lo) {
-  hi = float_to_bf16_rne(v);
-  lo = float_to_bf16_rne(v - Pack<bf16_t>::to_float(hi));
+  uint32_t h, l;
+  split_bf16x2(v, 0.f, h, l);
+  hi = (bf16_t)h; lo = (bf16_t)l;
 }
 
 // hi/lo[p][:] = split(src[p][:] * (gain ? gain[:] / sqrt(mean(src[p]^2) + eps) : 1)); one wave per position.
@@ -102,10 +116,11 @@ __global__ __launch_bounds__(kPfBlock) void k_pf_split(const float *src, int K, 
       const float4 gg = *(const float4 *)(gain + i);
       v.x *= rs * gg.x; v.y *= rs * gg.y; v.z *= rs * gg.z; v.w *= rs * gg.w;
     }
-    bf16_t h[4], l[4];
-    split_bf16(v.x, h[0], l[0]); split_bf16(v.y, h[1], l[1]); split_bf16(v.z, h[2], l[2]); split_bf16(v.w, h[3], l[3]);
-    *(uint2 *)(hi + (size_t)p * K + i) = make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16));
-    *(uint2 *)(lo + (size_t)p * K + i) = make_uint2((uint32_t)l[0] | ((uint32_t)l[1] << 16), (uint32_t)l[2] | ((uint32_t)l[3] << 16));
+    uint2 h, l;
+    split_bf16x2(v.x, v.y, h.x, l.x);
+    split_bf16x2(v.z, v.w, h.y, l.y);
+    *(uint2 *)(hi + (size_t)p * K + i) = h;
+    *(uint2 *)(lo + (size_t)p * K + i) = l;
   }
 }
 
@@ -282,17 +297,181 @@ __global__ __launch_bounds__(kPfBlock) void k_pf_reduce(Common c, PfGemm g) {
   pf_epilogue<EPI>(c, g, tile_n, p, col, v);
 }
 
-// Attention of the chunk's queries: one workgroup per (KV head, query position), keys 0..position.
+// Attention of the chunk's queries on the matrix cores (causal, online softmax over tiles of 32 keys).
+// A workgroup takes one KV head and 128 query rows that share it: G query heads x 128/G consecutive
+// positions, 32 rows per wave.  Per key tile a wave forms S^T = K Q^T (keys as MFMA rows, its 32 queries as
+// columns), so a lane owns one query and 16 of the tile's 32 keys: maximum and sum are in-lane plus one
+// exchange with lane + 32, the rescaling factor is a per-lane scalar, and the probabilities leave the
+// accumulator already in the layout of the next MFMA's B operand.  O^T += V^T P^T then wants, per lane,
+// 8 keys of one feature: the V tile is written to LDS transposed, keys in the order the accumulator
+// holds them (bits 2 and 3 of the key index swapped).  K and V are stored bf16 and enter exactly; the fp32
+// queries (pre-scaled by 1/sqrt(hd)) and the probabilities are split into bf16 high + low parts and both
+// are multiplied, as in the GEMMs.  LDS holds two stages of (K, V^T); the next tiles travel in registers.
+constexpr int kFaKeys = 32;
+constexpr int kFaKPitch = 128 + 8;       // K tile row pitch in bf16 elements (272 bytes)
+constexpr int kFaVPitch = kFaKeys + 8;   // V^T tile row pitch (80 bytes)
+
+struct FaRegs { uint4 k0, k1, v0, v1; };
+
+__device__ __forceinline__ int fa_key_column(int key) { return (key & ~12) | ((key & 4) << 1) | ((key & 8) >> 1); }
+
+__device__ __forceinline__ void fa_split8(const float (&x)[8], bf16x8_t &hi, bf16x8_t &lo) {
+  uint4 h, l;
+  split_bf16x2(x[0], x[1], h.x, l.x); split_bf16x2(x[2], x[3], h.y, l.y);
+  split_bf16x2(x[4], x[5], h.z, l.z); split_bf16x2(x[6], x[7], h.w, l.w);
+  hi = __builtin_bit_cast(bf16x8_t, h);
+  lo = __builtin_bit_cast(bf16x8_t, l);
+}
+
+// grid (n_kv, ceil(n_valid / (128 / G))); Q and AO are [chunk][n_h * 128] fp32.
 template <int G>
-__global__ __launch_bounds__(kPfBlock) void k_pf_attn(Common c, int layer, int c0, const float *Q, float *AO) {
-  constexpr int HD = 128;
-  constexpr int GPB = kPfBlock / (HD / Pack<bf16_t>::N);
-  __shared__ float merge[GPB * G * (HD + 2)];
-  __shared__ int s_last;
-  const int p = blockIdx.y;
-  const size_t nq = (size_t)c.dm.n_h * HD;
-  attn_unit<bf16_t, HD, G, kPfBlock>(c, c.page_table, layer, c0 + p, blockIdx.x, 0, 1, Q + p * nq, AO + p * nq, nullptr,
-                                     nullptr, merge, &s_last);
+__global__ __launch_bounds__(kPfBlock, 2) void k_pf_flash(Common c, int layer, int c0, int n_valid, const float *Q, float *AO) {
+  constexpr int HD = 128, WPH = 4 / G, QP = 32 * WPH;
+  __shared__ __attribute__((aligned(16))) bf16_t sK[2][kFaKeys * kFaKPitch];
+  __shared__ __attribute__((aligned(16))) bf16_t sVt[2][HD * kFaVPitch];
+  const Dims &m = c.dm;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, half = lane >> 5;
+  const int kvh = blockIdx.x;
+  const int q0 = ((int)gridDim.y - 1 - (int)blockIdx.y) * QP;        // long key ranges first
+  const int pw = q0 + 32 * (wave % WPH), head = kvh * G + wave / WPH;
+  const int my_p = pw + (lane & 31);
+  const int my_pos = c0 + min(my_p, n_valid - 1);
+  const size_t nq = (size_t)m.n_h * HD;
+  const int n_keys = c0 + min(q0 + QP, n_valid);                    // keys 0 .. last query position of the workgroup
+  const int n_tiles = (n_keys + kFaKeys - 1) / kFaKeys;
+
+  // the lane's query as B operands: feature block kb of 16, features 16*kb + 8*half + 0..7
+  bf16x8_t qh[HD / 16], ql[HD / 16];
+  {
+    const float *qr = Q + (size_t)min(my_p, n_valid - 1) * nq + (size_t)head * HD + 8 * half;
+    const float qs = m.qscale * 1.44269504088896341f;       // scores in units of log 2: exp becomes exp2
+#pragma unroll
+    for (int kb = 0; kb < HD / 16; ++kb) {
+      const float4 a = *(const float4 *)(qr + 16 * kb), b = *(const float4 *)(qr + 16 * kb + 4);
+      const float x[8] = {a.x * qs, a.y * qs, a.z * qs, a.w * qs, b.x * qs, b.y * qs, b.z * qs, b.w * qs};
+      fa_split8(x, qh[kb], ql[kb]);
+    }
+  }
+
+  // staging: K rows tid/16 and tid/16 + 16, 16-byte vector tid%16; V row tid%32, vectors tid/32 and tid/32 + 8
+  const int k_key = tid >> 4, k_vec = (tid & 15) * 8, v_key = tid & 31, v_vec = (tid >> 5) * 8;
+  auto gload = [&](int kt) {
+    FaRegs r;
+    const int base = kt * kFaKeys, last = n_keys - 1;
+    r.k0 = *(const uint4 *)(kv_row<bf16_t>(c, c.page_table, layer, min(base + k_key, last), kvh, 0) + k_vec);
+    r.k1 = *(const uint4 *)(kv_row<bf16_t>(c, c.page_table, layer, min(base + k_key + 16, last), kvh, 0) + k_vec);
+    const bf16_t *vr = kv_row<bf16_t>(c, c.page_table, layer, min(base + v_key, last), kvh, 1);
+    r.v0 = *(const uint4 *)(vr + v_vec);
+    r.v1 = *(const uint4 *)(vr + v_vec + 64);
+    return r;
+  };
+  const int v_col = fa_key_column(v_key);
+  auto lstore = [&](const FaRegs r, int st) {
+    *(uint4 *)(&sK[st][k_key * kFaKPitch + k_vec]) = r.k0;
+    *(uint4 *)(&sK[st][(k_key + 16) * kFaKPitch + k_vec]) = r.k1;
+    const uint32_t a[4] = {r.v0.x, r.v0.y, r.v0.z, r.v0.w}, b[4] = {r.v1.x, r.v1.y, r.v1.z, r.v1.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      sVt[st][(v_vec + 2 * e) * kFaVPitch + v_col] = (bf16_t)(a[e] & 0xffffu);
+      sVt[st][(v_vec + 2 * e + 1) * kFaVPitch + v_col] = (bf16_t)(a[e] >> 16);
+      sVt[st][(v_vec + 64 + 2 * e) * kFaVPitch + v_col] = (bf16_t)(b[e] & 0xffffu);
+      sVt[st][(v_vec + 64 + 2 * e + 1) * kFaVPitch + v_col] = (bf16_t)(b[e] >> 16);
+    }
+  };
+
+  f32x16_t o[HD / 32];                     // O^T: feature 32*dt + 8*(v/4) + 4*half + v%4 of the lane's query
+#pragma unroll
+  for (int dt = 0; dt < HD / 32; ++dt)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) o[dt][v] = 0.f;
+  float mx = -INFINITY, sum = 0.f;         // running maximum; this lane's share of the running sum
+
+  const int ka_at = (lane & 31) * kFaKPitch + 8 * half;     // K as A operand: key lane%32, 8 features
+  const int va_at = (lane & 31) * kFaVPitch + 8 * half;     // V^T as A operand: feature lane%32, 8 keys
+  auto compute = [&](int kt, int st) {
+    if (kt * kFaKeys > c0 + pw + 31) return;                 // every key of the tile lies behind the wave's queries
+    f32x16_t s;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < HD / 16; ++kb) {
+      const bf16x8_t ka = *(const bf16x8_t *)(&sK[st][ka_at + 16 * kb]);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qh[kb], s, 0, 0, 0);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, ql[kb], s, 0, 0, 0);
+    }
+    // s[v]: key kt*32 + 8*(v/4) + 4*half + v%4 against the lane's query, in units of log 2
+    if (kt * kFaKeys + kFaKeys - 1 > c0 + pw) {              // the tile reaches past the wave's first query: mask
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int key = kt * kFaKeys + 8 * (v >> 2) + 4 * half + (v & 3);
+        s[v] = key <= my_pos ? s[v] : -INFINITY;
+      }
+    }
+    float tmax = s[0];
+#pragma unroll
+    for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, s[v]);
+    tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+    const float mn = fmaxf(mx, tmax);
+    const float corr = __builtin_amdgcn_exp2f(mx - mn);
+    mx = mn;
+    float p[16], psum = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { p[v] = __builtin_amdgcn_exp2f(s[v] - mn); psum += p[v]; }
+    sum = sum * corr + psum;
+    if (__any(corr != 1.0f)) {                               // some query's maximum rose
+#pragma unroll
+      for (int dt = 0; dt < HD / 32; ++dt)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) o[dt][v] *= corr;
+    }
+    bf16x8_t ph[2], pl[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      const float x[8] = {p[8 * kb], p[8 * kb + 1], p[8 * kb + 2], p[8 * kb + 3], p[8 * kb + 4], p[8 * kb + 5], p[8 * kb + 6], p[8 * kb + 7]};
+      fa_split8(x, ph[kb], pl[kb]);
+    }
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+      bf16x8_t va[HD / 32];
+#pragma unroll
+      for (int dt = 0; dt < HD / 32; ++dt) va[dt] = *(const bf16x8_t *)(&sVt[st][va_at + dt * 32 * kFaVPitch + 16 * kb]);
+#pragma unroll
+      for (int dt = 0; dt < HD / 32; ++dt) o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[dt], ph[kb], o[dt], 0, 0, 0);
+#pragma unroll
+      for (int dt = 0; dt < HD / 32; ++dt) o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va[dt], pl[kb], o[dt], 0, 0, 0);
+    }
+  };
+
+  // as in the GEMM: stage kt % 2 holds tile kt, r0 / r1 carry the tiles behind it (indices clamped)
+  FaRegs r0 = gload(0), r1 = gload(min(1, n_tiles - 1));
+  lstore(r0, 0);
+  __syncthreads();
+  for (int kt = 0; kt + 2 <= n_tiles; kt += 2) {
+    r0 = gload(min(kt + 2, n_tiles - 1));
+    __builtin_amdgcn_sched_barrier(0);
+    compute(kt, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    lstore(r1, 1);
+    __syncthreads();
+    r1 = gload(min(kt + 3, n_tiles - 1));
+    __builtin_amdgcn_sched_barrier(0);
+    compute(kt + 1, 1);
+    __builtin_amdgcn_sched_barrier(0);
+    lstore(r0, 0);
+    __syncthreads();
+  }
+  if (n_tiles & 1) compute(n_tiles - 1, 0);
+
+  sum += __shfl_xor(sum, 32);
+  if (my_p < n_valid) {
+    const float inv = 1.0f / sum;
+    float *out = AO + (size_t)my_p * nq + (size_t)head * HD + 4 * half;
+#pragma unroll
+    for (int dt = 0; dt < HD / 32; ++dt)
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        *(float4 *)(out + 32 * dt + 8 * q) = make_float4(o[dt][4 * q] * inv, o[dt][4 * q + 1] * inv, o[dt][4 * q + 2] * inv, o[dt][4 * q + 3] * inv);
+  }
 }
 
 // The last prompt position's residual row becomes the LM head's input.
