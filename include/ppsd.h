@@ -133,8 +133,11 @@ typedef struct {
                               0xA0761D6478BD642F (64-bit wrapping), purpose = 0 draft, 1 acceptance,
                               2 replacement, 3 plain sampling: a pure function of the three, whatever the schedule */
   int32_t prefill_chunk;   /* positions the matrix-core prefill takes through the layers at a time: 0 = default
-                              (the whole prompt capacity max_seq, 2048 at most), else a multiple of 128 in
-                              128..2048.  Sizes the chunk buffers inside the workspace */
+                              (the whole prompt capacity max_seq, 4096 at most), else a multiple of 128 in
+                              128..4096.  Sizes the chunk buffers inside the workspace */
+  int32_t tune_prefill_tile; /* launch tuning of the matrix-core prefill GEMMs: 0 = choose per projection (256 x 256
+                              output tiles when they still fill the chip, else 128 x 128 with K split over
+                              several workgroups), 1 = always 128 x 128, 2 = always 256 x 256 */
 } ppsd_config;
 
 /* DEVICE pointers, BORROWED.  Per-layer entries are HOST arrays of n_layers DEVICE pointers

@@ -95,7 +95,8 @@ bool valid_config(const ppsd_config *c, const char **why) {
   REJECT(c->engine == PPSD_ENGINE_PERSISTENT && c->time_kernels, "time_kernels needs the per-operation engine");
   REJECT(c->prefill_loop != 0 && c->prefill_loop != 1, "prefill_loop must be 0 or 1");
   REJECT(c->prefill_chunk != 0 && (c->prefill_chunk < kPfBM || c->prefill_chunk > kPfChunkMax || c->prefill_chunk % kPfBM),
-         "prefill_chunk must be 0 or a multiple of 128 in 128..2048");
+         "prefill_chunk must be 0 or a multiple of 128 in 128..4096");
+  REJECT(c->tune_prefill_tile < 0 || c->tune_prefill_tile > 2, "tune_prefill_tile must be 0, 1 or 2");
   if (c->mode == PPSD_MODE_PIPELINE) {
     REJECT(c->engine != PPSD_ENGINE_STREAMS, "the full pipeline schedule runs on the per-operation engine only");
     REJECT(c->time_kernels, "time_kernels is not available with the full pipeline schedule");
@@ -163,7 +164,7 @@ Layout make_layout(const ppsd_config *c) {
   L.cand_counts = take(256);
   L.trace = take(8ull * kTraceSlots * kTracePhases);
   L.pf = pf_eligible(c);
-  // a chunk covers the whole prompt when max_seq allows, 2048 positions at most
+  // a chunk covers the whole prompt when max_seq allows, 4096 positions at most
   L.pf_chunk = !L.pf ? 0 : c->prefill_chunk ? c->prefill_chunk : std::min(kPfChunkMax, (c->max_seq + kPfBM - 1) / kPfBM * kPfBM);
   const size_t pc = (size_t)L.pf_chunk;
   const size_t wide = std::max((size_t)c->d_model, nq);
@@ -175,11 +176,12 @@ Layout make_layout(const ppsd_config *c) {
   L.pf_mh = take(2ull * pc * c->d_ffn);
   L.pf_ml = take(2ull * pc * c->d_ffn);
   size_t part = 0;       // the largest split-K partial-sum buffer any chunk length can ask for
+  const int tile = c->tune_prefill_tile ? c->tune_prefill_tile : -1;
   for (int nv = kPfBM; nv <= L.pf_chunk; nv += kPfBM) {
-    part = std::max(part, pf_partial_floats(pf_plan(nv, (int)(nq + 2ull * c->n_kv_heads * c->head_dim), c->d_model)));
-    part = std::max(part, pf_partial_floats(pf_plan(nv, c->d_model, (int)nq)));
-    part = std::max(part, pf_partial_floats(pf_plan(nv, 2 * c->d_ffn, c->d_model)));
-    part = std::max(part, pf_partial_floats(pf_plan(nv, c->d_model, c->d_ffn)));
+    part = std::max(part, pf_partial_floats(pf_plan(nv, (int)(nq + 2ull * c->n_kv_heads * c->head_dim), c->d_model, tile)));
+    part = std::max(part, pf_partial_floats(pf_plan(nv, c->d_model, (int)nq, tile)));
+    part = std::max(part, pf_partial_floats(pf_plan(nv, 2 * c->d_ffn, c->d_model, tile)));
+    part = std::max(part, pf_partial_floats(pf_plan(nv, c->d_model, c->d_ffn, tile)));
   }
   L.pf_part = take(4ull * part);
   const size_t nb = c->mode == PPSD_MODE_EESD ? kMaxBatch : 0;
@@ -740,18 +742,10 @@ int mega_setup(ppsd_ctx *x) {
 }
 
 // ---------------------------------------------------------------- matrix-core prefill
-// One projection of a chunk: the GEMM over g.n_valid positions and n_cols output columns, then, when K
-// was split, the kernel that adds the partial tiles and runs the epilogue.
 template <int EPI>
 void pf_launch_gemm(ppsd_ctx *x, PfGemm g, int n_cols) {
-  const PfPlan pl = pf_plan(g.n_valid, n_cols, g.K);
-  g.tiles_m = pl.tiles_m; g.tiles_n = pl.tiles_n; g.splits = pl.splits;
   g.part = at<float>(x, x->lay.pf_part);
-  const int n_groups = (pl.tiles_n + kPfXcds - 1) / kPfXcds;
-  hipLaunchKernelGGL((k_pf_gemm<EPI>), dim3(kPfXcds * pl.tiles_m * pl.splits * n_groups), dim3(kPfBlock), 0, x->sA, x->cm, g);
-  if (pl.splits > 1)
-    hipLaunchKernelGGL((k_pf_reduce<EPI>), dim3(pl.tiles_n, (g.n_valid + kPfBlock / 32 - 1) / (kPfBlock / 32)), dim3(kPfBlock), 0,
-                       x->sA, x->cm, g);
+  pf_launch<EPI>(x->sA, x->cm, g, pf_plan(g.n_valid, n_cols, g.K, x->cfg.tune_prefill_tile ? x->cfg.tune_prefill_tile : -1));
 }
 
 // Attention of a chunk's queries (group sizes 1, 2, 4: what valid_config admits).
@@ -917,6 +911,7 @@ int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *b, ppsd_ctx **
   HIP_TRY_X(hipEventCreateWithFlags(&x->ev_fork, hipEventDisableTiming));
   HIP_TRY_X(hipEventCreateWithFlags(&x->ev_join, hipEventDisableTiming));
   x->sx[0] = x->sA; x->sx[1] = x->sB;
+  if (x->lay.pf) HIP_TRY_X(pf_prepare());
   if (cfg->mode == PPSD_MODE_EESD) {
     x->gamma = cfg->eesd_gamma ? cfg->eesd_gamma : kDefaultGamma;
     hipError_t e = hipSuccess;

@@ -9,12 +9,16 @@
 // path's FMA chains, and the accumulators are fp32.  Attention over the chunk's queries is a
 // flash-style MFMA kernel of its own (k_pf_flash).
 //
-// The GEMM: 128 x 128 output tile per workgroup, K step 32, 4 waves x (32 positions x 128
-// features).  LDS holds two stages of (A high, A low, W) tiles, rows padded to 80 bytes so that the
-// 16-byte operand reads of 16 consecutive rows fall on distinct banks; the tiles two K steps ahead
-// travel in registers while the current ones are multiplied, one barrier per K step.  Few output
-// tiles (short prompts) are split along K over several workgroups, whose partial tiles a second
-// kernel adds in a fixed order before the epilogue, so results do not depend on timing.
+// The GEMM comes in two tile shapes.  Small: 128 x 128 outputs per workgroup, 4 waves x (32 positions x
+// 128 features), two workgroups per compute unit.  Big: 256 x 256 outputs, 8 waves x (64 positions x
+// 128 features), one workgroup per compute unit; it moves half the operand bytes per MFMA through
+// L2 and LDS and is taken when it still fills the chip.  K step 32.  LDS holds two stages of
+// (A high, A low, W) tiles; a row is 64 bytes and its four 16-byte vectors are stored at position
+// v ^ ((row / 4) % 4), which makes both the staging stores (4 rows x 4 vectors per 16 lanes) and the
+// MFMA operand loads (16 rows, one vector) hit every bank once.  The tiles two K steps ahead travel
+// in registers while the current ones are multiplied, one barrier per K step.  Few output tiles
+// (short prompts) are split along K over several workgroups, whose partial tiles a second kernel
+// adds in a fixed order before the epilogue, so results do not depend on timing.
 // Workgroup ids map to tiles so that all tiles of one weight row block run on one XCD (ids go
 // round-robin over the 8 XCDs): each weight tile is fetched from HBM into one L2 only.
 #pragma once
@@ -23,14 +27,15 @@
 
 namespace ppsd {
 
-constexpr int kPfChunkMax = 2048;   // positions per prefill chunk, at most
-constexpr int kPfBM = 128;          // positions per GEMM tile (4 waves x 32)
-constexpr int kPfBN = 128;          // output features per GEMM tile (4 MFMA tiles of 32)
+constexpr int kPfChunkMax = 4096;   // positions per prefill chunk, at most
+constexpr int kPfBM = 128;          // positions per unit tile (4 waves x 32)
+constexpr int kPfBN = 128;          // output features per unit tile (4 MFMA tiles of 32)
 constexpr int kPfBK = 32;           // K step (2 MFMA k-blocks of 16)
-constexpr int kPfPitch = kPfBK + 8; // LDS row pitch in bf16 elements (80 bytes)
-constexpr int kPfBlock = 256;
+constexpr int kPfBlock = 256;       // threads per unit tile
 constexpr int kPfXcds = 8;
-constexpr int kPfTargetWgs = 512;   // K is split until about this many workgroups exist
+constexpr int kPfTargetWgs = 512;   // small tiles: K is split until about this many workgroups exist
+constexpr int kPfBigTargetWgs = 256;// big tiles: one per compute unit
+constexpr int kPfBigMinTiles = 96;  // big tiles are taken from this many of them on
 constexpr int kPfMaxSplit = 8;
 constexpr int kPfMinSteps = 4;      // K steps per split, at least
 
@@ -39,16 +44,21 @@ typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 enum PfEpilogue : int { kPfQkv = 0, kPfResid = 1, kPfSwiglu = 2 };
 
-struct PfPlan { int tiles_m, tiles_n, splits; };
+// tiles_m, tiles_n count unit tiles (128 x 128); big = 1 or 2 is the workgroup tile's edge in unit tiles.
+struct PfPlan { int tiles_m, tiles_n, splits, big; };
 
 // How a [n_valid x n_cols] output with inner length K is cut into workgroups.
-inline PfPlan pf_plan(int n_valid, int n_cols, int K) {
+// force_big: -1 = choose, 1 / 2 = that tile edge.
+inline PfPlan pf_plan(int n_valid, int n_cols, int K, int force_big = -1) {
   PfPlan p;
   p.tiles_m = (n_valid + kPfBM - 1) / kPfBM;
   p.tiles_n = n_cols / kPfBN;
-  const int tiles = p.tiles_m * p.tiles_n, steps = K / kPfBK;
+  const int big_tiles = ((p.tiles_m + 1) / 2) * ((p.tiles_n + 1) / 2);
+  p.big = force_big > 0 ? force_big : (p.tiles_m >= 2 && big_tiles >= kPfBigMinTiles) ? 2 : 1;
+  const int tiles = p.big == 2 ? big_tiles : p.tiles_m * p.tiles_n;
+  const int target = p.big == 2 ? kPfBigTargetWgs : kPfTargetWgs, steps = K / kPfBK;
   int s = 1;
-  if (tiles < kPfTargetWgs) s = (kPfTargetWgs + tiles - 1) / tiles;
+  if (tiles < target) s = p.big == 2 ? (target + tiles / 2) / tiles : (target + tiles - 1) / tiles;
   if (s > kPfMaxSplit) s = kPfMaxSplit;
   if (s > steps / kPfMinSteps) s = steps / kPfMinSteps;
   p.splits = s < 1 ? 1 : s;
@@ -66,7 +76,7 @@ struct PfGemm {
   int n_valid;           // positions in this chunk
   int c0;                // first position of the chunk
   int layer;
-  int tiles_m, tiles_n, splits;
+  int tiles_m, tiles_n, splits;   // unit tiles of the output, K ranges
   float *part;           // [splits][tiles_m*128][tiles_n*128] partial sums, when splits > 1
   // epilogue targets
   float *X;              // kPfResid: X[p][n] += C (row pitch d)
@@ -177,31 +187,40 @@ __device__ __forceinline__ void pf_epilogue(const Common &c, const PfGemm &g, in
 
 struct PfRegs { uint4 ah0, ah1, al0, al1, w0, w1; };   // one K step of the three tiles, this thread's share
 
-// One 128 x 128 output tile (or one K range of it) per workgroup; 1-D grid of
-// 8 * tiles_m * splits * ceil(tiles_n / 8) workgroups.
-template <int EPI>
-__global__ __launch_bounds__(kPfBlock) void k_pf_gemm(Common c, PfGemm g) {
-  __shared__ __attribute__((aligned(16))) bf16_t lds[2][3][kPfBM * kPfPitch];
+// Element offset of the 16-byte vector v (8 consecutive k) of tile row r inside one LDS plane.
+__device__ __forceinline__ int pf_lds_at(int r, int v) { return (r * 4 + (v ^ ((r >> 2) & 3))) * 8; }
+
+// One BIG*128 x BIG*128 output tile (or one K range of it) per workgroup of BIG*256 threads; 1-D grid of
+// 8 * ceil(tiles_m / BIG) * splits * ceil(ceil(tiles_n / BIG) / 8) workgroups; BIG * 48 KB of dynamic LDS.
+template <int EPI, int BIG>
+__global__ __launch_bounds__(kPfBlock *BIG) void k_pf_gemm(Common c, PfGemm g) {
+  constexpr int ROWS = 128 * BIG, PLANE = ROWS * kPfBK, STAGE = 3 * PLANE, HALF = ROWS / 2;
+  extern __shared__ __attribute__((aligned(16))) bf16_t pf_lds[];   // [2 stages][A high, A low, W][ROWS][32]
   const Dims &m = c.dm;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, wm = wave & 3, wn = wave >> 2;
+  const int gm = (g.tiles_m + BIG - 1) / BIG, gn = (g.tiles_n + BIG - 1) / BIG;
   // id -> (XCD, then position tile fastest, then K range, then weight row block)
   const int xcd = blockIdx.x % kPfXcds, local = blockIdx.x / kPfXcds;
-  const int tile_m = local % g.tiles_m, rest = local / g.tiles_m;
+  const int tile_m = local % gm, rest = local / gm;
   const int split = rest % g.splits, tile_n = (rest / g.splits) * kPfXcds + xcd;
-  if (tile_n >= g.tiles_n) return;
+  if (tile_n >= gn) return;
   const int K = g.K, steps = K / kPfBK;
   const int step0 = (int)((long long)steps * split / g.splits), nk = (int)((long long)steps * (split + 1) / g.splits) - step0;
 
-  // staging: thread t moves, per tile, the 16-byte vector (t % 4) of rows t/4 and t/4 + 64
-  const int srow = tid >> 2, svec = (tid & 3) * 8;
-  const int prow0 = min(tile_m * kPfBM + srow, g.n_valid - 1), prow1 = min(tile_m * kPfBM + srow + 64, g.n_valid - 1);   // clamped
-  int wrow0, wrow1;
-  if (EPI == kPfSwiglu) { wrow0 = tile_n * 64 + srow; wrow1 = m.f + tile_n * 64 + srow; }
-  else { wrow0 = tile_n * kPfBN + srow; wrow1 = wrow0 + 64; }
-  const size_t koff = (size_t)step0 * kPfBK + svec;
+  // staging: thread t moves, per tile, the 16-byte vector (t % 4) of rows t/4 and t/4 + ROWS/2
+  const int srow = tid >> 2, svec = tid & 3;
+  const int prow0 = min(tile_m * ROWS + srow, g.n_valid - 1), prow1 = min(tile_m * ROWS + srow + HALF, g.n_valid - 1);   // clamped
+  auto weight_row = [&](int r) {       // tile row r -> row of W; a unit tile beyond the last one repeats the first
+    int tn = tile_n * BIG + r / 128;
+    if (tn >= g.tiles_n) tn = tile_n * BIG;
+    const int rr = r % 128;
+    if (EPI == kPfSwiglu) return rr < 64 ? tn * 64 + rr : m.f + tn * 64 + (rr - 64);
+    return tn * kPfBN + rr;
+  };
+  const size_t koff = (size_t)step0 * kPfBK + svec * 8;
   const bf16_t *ah_src0 = g.Ah + (size_t)prow0 * K + koff, *ah_src1 = g.Ah + (size_t)prow1 * K + koff;
   const bf16_t *al_src0 = g.Al + (size_t)prow0 * K + koff, *al_src1 = g.Al + (size_t)prow1 * K + koff;
-  const bf16_t *w_src0 = g.W + (size_t)wrow0 * K + koff, *w_src1 = g.W + (size_t)wrow1 * K + koff;
+  const bf16_t *w_src0 = g.W + (size_t)weight_row(srow) * K + koff, *w_src1 = g.W + (size_t)weight_row(srow + HALF) * K + koff;
   auto gload = [&](int kt) {
     const int off = kt * kPfBK;
     PfRegs r;
@@ -210,44 +229,57 @@ __global__ __launch_bounds__(kPfBlock) void k_pf_gemm(Common c, PfGemm g) {
     r.w0 = *(const uint4 *)(w_src0 + off); r.w1 = *(const uint4 *)(w_src1 + off);
     return r;
   };
-  const int s_at0 = srow * kPfPitch + svec, s_at1 = (srow + 64) * kPfPitch + svec;
+  const int s_at0 = pf_lds_at(srow, svec), s_at1 = pf_lds_at(srow + HALF, svec);
   auto lstore = [&](const PfRegs r, int st) {
-    *(uint4 *)(&lds[st][0][s_at0]) = r.ah0; *(uint4 *)(&lds[st][0][s_at1]) = r.ah1;
-    *(uint4 *)(&lds[st][1][s_at0]) = r.al0; *(uint4 *)(&lds[st][1][s_at1]) = r.al1;
-    *(uint4 *)(&lds[st][2][s_at0]) = r.w0; *(uint4 *)(&lds[st][2][s_at1]) = r.w1;
+    bf16_t *base = pf_lds + st * STAGE;
+    *(uint4 *)(base + s_at0) = r.ah0; *(uint4 *)(base + s_at1) = r.ah1;
+    *(uint4 *)(base + PLANE + s_at0) = r.al0; *(uint4 *)(base + PLANE + s_at1) = r.al1;
+    *(uint4 *)(base + 2 * PLANE + s_at0) = r.w0; *(uint4 *)(base + 2 * PLANE + s_at1) = r.w1;
   };
 
-  f32x16_t acc[4];
+  f32x16_t acc[BIG][4];
 #pragma unroll
-  for (int nt = 0; nt < 4; ++nt)
+  for (int j = 0; j < BIG; ++j)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[nt][v] = 0.f;
+    for (int nt = 0; nt < 4; ++nt)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[j][nt][v] = 0.f;
 
-  // MFMA operand of a lane: row lane % 32 of its 32-row block, 8 consecutive k at 8 * (lane / 32)
-  const int a_at = (wave * 32 + (lane & 31)) * kPfPitch + 8 * (lane >> 5);
-  const int b_at = (lane & 31) * kPfPitch + 8 * (lane >> 5);
+  // MFMA operand of a lane: row lane % 32 of a 32-row block, 8 consecutive k at 8 * (lane / 32).  Block
+  // bases are multiples of 32, so the row's swizzle term depends on the lane only.
+  const int half = lane >> 5, swz = (lane >> 2) & 3;
+  const int a_row = (wm * BIG * 32 + (lane & 31)) * kPfBK, b_row = (wn * 128 + (lane & 31)) * kPfBK;
   auto compute = [&](int st) {
+    const bf16_t *base = pf_lds + st * STAGE;
 #pragma unroll
     for (int kk = 0; kk < kPfBK / 16; ++kk) {
-      const bf16x8_t ah = *(const bf16x8_t *)(&lds[st][0][a_at + kk * 16]);
-      const bf16x8_t al = *(const bf16x8_t *)(&lds[st][1][a_at + kk * 16]);
-      bf16x8_t b[4];
+      const int kv = ((kk * 2 + half) ^ swz) * 8;
+      bf16x8_t ah[BIG], al[BIG], b[4];
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt) b[nt] = *(const bf16x8_t *)(&lds[st][2][b_at + nt * 32 * kPfPitch + kk * 16]);
+      for (int j = 0; j < BIG; ++j) {
+        ah[j] = *(const bf16x8_t *)(base + a_row + j * 32 * kPfBK + kv);
+        al[j] = *(const bf16x8_t *)(base + PLANE + a_row + j * 32 * kPfBK + kv);
+      }
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt) acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, b[nt], acc[nt], 0, 0, 0);
+      for (int nt = 0; nt < 4; ++nt) b[nt] = *(const bf16x8_t *)(base + 2 * PLANE + b_row + nt * 32 * kPfBK + kv);
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt) acc[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, b[nt], acc[nt], 0, 0, 0);
+      for (int j = 0; j < BIG; ++j)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) acc[j][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[j], b[nt], acc[j][nt], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < BIG; ++j)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) acc[j][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[j], b[nt], acc[j][nt], 0, 0, 0);
     }
   };
 
   // stage s holds K step kt when kt % 2 == s; r0/r1 carry the steps after it (indices clamped to
-  // the last step: the surplus loads and stores at the end touch valid memory and are never read)
+  // the last step: the surplus loads and stores at the end touch valid memory and are never read).
+  // The scheduling fences keep the order  issue loads -> multiply -> store the older loads,  which is
+  // what leaves a load two K steps of time to arrive.
   PfRegs r0 = gload(0), r1 = gload(min(1, nk - 1));
   lstore(r0, 0);
   __syncthreads();
-  // the scheduling fences keep the order  issue loads -> multiply -> store the older loads,  which is
-  // what leaves a load two K steps of time to arrive
   for (int kt = 0; kt + 2 <= nk; kt += 2) {
     r0 = gload(min(kt + 2, nk - 1));
     __builtin_amdgcn_sched_barrier(0);
@@ -264,22 +296,27 @@ __global__ __launch_bounds__(kPfBlock) void k_pf_gemm(Common c, PfGemm g) {
   }
   if (nk & 1) compute(0);
 
-  // acc[nt][v]: tile row wave*32 + 8*(v/4) + 4*(lane/32) + v%4, tile column nt*32 + lane%32
+  // acc[j][nt][v]: row wm*BIG*32 + j*32 + 8*(v/4) + 4*(lane/32) + v%4 of the workgroup tile, column nt*32 + lane%32
+  // of unit tile tn
+  const int tn = tile_n * BIG + wn;
+  if (tn >= g.tiles_n) return;
   const int col = lane & 31;
   const size_t ncols = (size_t)g.tiles_n * kPfBN, mpad = (size_t)g.tiles_m * kPfBM;
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const int p = tile_m * kPfBM + wave * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-    if (p >= g.n_valid) continue;
-    if (g.splits > 1) {
-      float *dst = g.part + ((size_t)split * mpad + p) * ncols + (size_t)tile_n * kPfBN + col;
+  for (int j = 0; j < BIG; ++j)
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt) dst[nt * 32] = acc[nt][v];
-    } else {
-      const float vals[4] = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
-      pf_epilogue<EPI>(c, g, tile_n, p, col, vals);
+    for (int v = 0; v < 16; ++v) {
+      const int p = tile_m * ROWS + wm * BIG * 32 + j * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+      if (p >= g.n_valid) continue;
+      if (g.splits > 1) {
+        float *dst = g.part + ((size_t)split * mpad + p) * ncols + (size_t)tn * kPfBN + col;
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) dst[nt * 32] = acc[j][nt][v];
+      } else {
+        const float vals[4] = {acc[j][0][v], acc[j][1][v], acc[j][2][v], acc[j][3][v]};
+        pf_epilogue<EPI>(c, g, tn, p, col, vals);
+      }
     }
-  }
 }
 
 // Adds the K ranges' partial tiles in range order and runs the epilogue; grid (tiles_n, ceil(n_valid / 8)).
@@ -295,6 +332,34 @@ __global__ __launch_bounds__(kPfBlock) void k_pf_reduce(Common c, PfGemm g) {
     for (int nt = 0; nt < 4; ++nt) v[nt] += src[nt * 32];
   }
   pf_epilogue<EPI>(c, g, tile_n, p, col, v);
+}
+
+// Dynamic LDS of the big-tile GEMM exceeds the default limit: raise it once per process and device.
+template <int EPI>
+inline hipError_t pf_allow_big_lds() {
+  return hipFuncSetAttribute((const void *)k_pf_gemm<EPI, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 3 * 256 * kPfBK * 2);
+}
+inline hipError_t pf_prepare() {
+  hipError_t e = pf_allow_big_lds<kPfQkv>();
+  if (e == hipSuccess) e = pf_allow_big_lds<kPfResid>();
+  if (e == hipSuccess) e = pf_allow_big_lds<kPfSwiglu>();
+  return e;
+}
+
+// One projection of a chunk: the GEMM over g.n_valid positions and n_cols output columns, then, when K
+// was split, the kernel that adds the partial tiles and runs the epilogue.  g.part must hold
+// pf_partial_floats(pl) floats.
+template <int EPI>
+inline void pf_launch(hipStream_t stream, const Common &c, PfGemm g, const PfPlan &pl) {
+  g.tiles_m = pl.tiles_m; g.tiles_n = pl.tiles_n; g.splits = pl.splits;
+  const int gm = (pl.tiles_m + pl.big - 1) / pl.big, gn = (pl.tiles_n + pl.big - 1) / pl.big;
+  const dim3 grid(kPfXcds * gm * pl.splits * ((gn + kPfXcds - 1) / kPfXcds));
+  const size_t lds = (size_t)pl.big * 2 * 3 * 128 * kPfBK * 2;
+  if (pl.big == 2) hipLaunchKernelGGL((k_pf_gemm<EPI, 2>), grid, dim3(2 * kPfBlock), lds, stream, c, g);
+  else hipLaunchKernelGGL((k_pf_gemm<EPI, 1>), grid, dim3(kPfBlock), lds, stream, c, g);
+  if (pl.splits > 1)
+    hipLaunchKernelGGL((k_pf_reduce<EPI>), dim3(pl.tiles_n, (g.n_valid + kPfBlock / 32 - 1) / (kPfBlock / 32)), dim3(kPfBlock), 0,
+                       stream, c, g);
 }
 
 // Attention of the chunk's queries on the matrix cores (causal, online softmax over tiles of 32 keys).

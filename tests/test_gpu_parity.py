@@ -332,10 +332,14 @@ PF_SHAPES = {
 }
 
 
-@pytest.mark.parametrize("shape,prompt_len,chunk", [("pf", 200, 0), ("pf", 700, 512), ("pf", 700, 0), ("pf128", 300, 0),
-                                                    ("pf128", 300, 128)],
-                         ids=["one_chunk_ragged", "two_chunks", "six_position_tiles", "unsplit_k", "unsplit_k_three_chunks"])
-def test_matrix_core_prefill_matches_oracle_and_looped_prefill(P, shape, prompt_len, chunk):
+@pytest.mark.parametrize("shape,prompt_len,chunk,tile", [
+    ("pf", 200, 0, 0), ("pf", 700, 512, 0), ("pf", 700, 0, 0), ("pf128", 300, 0, 0), ("pf128", 300, 128, 0),
+    # 256 x 256 tiles forced onto small shapes: odd counts of 128-wide column tiles (11 for gate/up, 1 for
+    # d_model 128: the second half of the last workgroup tile is empty), odd counts of position tiles
+    ("pf", 700, 0, 2), ("pf", 300, 256, 2), ("pf128", 300, 0, 2), ("pf", 700, 0, 1)],
+    ids=["one_chunk_ragged", "two_chunks", "six_position_tiles", "unsplit_k", "unsplit_k_three_chunks",
+         "big_tiles", "big_tiles_two_chunks", "big_tiles_unsplit_k", "small_tiles"])
+def test_matrix_core_prefill_matches_oracle_and_looped_prefill(P, shape, prompt_len, chunk, tile):
     """Prefill through the MFMA GEMMs (one or several chunks of positions) against the oracle and against
     the decode kernels looped over the prompt: same first token and decode stream under the bf16 protocol,
     and logits of the two prefill paths within 2e-3 of each other (both carry fp32-grade activations;
@@ -348,7 +352,7 @@ def test_matrix_core_prefill_matches_oracle_and_looped_prefill(P, shape, prompt_
     runs = []
     for loop in (False, True):
         ss = P.Session(w, Wg, max_seq=prompt_len + 12, mode=P.MODE_OVERLAP, debug_logits=11, prefill_loop=loop,
-                       prefill_chunk=chunk)
+                       prefill_chunk=chunk, tune_prefill_tile=tile)
         toks = [ss.ppsd_prefill(prompt)] + ss.ppsd_decode(10)
         logits = ss.read_logits(0, 11)
         ss.close()
