@@ -15,8 +15,8 @@
 // L2 and LDS and is taken when it still fills the chip.  K step 32.  LDS holds two stages of
 // (A high, A low, W) tiles; a row is 64 bytes and its four 16-byte vectors are stored at position
 // v ^ ((row / 4) % 4), which makes both the staging stores (4 rows x 4 vectors per 16 lanes) and the
-// MFMA operand loads (16 rows, one vector) hit every bank once.  The tiles two K steps ahead travel
-// in registers while the current ones are multiplied, one barrier per K step.  Few output tiles
+// MFMA operand loads (16 rows, one vector) hit every bank once.  The next tiles travel in registers
+// while the current one is multiplied, one barrier per K step.  Few output tiles
 // (short prompts) are split along K over several workgroups, whose partial tiles a second kernel
 // adds in a fixed order before the epilogue, so results do not depend on timing.
 // Workgroup ids map to tiles so that all tiles of one weight row block run on one XCD (ids go
@@ -251,48 +251,77 @@ __global__ __launch_bounds__(kPfBlock *BIG) void k_pf_gemm(Common c, PfGemm g) {
   const int a_row = (wm * BIG * 32 + (lane & 31)) * kPfBK, b_row = (wn * 128 + (lane & 31)) * kPfBK;
   auto compute = [&](int st) {
     const bf16_t *base = pf_lds + st * STAGE;
+    // every operand of the K step is requested before the first MFMA: the reads return in order, so
+    // the matrix cores start after the first few and the rest arrive underneath them
+    bf16x8_t ah[2][BIG], al[2][BIG], b[2][4];
 #pragma unroll
-    for (int kk = 0; kk < kPfBK / 16; ++kk) {
+    for (int kk = 0; kk < 2; ++kk) {
       const int kv = ((kk * 2 + half) ^ swz) * 8;
-      bf16x8_t ah[BIG], al[BIG], b[4];
 #pragma unroll
-      for (int j = 0; j < BIG; ++j) {
-        ah[j] = *(const bf16x8_t *)(base + a_row + j * 32 * kPfBK + kv);
-        al[j] = *(const bf16x8_t *)(base + PLANE + a_row + j * 32 * kPfBK + kv);
-      }
+      for (int j = 0; j < BIG; ++j) ah[kk][j] = *(const bf16x8_t *)(base + a_row + j * 32 * kPfBK + kv);
 #pragma unroll
-      for (int nt = 0; nt < 4; ++nt) b[nt] = *(const bf16x8_t *)(base + 2 * PLANE + b_row + nt * 32 * kPfBK + kv);
+      for (int nt = 0; nt < 4; ++nt) b[kk][nt] = *(const bf16x8_t *)(base + 2 * PLANE + b_row + nt * 32 * kPfBK + kv);
 #pragma unroll
-      for (int j = 0; j < BIG; ++j)
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) acc[j][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[j], b[nt], acc[j][nt], 0, 0, 0);
-#pragma unroll
-      for (int j = 0; j < BIG; ++j)
-#pragma unroll
-        for (int nt = 0; nt < 4; ++nt) acc[j][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[j], b[nt], acc[j][nt], 0, 0, 0);
+      for (int j = 0; j < BIG; ++j) al[kk][j] = *(const bf16x8_t *)(base + PLANE + a_row + j * 32 * kPfBK + kv);
     }
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+#pragma unroll
+      for (int j = 0; j < BIG; ++j)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) acc[j][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[kk][j], b[kk][nt], acc[j][nt], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < BIG; ++j)
+#pragma unroll
+        for (int nt = 0; nt < 4; ++nt) acc[j][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[kk][j], b[kk][nt], acc[j][nt], 0, 0, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x100, 2 * (2 * BIG + 4), 0);   // the LDS reads, all of them
+    __builtin_amdgcn_sched_group_barrier(0x008, 2 * 2 * BIG * 4, 0);     // then the MFMAs
   };
 
-  // stage s holds K step kt when kt % 2 == s; r0/r1 carry the steps after it (indices clamped to
-  // the last step: the surplus loads and stores at the end touch valid memory and are never read).
-  // The scheduling fences keep the order  issue loads -> multiply -> store the older loads,  which is
-  // what leaves a load two K steps of time to arrive.
-  PfRegs r0 = gload(0), r1 = gload(min(1, nk - 1));
-  lstore(r0, 0);
-  __syncthreads();
-  for (int kt = 0; kt + 2 <= nk; kt += 2) {
-    r0 = gload(min(kt + 2, nk - 1));
-    __builtin_amdgcn_sched_barrier(0);
-    compute(0);
-    __builtin_amdgcn_sched_barrier(0);
-    lstore(r1, 1);
+  // Stage kt % 2 holds K step kt.  Load indices are clamped to the last step: the surplus loads and
+  // stores at the end touch valid memory and are never read.  The scheduling fences keep the order written.
+  if constexpr (BIG == 2) {
+    // A step stores the tile loaded during the step before into the other stage (nobody reads that one
+    // until the barrier), asks for the tile after it, and multiplies: a load has one step's worth of
+    // MFMA time (32 per wave) to arrive, the stores drain under the MFMAs, one register set is in flight.
+    PfRegs r = gload(0);
+    lstore(r, 0);
+    r = gload(min(1, nk - 1));
     __syncthreads();
-    r1 = gload(min(kt + 3, nk - 1));
-    __builtin_amdgcn_sched_barrier(0);
-    compute(1);
-    __builtin_amdgcn_sched_barrier(0);
+    for (int kt = 0; kt + 2 <= nk; kt += 2) {
+      lstore(r, 1);
+      r = gload(min(kt + 2, nk - 1));
+      __builtin_amdgcn_sched_barrier(0);
+      compute(0);
+      __builtin_amdgcn_sched_barrier(0);
+      __syncthreads();
+      lstore(r, 0);
+      r = gload(min(kt + 3, nk - 1));
+      __builtin_amdgcn_sched_barrier(0);
+      compute(1);
+      __builtin_amdgcn_sched_barrier(0);
+      __syncthreads();
+    }
+  } else {
+    // Steps are short (16 MFMAs per wave) and K ranges too: two register sets, a load has two steps to arrive.
+    PfRegs r0 = gload(0), r1 = gload(min(1, nk - 1));
     lstore(r0, 0);
     __syncthreads();
+    for (int kt = 0; kt + 2 <= nk; kt += 2) {
+      r0 = gload(min(kt + 2, nk - 1));
+      __builtin_amdgcn_sched_barrier(0);
+      compute(0);
+      __builtin_amdgcn_sched_barrier(0);
+      lstore(r1, 1);
+      __syncthreads();
+      r1 = gload(min(kt + 3, nk - 1));
+      __builtin_amdgcn_sched_barrier(0);
+      compute(1);
+      __builtin_amdgcn_sched_barrier(0);
+      lstore(r0, 0);
+      __syncthreads();
+    }
   }
   if (nk & 1) compute(0);
 
