@@ -374,7 +374,7 @@ def main():
         "ms_per_generation_min": r["ms_per_generation_min"], "ms_per_generation_median": r["ms_per_generation_median"],
         "hbm_frac_per_moved_byte": moved_per_token and r["tokens_per_s"] * moved_per_token / (HBM_PEAK_GBPS * 1e9),
         "prefill": {"ms": r["prefill_ms"], "tokens_per_s": w.prompt_len / r["prefill_ms"] * 1e3,
-                    "path": "looped decode kernels" if args.prefill_loop else "MFMA GEMMs in chunks of 512 positions (when eligible)"},
+                    "path": "looped decode kernels" if args.prefill_loop else "MFMA GEMMs and attention over chunks of up to 4096 positions (when eligible)"},
         "roofline": roofline, "kernels": ktimes, "cpu_baseline": cpu,
         "weight_generation_s": gen_s,
     }
