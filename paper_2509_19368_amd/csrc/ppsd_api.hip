@@ -45,7 +45,7 @@ size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 constexpr int kOneSplitUpTo = 512;     // attention: a single split up to this capacity (max_seq)
 constexpr int kSplitPositions = 512;   // beyond it, one split per this many positions of capacity (measured at
                                        // 8192 positions, 8 KV heads: 512 -> 25 us, 256 -> 26 us, 128 -> 28.5 us)
-constexpr int kMaxSplits = 64;         // attention splits along the sequence (both engines)
+constexpr int kMaxSplits = kMaxAttnSplits;   // attention splits along the sequence (both engines)
 constexpr int kDefaultGamma = 3;       // drafts per round of PPSD_MODE_EESD
 constexpr size_t kBatchLdsMax = 150 * 1024;   // staged input vectors of a batched kernel: at most this much LDS
 constexpr size_t kBatchSlabBytes = 64 * 1024; // o_proj / down of the batched pass: column slabs of at most this much

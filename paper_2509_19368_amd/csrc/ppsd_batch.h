@@ -199,10 +199,15 @@ __global__ __launch_bounds__(kGBlock) void k_attn_b(Common c, int layer, const f
   __syncthreads();
   const int b = blockIdx.z;
   const int nq = c.dm.n_h * HD;
-  attn_unit<WT, HD, G, kGBlock>(c, lds_pt ? s_ptab : c.page_table, layer, si.pos + b, blockIdx.x, blockIdx.y, gridDim.y,
-                                q + (size_t)b * nq, aout + (size_t)b * nq,
-                                partials + (size_t)b * c.dm.n_h * gridDim.y * (HD + 2),
-                                counters + (size_t)b * c.dm.n_kv * kCounterStride, merge, &s_last);
+  float *part_b = partials + (size_t)b * c.dm.n_h * gridDim.y * (HD + 2);
+  int *count_b = counters + (size_t)b * c.dm.n_kv * kCounterStride;
+  // one call per address space of the page table (a selected pointer would turn the lookups into flat loads)
+  if (lds_pt)
+    attn_unit<WT, HD, G, kGBlock>(c, s_ptab, layer, si.pos + b, blockIdx.x, blockIdx.y, gridDim.y, q + (size_t)b * nq,
+                                  aout + (size_t)b * nq, part_b, count_b, merge, &s_last);
+  else
+    attn_unit<WT, HD, G, kGBlock>(c, c.page_table, layer, si.pos + b, blockIdx.x, blockIdx.y, gridDim.y, q + (size_t)b * nq,
+                                  aout + (size_t)b * nq, part_b, count_b, merge, &s_last);
 }
 
 // out_b[r] = resid_b[r] + W[r, c0 : c0 + Cs] . vin_b[c0 : c0 + Cs] for B tokens; vin is [B][C_total].

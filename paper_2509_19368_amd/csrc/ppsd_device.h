@@ -214,6 +214,26 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+// v of the lane that a DPP control selects inside the lane's row of 16 (a VALU move, no LDS traffic).
+template <int CTRL>
+__device__ __forceinline__ float dpp_row(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+// Sum over aligned groups of GS consecutive lanes (GS = 8, 16 or 32); every lane gets its group's sum.
+// Within a row of 16 lanes the partners come from DPP: lanes ^1 and ^2 by quad permutation, then the
+// mirrored lane of the 8-lane half and of the row (after the earlier steps every lane of a 4- or
+// 8-lane block holds the block's sum, so the mirrored lane holds what lane ^4 / ^8 holds).
+template <int GS>
+__device__ __forceinline__ float group_sum(float v) {
+  static_assert(GS == 8 || GS == 16 || GS == 32, "group sizes of the attention kernels");
+  v += dpp_row<0xB1>(v);                       // quad_perm [1,0,3,2]
+  v += dpp_row<0x4E>(v);                       // quad_perm [2,3,0,1]
+  v += dpp_row<0x141>(v);                      // row_half_mirror
+  if (GS >= 16) v += dpp_row<0x140>(v);        // row_mirror
+  if (GS >= 32) v += __shfl_xor(v, 16, kWave);
+  return v;
+}
+
 // Sum over the workgroup; every thread gets the result.  red: >= kWavesPerBlock floats of LDS.
 __device__ __forceinline__ float block_sum(float v, float *red) {
   v = wave_sum(v);

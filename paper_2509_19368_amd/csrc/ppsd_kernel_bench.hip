@@ -5,7 +5,9 @@
 // Also the reference dispatches for scaling rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings:
 // k_read_probe over 1 GiB and a 1 GiB device-to-device copy.
 //
-// usage: ppsd_kernel_bench [d_model d_ffn vocab n_heads n_kv_heads head_dim [iters]]   (bf16 storage)
+// usage: ppsd_kernel_bench [d_model d_ffn vocab n_heads n_kv_heads head_dim [iters [context [splits]]]]   (bf16 storage)
+// With a context length, the decode attention kernel is timed too: one query over `context` cached positions,
+// 32 layers' worth of K/V pages visited in turn (so no launch finds its rows in a cache), head_dim 128 only.
 #include <cstdio>
 #include <cstdlib>
 
@@ -29,6 +31,8 @@ int main(int argc, char **argv) {
   int d = 4096, f = 11008, V = 32000, n_h = 32, n_kv = 32, hd = 128, iters = 30;
   if (argc >= 7) { d = atoi(argv[1]); f = atoi(argv[2]); V = atoi(argv[3]); n_h = atoi(argv[4]); n_kv = atoi(argv[5]); hd = atoi(argv[6]); }
   if (argc >= 8) iters = atoi(argv[7]);
+  const int ctx = argc >= 9 ? atoi(argv[8]) : 0;
+  const int ctx_splits = argc >= 10 ? atoi(argv[9]) : 0;
   const int nq = n_h * hd;
   if (d % 8 || f % 8 || d > 8192 || f > 16384 || nq > 16384 || (hd != 64 && hd != 128)) { printf("unsupported shape\n"); return 2; }
   int dev = 0, n_cu = 0;
@@ -104,6 +108,48 @@ int main(int argc, char **argv) {
     hipLaunchKernelGGL((k_head<bf16_t>), dim3(c.dm.head_blocks), dim3(kGBlock), (size_t)xs_floats(2, d) * 4, 0, c, (int)kVanilla, (int)kXDraft, gain,
                        w, cand, (float *)nullptr, 1, (float *)nullptr);
   });
+
+  // decode attention at a long context
+  if (ctx > 0 && hd == 128 && (n_h / n_kv == 1 || n_h / n_kv == 2 || n_h / n_kv == 4) && n_h % n_kv == 0) {
+    const int a_layers = 32, a_pages = (ctx + pt - 1) / pt;
+    int a_splits = ctx_splits > 0 ? ctx_splits : (ctx <= 512 ? 1 : (ctx + 511) / 512);
+    if (a_splits > kMaxAttnSplits) a_splits = kMaxAttnSplits;
+    if (a_pages > kAttnLdsPages) { printf("context too long for this benchmark\n"); return 2; }
+    const size_t layer_bytes = (size_t)a_pages * n_kv * 2 * pt * hd * 2;
+    char *kvp; int32_t *ptab; float *apart; int *acount;
+    CK(hipMalloc(&kvp, layer_bytes * a_layers));
+    CK(hipMemset(kvp, 0x3c, layer_bytes * a_layers));
+    CK(hipMalloc(&ptab, 4 * (size_t)a_pages));
+    CK(hipMalloc(&apart, 4 * (size_t)n_h * kMaxAttnSplits * (hd + 2)));
+    CK(hipMalloc(&acount, 4 * (size_t)kCounterStride * n_kv));
+    CK(hipMemset(acount, 0, 4 * (size_t)kCounterStride * n_kv));
+    {
+      int32_t *h = (int32_t *)malloc(4 * (size_t)a_pages);
+      for (int i = 0; i < a_pages; ++i) h[i] = i;
+      CK(hipMemcpy(ptab, h, 4 * (size_t)a_pages, hipMemcpyHostToDevice));
+      free(h);
+    }
+    Common ca = c;
+    ca.page_table = ptab; ca.kv_pool = kvp;
+    ca.dm.max_seq = a_pages * pt; ca.dm.n_pages = a_pages; ca.dm.n_splits = a_splits; ca.dm.L = a_layers;
+    DevState sa = st;
+    sa.t = ctx - 1;
+    CK(hipMemcpy(ws, &sa, sizeof sa, hipMemcpyHostToDevice));
+    const size_t kv_read = (size_t)ctx * n_kv * 2 * hd * 2;
+    int turn = 0;
+    char name[64];
+    snprintf(name, sizeof name, "k_attn ctx %d x%d", ctx, a_splits);
+    run(name, kv_read, [&](const bf16_t *) {
+      const int layer = turn++ % a_layers;
+      const dim3 grid(n_kv, a_splits);
+      const int G = n_h / n_kv;
+      if (G == 1) hipLaunchKernelGGL((k_attn<bf16_t, 128, 1>), grid, dim3(kGBlock), 0, 0, ca, (int)kVanilla, layer, (const float *)vin, mout, apart, acount);
+      else if (G == 2) hipLaunchKernelGGL((k_attn<bf16_t, 128, 2>), grid, dim3(kGBlock), 0, 0, ca, (int)kVanilla, layer, (const float *)vin, mout, apart, acount);
+      else hipLaunchKernelGGL((k_attn<bf16_t, 128, 4>), grid, dim3(kGBlock), 0, 0, ca, (int)kVanilla, layer, (const float *)vin, mout, apart, acount);
+    });
+    CK(hipMemcpy(ws, &st, sizeof st, hipMemcpyHostToDevice));
+    CK(hipGetLastError());
+  }
 
   // the batched verify pass of draft-then-verify rounds, four tokens (same matrices, streamed once)
   constexpr int B = 4;

@@ -110,7 +110,8 @@ __global__ __launch_bounds__(kGBlock) void k_qkv(Common c, int role, int layer, 
 // Must be called by all BLOCK threads of the workgroup; ends with the workgroup synchronised.
 constexpr int kCounterStride = 64;   // ints between the arrival counters of two KV heads: atomics on one
                                     // cache line serialise, each head gets a line of its own
-constexpr int kMergeBatch = 16;   // splits whose partial results the merging workgroup loads at once
+constexpr int kMergeBatch = 32;   // splits whose partial results the merging workgroup loads at once
+constexpr int kMaxAttnSplits = 64; // splits along the sequence, at most (G * splits <= threads of the workgroup)
 template <typename WT, int HD, int G, int BLOCK>
 __device__ __forceinline__ void attn_unit(const Common &c, const int32_t *ptab, int layer, int pos, int kvh,
                                           int split, int n_splits, const float *q, float *aout, float *partials,
@@ -159,25 +160,19 @@ __device__ __forceinline__ void attn_unit(const Common &c, const int32_t *ptab, 
       vv[u] = *(const uint4 *)(kr + (size_t)m.page_tokens * HD);
     }
   };
-  int p0 = start + grp;
-  if (start < end) load_block(p0, ku, vu);
-  // the trip count is the same for every group of the workgroup (no barrier inside, but uniform per wave)
-  for (int b0 = start; b0 < end; b0 += U * GPB, p0 += U * GPB) {
-    const bool more = b0 + U * GPB < end;
-    if (more) load_block(p0 + U * GPB, kn, vn);
+  auto process = [&](int p0, const uint4 (&kk)[U], const uint4 (&vv)[U]) {
     float sc[G][U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       float kf[N];
-      Pack<WT>::unpack(ku[u], kf);
+      Pack<WT>::unpack(kk[u], kf);
       const bool ok = p0 + u * GPB < end;
 #pragma unroll
       for (int g = 0; g < G; ++g) {
         float sdot = 0.f;
 #pragma unroll
         for (int k = 0; k < N; ++k) sdot = fmaf(qr[g][k], kf[k], sdot);
-#pragma unroll
-        for (int o = GS / 2; o > 0; o >>= 1) sdot += __shfl_xor(sdot, o, kWave);
+        sdot = group_sum<GS>(sdot);
         sc[g][u] = ok ? sdot : kNegBig;
       }
     }
@@ -197,7 +192,7 @@ __device__ __forceinline__ void attn_unit(const Common &c, const int32_t *ptab, 
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       float vf[N];
-      Pack<WT>::unpack(vu[u], vf);
+      Pack<WT>::unpack(vv[u], vf);
 #pragma unroll
       for (int g = 0; g < G; ++g) {
         l[g] += sc[g][u];
@@ -205,11 +200,23 @@ __device__ __forceinline__ void attn_unit(const Common &c, const int32_t *ptab, 
         for (int k = 0; k < N; ++k) acc[g][k] = fmaf(sc[g][u], vf[k], acc[g][k]);
       }
     }
-    if (more) {
-#pragma unroll
-      for (int u = 0; u < U; ++u) { ku[u] = kn[u]; vu[u] = vn[u]; }
-    }
+  };
+  // Two register sets alternate, so a block's loads stay in flight while the block before it is used
+  // (copying one set into the other would wait for them).  The load behind the last block is clamped to
+  // valid rows and never used.  The trip count is the same for every group of the workgroup.
+  constexpr int STEP = U * GPB;
+  const int nb = start < end ? (end - start + STEP - 1) / STEP : 0;
+  int p0 = start + grp;
+  if (nb > 0) load_block(p0, ku, vu);
+  for (int i = 0; i + 2 <= nb; i += 2, p0 += 2 * STEP) {
+    load_block(p0 + STEP, kn, vn);
+    __builtin_amdgcn_sched_barrier(0);
+    process(p0, ku, vu);
+    load_block(p0 + 2 * STEP, ku, vu);
+    __builtin_amdgcn_sched_barrier(0);
+    process(p0 + STEP, kn, vn);
   }
+  if (nb & 1) process(p0, ku, vu);
 
   // merge the groups of a wave through shuffles (same lane j of every group holds the same dims),
   // then the waves of the workgroup through LDS, both in fixed order
@@ -278,36 +285,61 @@ __device__ __forceinline__ void attn_unit(const Common &c, const int32_t *ptab, 
     }
     __syncthreads();
     if (*s_last) {
-      for (int o = tid; o < G * HD; o += BLOCK) {
-        const int g = o / HD, dim = o % HD;
-        const int head = kvh * G + g;
-        const float *pr = partials + (size_t)head * n_splits * REC;
-        // splits in fixed order, kMergeBatch at a time so that their loads are in flight together
-        // (one round trip past the L2 per batch instead of one per split)
-        float M = kNegBig, L = 0.f, A = 0.f;
-        for (int s0 = 0; s0 < n_splits; s0 += kMergeBatch) {
-          float pm[kMergeBatch], pl[kMergeBatch], pa[kMergeBatch];
+      // Splits are added in index order.  Everything the merge needs is requested at once -- the (max, sum)
+      // pair of every (head, split), one pair per thread, and this thread's accumulator element of up to
+      // kMergeBatch splits -- so a merge of up to kMergeBatch splits waits for one trip past the L2, not
+      // one per batch and output.  The pairs go through LDS (the group-merge records are dead by now):
+      // lm/ll = max and sum per (head, split), lw = exp(max - head's max).
+      constexpr int OPT = (G * HD + BLOCK - 1) / BLOCK;      // outputs per thread
+      float *lm = merge, *ll = merge + G * kMaxAttnSplits, *lw = merge + 2 * G * kMaxAttnSplits;
+      float pa[OPT][kMergeBatch];
+      auto load_acc = [&](int s0) {
 #pragma unroll
-          for (int k = 0; k < kMergeBatch; ++k) {
-            const float *ps = pr + (size_t)min(s0 + k, n_splits - 1) * REC;
-            pm[k] = ld_agent(ps); pl[k] = ld_agent(ps + 1); pa[k] = ld_agent(ps + 2 + dim);
-          }
-          float Mn = M;
+        for (int r = 0; r < OPT; ++r) {
+          const int o = min(tid + r * BLOCK, G * HD - 1), g = o / HD, dim = o % HD;
+          const float *pr = partials + (size_t)(kvh * G + g) * n_splits * REC + 2 + dim;
 #pragma unroll
-          for (int k = 0; k < kMergeBatch; ++k) if (s0 + k < n_splits) Mn = fmaxf(Mn, pm[k]);
-          const float corr = __expf(M - Mn);
-          L *= corr; A *= corr;
+          for (int k = 0; k < kMergeBatch; ++k) pa[r][k] = ld_agent(pr + (size_t)min(s0 + k, n_splits - 1) * REC);
+        }
+      };
+      float my_m = kNegBig, my_l = 0.f;
+      static_assert(G * kMaxAttnSplits <= BLOCK, "one (max, sum) pair per thread");
+      if (tid < G * n_splits) {
+        const float *ps = partials + ((size_t)(kvh * G + tid / n_splits) * n_splits + tid % n_splits) * REC;
+        my_m = ld_agent(ps); my_l = ld_agent(ps + 1);
+      }
+      load_acc(0);
+      if (tid < G * n_splits) { lm[tid] = my_m; ll[tid] = my_l; }
+      __syncthreads();
+      if (tid < G * n_splits) {
+        const int g = tid / n_splits;
+        float M = kNegBig;
+        for (int s2 = 0; s2 < n_splits; ++s2) M = fmaxf(M, lm[g * n_splits + s2]);
+        lw[tid] = __expf(my_m - M);
+      }
+      __syncthreads();
+      float A[OPT], L[OPT];
+#pragma unroll
+      for (int r = 0; r < OPT; ++r) { A[r] = 0.f; L[r] = 0.f; }
+      for (int s0 = 0; s0 < n_splits; s0 += kMergeBatch) {
+        if (s0 > 0) load_acc(s0);
+#pragma unroll
+        for (int r = 0; r < OPT; ++r) {
+          const int g = min(tid + r * BLOCK, G * HD - 1) / HD;
 #pragma unroll
           for (int k = 0; k < kMergeBatch; ++k) {
             if (s0 + k < n_splits) {
-              const float w = __expf(pm[k] - Mn);
-              L = fmaf(pl[k], w, L);
-              A = fmaf(pa[k], w, A);
+              const float w = lw[g * n_splits + s0 + k];
+              L[r] = fmaf(ll[g * n_splits + s0 + k], w, L[r]);
+              A[r] = fmaf(pa[r][k], w, A[r]);
             }
           }
-          M = Mn;
         }
-        aout[head * HD + dim] = A / L;
+      }
+#pragma unroll
+      for (int r = 0; r < OPT; ++r) {
+        const int o = tid + r * BLOCK;
+        if (o < G * HD) aout[(kvh * G + o / HD) * HD + o % HD] = A[r] / L[r];
       }
       // ready for the next use (a later launch or a later phase)
       if (tid == 0) __hip_atomic_store(&counters[kvh * kCounterStride], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -333,8 +365,10 @@ __global__ __launch_bounds__(kGBlock) void k_attn(Common c, int role, int layer,
   const StageIn si = stage_in(c, role);
   if (!si.active) return;
   __syncthreads();
-  attn_unit<WT, HD, G, kGBlock>(c, lds_pt ? s_ptab : c.page_table, layer, si.pos, blockIdx.x, blockIdx.y, gridDim.y,
-                                q, aout, partials, counters, merge, &s_last);
+  // two calls, not one with a selected pointer: a pointer that may be LDS or global memory makes every
+  // page lookup a flat load, and waiting for a flat load waits for all K/V loads in flight as well
+  if (lds_pt) attn_unit<WT, HD, G, kGBlock>(c, s_ptab, layer, si.pos, blockIdx.x, blockIdx.y, gridDim.y, q, aout, partials, counters, merge, &s_last);
+  else attn_unit<WT, HD, G, kGBlock>(c, c.page_table, layer, si.pos, blockIdx.x, blockIdx.y, gridDim.y, q, aout, partials, counters, merge, &s_last);
 }
 
 // ------------------------------------------------------------------------------------------
