@@ -208,11 +208,6 @@ template <> struct Pack<bf16_t> {
   static __device__ __forceinline__ bf16_t from_float(float v) { return float_to_bf16_rne(v); }
 };
 
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-  return v;
-}
 
 // v of the lane that a DPP control selects inside the lane's row of 16 (a VALU move, no LDS traffic).
 template <int CTRL>
@@ -231,6 +226,13 @@ __device__ __forceinline__ float group_sum(float v) {
   v += dpp_row<0x141>(v);                      // row_half_mirror
   if (GS >= 16) v += dpp_row<0x140>(v);        // row_mirror
   if (GS >= 32) v += __shfl_xor(v, 16, kWave);
+  return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+  v = group_sum<16>(v);                        // within each row of 16 lanes, on the VALU
+  v += __shfl_xor(v, 16, kWave);
+  v += __shfl_xor(v, 32, kWave);
   return v;
 }
 
