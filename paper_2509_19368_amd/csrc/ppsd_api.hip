@@ -417,14 +417,19 @@ void launch_proj_b(Launcher &L, int kind, const float *vin, int C, const WT *W, 
   int n_slabs = (int)(((size_t)B * C * 4 + kBatchSlabBytes - 1) / kBatchSlabBytes);
   int Cs = ((C + n_slabs - 1) / n_slabs + blk - 1) / blk * blk;
   if ((size_t)B * Cs * 4 > kBatchLdsMax) Cs = (int)(kBatchLdsMax / (4 * B)) / blk * blk;
-  for (int c0 = 0; c0 < C; c0 += Cs) {
-    const int w = C - c0 < Cs ? C - c0 : Cs;
-    const size_t lds = (size_t)B * x->xs_bytes(w);
+  if (Cs < C) {
+    // several slabs: one launch that walks them, one row per wave
     L.before(kind);
-    hipLaunchKernelGGL((k_proj_resid_b<WT, B>), dim3(batch_grid(x, (d + 1) / 2, lds, kGemvWgsPerCu)), dim3(kGBlock), lds, L.s,
-                       x->cm, vin, C, c0, w, W, d, c0 == 0 ? resid_slot0 : out_slot0, out_slot0);
+    hipLaunchKernelGGL((k_proj_resid_bs<WT, B>), dim3((d + kGWaves - 1) / kGWaves), dim3(kGBlock), (size_t)B * x->xs_bytes(Cs), L.s, x->cm,
+                       vin, C, Cs, W, d, resid_slot0, out_slot0);
     L.after();
+    return;
   }
+  const size_t lds = (size_t)B * x->xs_bytes(C);
+  L.before(kind);
+  hipLaunchKernelGGL((k_proj_resid_b<WT, B>), dim3(batch_grid(x, (d + 1) / 2, lds, kGemvWgsPerCu)), dim3(kGBlock), lds, L.s, x->cm, vin,
+                     C, 0, C, W, d, resid_slot0, out_slot0);
+  L.after();
 }
 
 template <typename WT, int B>
@@ -475,6 +480,7 @@ hipError_t allow_batch_lds() {
   if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_gate_up_b<WT, B>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_head_b<WT, B>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
   if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_proj_resid_b<WT, B>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) e = hipFuncSetAttribute((const void *)k_proj_resid_bs<WT, B>, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
   return e;
 }
 

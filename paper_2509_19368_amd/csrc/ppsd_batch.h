@@ -247,6 +247,81 @@ __global__ __launch_bounds__(kGBlock) void k_proj_resid_b(Common c, const float 
   });
 }
 
+// The same projection when the B staged input vectors exceed the LDS budget: one launch, one row per wave
+// (n_rows waves in all), the column slabs taken in turn inside the kernel.  A wave keeps its row's B sums in
+// registers across the slabs, so per (row, token) the products are added in exactly the order of the
+// single-token kernel, and the first weight loads of a slab are in flight while the slab's inputs are staged.
+// Cs: columns per slab, a multiple of a column block (64 lanes x 16 bytes).  Dynamic LDS = B * Cs floats.
+// grid = ceil(n_rows / waves per workgroup).
+template <typename WT, int B>
+__global__ __launch_bounds__(kGBlock) void k_proj_resid_bs(Common c, const float *vin, int C, int Cs, const WT *W, int n_rows,
+                                                           int resid_slot0, int out_slot0) {
+  extern __shared__ __align__(16) float xs[];
+  constexpr int N = Pack<WT>::N, KB = kProjTripBlocks, kStride = kWave * N;
+  const StageIn si = stage_in(c, kEesdVerify);
+  if (!si.active) return;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int row = blockIdx.x * kGWaves + wave;
+  const bool mine = row < n_rows;                        // every wave takes part in the barriers
+  const WT *rows[1] = {W + (size_t)(mine ? row : 0) * C};
+  Trip<WT, 1, KB> trip;
+  {
+    const int w0 = C < Cs ? C : Cs;
+    if (mine) trip_load<WT, 1, KB>(trip, rows, 0, col_blocks<WT>(w0), w0);
+  }
+  float acc[B];
+#pragma unroll
+  for (int b = 0; b < B; ++b) acc[b] = 0.f;
+  const int ldx = xs_floats((int)sizeof(WT), Cs);
+  for (int c0 = 0; c0 < C; c0 += Cs) {
+    const int w = C - c0 < Cs ? C - c0 : Cs, nblk = col_blocks<WT>(w);
+    if (c0 > 0) __syncthreads();                         // the slab before has been read
+#pragma unroll
+    for (int b = 0; b < B; ++b)
+      for (int i = 4 * threadIdx.x; i < w; i += 4 * kGBlock)
+        *(float4 *)(xs + (size_t)b * ldx + xs_pos<WT>(i)) = *(const float4 *)(vin + (size_t)b * C + c0 + i);
+    __syncthreads();
+    if (mine) {
+      for (int cb = 0; cb < nblk; cb += KB) {
+#pragma unroll
+        for (int k = 0; k < KB; ++k) {
+          if ((cb + k) * kStride + lane * N < w) {
+            float wf[N];
+            Pack<WT>::unpack(trip.u[k], wf);
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+              float x[N];
+#pragma unroll
+              for (int q = 0; q < N / 4; ++q) {
+                const float4 v = *(const float4 *)(xs + (size_t)b * ldx + (cb + k) * kStride + q * (4 * kWave) + lane * 4);
+                x[4 * q] = v.x; x[4 * q + 1] = v.y; x[4 * q + 2] = v.z; x[4 * q + 3] = v.w;
+              }
+#pragma unroll
+              for (int e = 0; e < N; ++e) acc[b] = fmaf(wf[e], x[e], acc[b]);
+            }
+          }
+        }
+        if (cb + KB < nblk) {
+          trip_load<WT, 1, KB>(trip, rows, cb + KB, nblk, w);
+        } else if (c0 + Cs < C) {                        // first trip of the next slab
+          const int w2 = C - c0 - Cs < Cs ? C - c0 - Cs : Cs;
+          rows[0] += Cs;
+          trip_load<WT, 1, KB>(trip, rows, 0, col_blocks<WT>(w2), w2);
+        }
+      }
+    }
+  }
+  if (!mine) return;
+  const int d = c.dm.d;
+  const float *resid = c.xbuf + (size_t)resid_slot0 * d;
+  float *out = c.xbuf + (size_t)out_slot0 * d;
+#pragma unroll
+  for (int b = 0; b < B; ++b) {
+    const float sum = wave_sum(acc[b]);
+    if (lane == 0) out[(size_t)b * d + row] = resid[(size_t)b * d + row] + sum;
+  }
+}
+
 // RMSNorm + gate/up + SwiGLU for B tokens: mout is [B][f].  Dynamic LDS = B * d floats.
 template <typename WT, int B>
 __global__ __launch_bounds__(kGBlock) void k_gate_up_b(Common c, int x_slot0, const float *gain, const WT *wgu,

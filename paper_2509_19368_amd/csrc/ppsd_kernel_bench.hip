@@ -175,14 +175,18 @@ int main(int argc, char **argv) {
     hipLaunchKernelGGL((k_gate_up_b<bf16_t, B>), dim3(bgrid(f, lds_d, kGateUpWgsPerCu)), dim3(kGBlock), lds_d, 0, c,
                        (int)kXBatchWorkSlot0, gain, w, mb);
   });
-  run("k_proj_resid_b<4> (down)", (size_t)d * f * 2, [&](const bf16_t *w) {
+  CK(hipFuncSetAttribute((const void *)k_proj_resid_bs<bf16_t, B>, hipFuncAttributeMaxDynamicSharedMemorySize, lds_cap));
+  run("k_proj_resid_bs<4> (down)", (size_t)d * f * 2, [&](const bf16_t *w) {
+    // as the library launches it: column slabs of at most 64 KB of staged inputs, walked inside one launch
     const int n_slabs = (int)(((size_t)B * f * 4 + 65535) / 65536);
     const int Cs = ((f + n_slabs - 1) / n_slabs + 511) / 512 * 512;
-    for (int c0 = 0; c0 < f; c0 += Cs) {
-      const int wd = f - c0 < Cs ? f - c0 : Cs;
-      const size_t lds = (size_t)B * xs_floats(2, wd) * 4;
+    if (Cs < f) {
+      hipLaunchKernelGGL((k_proj_resid_bs<bf16_t, B>), dim3((d + kGWaves - 1) / kGWaves), dim3(kGBlock), (size_t)B * xs_floats(2, Cs) * 4, 0, c,
+                         (const float *)mb, f, Cs, w, d, (int)kXBatchWorkSlot0, (int)kXBatchWorkSlot0);
+    } else {
+      const size_t lds = (size_t)B * xs_floats(2, f) * 4;
       hipLaunchKernelGGL((k_proj_resid_b<bf16_t, B>), dim3(bgrid((d + 1) / 2, lds, kGemvWgsPerCu)), dim3(kGBlock), lds, 0, c,
-                         (const float *)mb, f, c0, wd, w, d, (int)kXBatchWorkSlot0, (int)kXBatchWorkSlot0);
+                         (const float *)mb, f, 0, f, w, d, (int)kXBatchWorkSlot0, (int)kXBatchWorkSlot0);
     }
   });
   run("k_head_b<4>", (size_t)V * d * 2, [&](const bf16_t *w) {

@@ -124,15 +124,20 @@ def test_all_accept_and_never_accept_limits(P):
 
 def test_column_slabs_of_the_down_projection(P):
     """d_ffn so large that four staged input vectors exceed a slab: the down-projection of the batched
-    pass runs as two launches over column ranges (the second adds onto the first)."""
-    for dtype, tol in (("fp32", REL_TOL_FP32), ("bf16", REL_TOL_BF16)):
-        w = S.Workload("slab", n_layers=3, exit_layer=1, d_model=128, n_heads=2, n_kv_heads=1, head_dim=64, d_ffn=4360,
+    pass walks column slabs inside one launch, keeping each row's sums in registers, so per token the
+    products are still added in the single-token kernel's order: logits bitwise equal to vanilla mode.
+    d_ffn 4360 (two slabs, ragged last column block) and 9000 (three)."""
+    for dtype, tol, f in (("fp32", REL_TOL_FP32, 4360), ("bf16", REL_TOL_BF16, 4360), ("bf16", REL_TOL_BF16, 9000)):
+        w = S.Workload("slab", n_layers=3, exit_layer=1, d_model=128, n_heads=2, n_kv_heads=1, head_dim=64, d_ffn=f,
                        vocab=331, dtype=dtype, damp=0.1, seed=41, prompt_len=4, decode_len=24)
         W = S.make_weights(w)
         prompt = S.make_prompt(w)
-        r = _run(P, w, to_device(W, "cuda"), prompt, [w.decode_len], P.MODE_EESD, 3)
+        Wg = to_device(W, "cuda")
+        r = _run(P, w, Wg, prompt, [w.decode_len], P.MODE_EESD, 3)
         check_against_teacher_forced_oracle(O.Decoder(w, W), prompt, r["tokens"], r["logits"], tol)
         assert r["stats"][-1]["committed"] == w.decode_len
+        v = _run(P, w, Wg, prompt, [w.decode_len], P.MODE_VANILLA)
+        assert v["tokens"] == r["tokens"] and torch.equal(v["logits"], r["logits"])
 
 
 def test_bf16_ragged_gqa_shapes(P):

@@ -395,8 +395,8 @@ def test_matrix_core_prefill_in_chunks_of_different_sizes(P):
 
 def test_widest_supported_shape(P):
     """The staging capacity limits: d_model 8192 and d_ffn 16384 (64 KB of LDS per staged vector), 64 heads.
-    Every schedule must commit vanilla mode's stream bit for bit (draft-then-verify: the batched pass needs
-    column slabs here, so it is held to the oracle instead), and the oracle protocol must hold."""
+    Every schedule must commit vanilla mode's stream bit for bit (draft-then-verify too: its batched pass walks
+    column slabs of the down-projection here), and the oracle protocol must hold."""
     w = S.Workload("wide", n_layers=2, exit_layer=1, d_model=8192, n_heads=64, n_kv_heads=64, head_dim=128, d_ffn=16384,
                    vocab=1031, dtype="bf16", damp=0.2, seed=77, prompt_len=5, decode_len=7)
     Wg = S.make_weights(w, device="cuda")
@@ -409,7 +409,7 @@ def test_widest_supported_shape(P):
         toks = [ss.ppsd_prefill(prompt)] + ss.ppsd_decode(n)
         runs[name] = (toks, ss.read_logits(0, n + 1))
         ss.close()
-    for name in ("overlap", "pipeline"):
+    for name in ("overlap", "pipeline", "eesd"):
         assert runs[name][0] == runs["vanilla"][0] and torch.equal(runs[name][1], runs["vanilla"][1]), name
     W = {k: ([t.cpu() for t in v] if isinstance(v, list) else v.cpu()) for k, v in Wg.items()}
     del Wg
