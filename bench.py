@@ -22,13 +22,24 @@ if ROOT not in sys.path:
 HBM_PEAK_GBPS = 8000.0
 
 # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE (scaled by reference
-# dispatches of known size), 7B shapes: profiles/weight_streaming_kernels_7B_shapes_pmc.md
+# dispatches of known size: one FETCH_SIZE unit = 2 KiB, one WRITE_SIZE unit = 1 KiB), at the 7B, 13B and
+# 8B-GQA shapes: profiles/weight_streaming_kernels_7B_shapes_pmc.md
 MEASURED_TRAFFIC_BYTES = {
-    ("C2", "gate_up"): 88234.7 * 2048 + 43.1 * 1024,
-    ("C2", "qkv"): 49335.5 * 2048 + 48.0 * 1024,
-    ("C2", "head"): 128177.9 * 2048 + 20.8 * 1024,
-    ("C2", "o_proj"): 16513.5 * 2048 + 16.0 * 1024,
-    ("C2", "down"): 44277.2 * 2048 + 16.0 * 1024,
+    ("C2", "gate_up"): 88233.2 * 2048 + 43.1 * 1024,
+    ("C2", "qkv"): 49329.5 * 2048 + 48.0 * 1024,
+    ("C2", "head"): 128176.9 * 2048 + 20.9 * 1024,
+    ("C2", "o_proj"): 16519.5 * 2048 + 16.0 * 1024,
+    ("C2", "down"): 44281.1 * 2048 + 16.0 * 1024,
+    ("C4", "gate_up"): 138442.7 * 2048 + 54.1 * 1024,
+    ("C4", "qkv"): 77018.4 * 2048 + 60.0 * 1024,
+    ("C4", "head"): 160208.9 * 2048 + 20.8 * 1024,
+    ("C4", "o_proj"): 25759.6 * 2048 + 20.0 * 1024,
+    ("C4", "down"): 69417.7 * 2048 + 20.0 * 1024,
+    ("C5", "gate_up"): 114857.5 * 2048 + 56.2 * 1024,
+    ("C5", "qkv"): 24753.5 * 2048 + 24.0 * 1024,
+    ("C5", "head"): 513205.9 * 2048 + 22.8 * 1024,
+    ("C5", "o_proj"): 16519.6 * 2048 + 16.0 * 1024,
+    ("C5", "down"): 57646.1 * 2048 + 16.0 * 1024,
 }
 
 
