@@ -56,3 +56,24 @@ def test_config_validation_runs_on_the_host():
         assert False
     except P.PpsdError as e:
         assert "exit_layer" in str(e)
+
+
+def test_prefill_chunk_and_tile_settings_size_the_workspace_on_the_host():
+    """prefill_chunk sizes the chunk buffers (residual, queries, attention output in fp32; the bf16 high + low
+    parts), so a smaller chunk needs a smaller workspace; invalid settings are refused before any GPU call."""
+    import paper_2509_19368_amd as P
+    import synth_inputs as S
+    from paper_2509_19368_amd.binding import make_config
+    w = S.WORKLOADS["C5"]
+    big = P.ppsd_workspace_bytes(make_config(w, 8192 + 600, P.MODE_VANILLA))                       # chunk 4096
+    small = P.ppsd_workspace_bytes(make_config(w, 8192 + 600, P.MODE_VANILLA, prefill_chunk=512))
+    looped = P.ppsd_workspace_bytes(make_config(w, 8192 + 600, P.MODE_VANILLA, prefill_loop=True))
+    assert looped < small < big
+    per_position = 4 * 3 * 4096 + 2 * 2 * (4096 + 14336)     # the buffers that scale with the chunk, bytes per position
+    assert big - small >= (4096 - 512) * per_position
+    for kw in (dict(prefill_chunk=100), dict(prefill_chunk=8192), dict(prefill_chunk=-128), dict(tune_prefill_tile=3)):
+        try:
+            P.ppsd_workspace_bytes(make_config(w, 9000, P.MODE_VANILLA, **kw))
+            assert False, kw
+        except P.PpsdError as e:
+            assert "prefill" in str(e)
