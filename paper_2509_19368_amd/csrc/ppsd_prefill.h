@@ -249,11 +249,11 @@ __global__ __launch_bounds__(kPfBlock *BIG) void k_pf_gemm(Common c, PfGemm g) {
   // bases are multiples of 32, so the row's swizzle term depends on the lane only.
   const int half = lane >> 5, swz = (lane >> 2) & 3;
   const int a_row = (wm * BIG * 32 + (lane & 31)) * kPfBK, b_row = (wn * 128 + (lane & 31)) * kPfBK;
-  auto compute = [&](int st) {
+  // A K step = fetch (the step's MFMA operands from LDS into registers, all requested at once: the reads
+  // return in order, so the first MFMAs can start while the rest arrive) + mma (the MFMAs, from registers).
+  bf16x8_t ah[2][BIG], al[2][BIG], b[2][4];
+  auto fetch = [&](int st) {
     const bf16_t *base = pf_lds + st * STAGE;
-    // every operand of the K step is requested before the first MFMA: the reads return in order, so
-    // the matrix cores start after the first few and the rest arrive underneath them
-    bf16x8_t ah[2][BIG], al[2][BIG], b[2][4];
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
       const int kv = ((kk * 2 + half) ^ swz) * 8;
@@ -264,6 +264,8 @@ __global__ __launch_bounds__(kPfBlock *BIG) void k_pf_gemm(Common c, PfGemm g) {
 #pragma unroll
       for (int j = 0; j < BIG; ++j) al[kk][j] = *(const bf16x8_t *)(base + PLANE + a_row + j * 32 * kPfBK + kv);
     }
+  };
+  auto mma = [&]() {
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
 #pragma unroll
@@ -275,6 +277,10 @@ __global__ __launch_bounds__(kPfBlock *BIG) void k_pf_gemm(Common c, PfGemm g) {
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt) acc[j][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al[kk][j], b[kk][nt], acc[j][nt], 0, 0, 0);
     }
+  };
+  auto compute = [&](int st) {
+    fetch(st);
+    mma();
     __builtin_amdgcn_sched_group_barrier(0x100, 2 * (2 * BIG + 4), 0);   // the LDS reads, all of them
     __builtin_amdgcn_sched_group_barrier(0x008, 2 * 2 * BIG * 4, 0);     // then the MFMAs
   };
@@ -282,25 +288,29 @@ __global__ __launch_bounds__(kPfBlock *BIG) void k_pf_gemm(Common c, PfGemm g) {
   // Stage kt % 2 holds K step kt.  Load indices are clamped to the last step: the surplus loads and
   // stores at the end touch valid memory and are never read.  The scheduling fences keep the order written.
   if constexpr (BIG == 2) {
-    // A step stores the tile loaded during the step before into the other stage (nobody reads that one
-    // until the barrier), asks for the tile after it, and multiplies: a load has one step's worth of
-    // MFMA time (32 per wave) to arrive, the stores drain under the MFMAs, one register set is in flight.
+    // Two waves share a SIMD (waves w and w + 4).  Running in step they would fetch together and leave the
+    // matrix cores idle meanwhile, so the two halves of the workgroup run half a step apart: while waves
+    // 0-3 multiply step kt, waves 4-7 do their memory phase of step kt (operands of step kt from LDS
+    // into registers, the global tile kt + 1 from registers into the other LDS stage, the request for tile
+    // kt + 2); then they swap.  One barrier per half step.  Tile kt + 1 is complete in LDS after both
+    // halves' memory phases of step kt and is first read in a memory phase of step kt + 1, behind a barrier;
+    // the stage it overwrites was last read in the memory phases of step kt - 1, also behind a barrier.
+    const bool ahead = wave < 4;      // waves w and w + 4 share a SIMD (measured: other pairings run 1.4x slower)
     PfRegs r = gload(0);
     lstore(r, 0);
     r = gload(min(1, nk - 1));
     __syncthreads();
-    for (int kt = 0; kt + 2 <= nk; kt += 2) {
-      lstore(r, 1);
+    auto memory_phase = [&](int kt) {
+      fetch(kt & 1);
+      lstore(r, (kt + 1) & 1);
       r = gload(min(kt + 2, nk - 1));
-      __builtin_amdgcn_sched_barrier(0);
-      compute(0);
-      __builtin_amdgcn_sched_barrier(0);
+    };
+    if (ahead) memory_phase(0);
+    __syncthreads();
+    for (int kt = 0; kt < nk; ++kt) {
+      if (ahead) mma(); else memory_phase(kt);
       __syncthreads();
-      lstore(r, 0);
-      r = gload(min(kt + 3, nk - 1));
-      __builtin_amdgcn_sched_barrier(0);
-      compute(1);
-      __builtin_amdgcn_sched_barrier(0);
+      if (!ahead) mma(); else if (kt + 1 < nk) memory_phase(kt + 1);
       __syncthreads();
     }
   } else {
@@ -322,8 +332,9 @@ __global__ __launch_bounds__(kPfBlock *BIG) void k_pf_gemm(Common c, PfGemm g) {
       lstore(r0, 0);
       __syncthreads();
     }
+    if (nk & 1) compute(0);
   }
-  if (nk & 1) compute(0);
+
 
   // acc[j][nt][v]: row wm*BIG*32 + j*32 + 8*(v/4) + 4*(lane/32) + v%4 of the workgroup tile, column nt*32 + lane%32
   // of unit tile tn
