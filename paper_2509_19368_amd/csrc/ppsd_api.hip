@@ -413,20 +413,18 @@ template <typename WT, int B>
 void launch_proj_b(Launcher &L, int kind, const float *vin, int C, const WT *W, int resid_slot0, int out_slot0) {
   ppsd_ctx *x = L.x;
   const int d = x->cfg.d_model;
-  const int blk = 512;                                  // slabs end on column-block boundaries
-  int n_slabs = (int)(((size_t)B * C * 4 + kBatchSlabBytes - 1) / kBatchSlabBytes);
-  int Cs = ((C + n_slabs - 1) / n_slabs + blk - 1) / blk * blk;
-  if ((size_t)B * Cs * 4 > kBatchLdsMax) Cs = (int)(kBatchLdsMax / (4 * B)) / blk * blk;
-  if (n_slabs > 1) {
-    // the slab-walking kernel has one row per wave: size the slabs so that all its workgroups are resident
-    // at once, two per compute unit or, with more than two per unit's worth of rows, three (its registers allow three)
+  int Cs = C;                                           // one slab when the B staged vectors fit the slab budget
+  if ((size_t)B * C * 4 > kBatchSlabBytes) {
+    // The slab-walking kernel has one row per wave: size the slabs so that all its workgroups are resident at
+    // once, two per compute unit or, with more rows than that, three (its registers allow three).
+    const int blk = 512;                                // slabs end on column-block boundaries
     const int wgs = (d + kGWaves - 1) / kGWaves;
     const int per_cu = wgs > 2 * x->n_cu ? 3 : 2;
     size_t budget = (size_t)160 * 1024 / per_cu - 2048;
     if (budget > kBatchSlabBytes) budget = kBatchSlabBytes;
     int cs_max = (int)(budget / 4 / B) / blk * blk;
     if (cs_max < blk) cs_max = blk;
-    n_slabs = (C + cs_max - 1) / cs_max;
+    const int n_slabs = (C + cs_max - 1) / cs_max;
     Cs = ((C + n_slabs - 1) / n_slabs + blk - 1) / blk * blk;
   }
   if (Cs < C) {
