@@ -368,6 +368,31 @@ def test_matrix_core_prefill_matches_oracle_and_looped_prefill(P, shape, prompt_
     assert diff[:same].max().item() < 2e-3, diff
 
 
+def test_matrix_core_prefill_through_small_shuffled_pages(P):
+    """Pages of 8 positions in a shuffled physical order, two and four query heads per KV head: the GEMM
+    epilogue appends K/V rows through the page table and the attention kernel gathers them through it.
+    Same first token, and a decode stream that passes the oracle protocol."""
+    for n_heads, n_kv in ((2, 1), (4, 1), (4, 2)):
+        w = S.Workload("pfpg", n_layers=2, exit_layer=1, d_model=256, n_heads=n_heads, n_kv_heads=n_kv, head_dim=128, d_ffn=448,
+                       vocab=515, dtype="bf16", damp=0.2, seed=33, prompt_len=203, decode_len=8)
+        W = S.make_weights(w)
+        prompt = S.make_prompt(w)
+        dec = O.Decoder(w, W)
+        Wg = to_device(W, "cuda")
+        max_seq = 203 + 10
+        table = S.page_permutation(7, (max_seq + 7) // 8)
+        firsts = []
+        for loop in (False, True):
+            ss = P.Session(w, Wg, max_seq=max_seq, mode=P.MODE_VANILLA, debug_logits=9, prefill_loop=loop, kv_page_tokens=8,
+                           page_table=table, prefill_chunk=128 if not loop else 0)
+            toks = [ss.ppsd_prefill(prompt)] + ss.ppsd_decode(8)
+            logits = ss.read_logits(0, 9)
+            ss.close()
+            check_against_teacher_forced_oracle(dec, prompt, toks, logits, REL_TOL_BF16)
+            firsts.append(toks[0])
+        assert firsts[0] == firsts[1]
+
+
 def test_matrix_core_prefill_in_chunks_of_different_sizes(P):
     """The same prompt in one chunk and in chunks of 128 and 256 positions.  A chunk's GEMM rows do not
     interact and attention reads the KV pages, so only the K ranges of the split GEMMs (chosen from the
