@@ -83,6 +83,8 @@ bool valid_config(const ppsd_config *c, const char **why) {
   REJECT(c->max_seq < 3, "max_seq too small");
   REJECT(c->kv_page_tokens != 8 && c->kv_page_tokens != 16 && c->kv_page_tokens != 32 && c->kv_page_tokens != 64,
          "kv_page_tokens must be 8, 16, 32 or 64");
+  REJECT((double)(c->n_layers + 1) * ((c->max_seq + c->kv_page_tokens - 1) / c->kv_page_tokens) * c->n_kv_heads * 2 >= 2147483648.0,
+         "layers x pages x KV heads x 2 must stay below 2^31 (KV block index)");
   REJECT(c->mode < 0 || c->mode > 4, "mode must be 0..4");
   REJECT(!(c->rope_base > 1.0f) || !(c->rms_eps >= 0.0f), "bad rope_base / rms_eps");
   REJECT(c->debug_logits < 0, "debug_logits < 0");
@@ -908,7 +910,9 @@ int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *b, ppsd_ctx **
   m.V = cfg->vocab; m.L = cfg->n_layers; m.E = cfg->exit_layer; m.max_seq = cfg->max_seq;
   m.page_tokens = cfg->kv_page_tokens; m.n_pages = lay.n_pages; m.n_splits = lay.n_splits;
   m.debug_rows = cfg->debug_logits; m.head_blocks = 0;   // set below, once the device is known
-  m.n_stages = (cfg->n_layers + cfg->exit_layer - 1) / cfg->exit_layer; m.pad0 = 0;
+  m.n_stages = (cfg->n_layers + cfg->exit_layer - 1) / cfg->exit_layer;
+  m.page_shift = 0;
+  while ((1 << m.page_shift) < cfg->kv_page_tokens) ++m.page_shift;
   m.eps = cfg->rms_eps; m.qscale = (float)(1.0 / std::sqrt((double)cfg->head_dim));
 
   auto cleanup = [&](int rc) { ppsd_free(x); return rc; };

@@ -72,7 +72,7 @@ struct Dims {
   int32_t d, n_h, n_kv, hd, f, V, L, E;
   int32_t max_seq, page_tokens, n_pages, n_splits;
   int32_t debug_rows, head_blocks;
-  int32_t n_stages, pad0;   // ceil(L / E)
+  int32_t n_stages, page_shift;   // ceil(L / E); log2(page_tokens) (pages hold 8, 16, 32 or 64 positions)
   float eps, qscale;     // qscale = 1/sqrt(hd)
 };
 

@@ -53,7 +53,7 @@ int main(int argc, char **argv) {
   c.page_table = (int32_t *)(ws + (4 << 20));
   c.kv_pool = ws + (8 << 20);
   const int max_seq = 386, pt = 16, n_pages = (max_seq + pt - 1) / pt;
-  c.dm = Dims{d, n_h, n_kv, hd, f, V, 32, 8, max_seq, pt, n_pages, 1, 0, gemv_grid_for((V + 1) / 2, n_cu, kGemvWgsPerCu), 4, 0, 1e-5f, 0.088f};
+  c.dm = Dims{d, n_h, n_kv, hd, f, V, 32, 8, max_seq, pt, n_pages, 1, 0, gemv_grid_for((V + 1) / 2, n_cu, kGemvWgsPerCu), 4, 4 /* log2(pt) */, 1e-5f, 0.088f};
   DevState st{};
   st.t = 10; st.last_token = 5; st.full = 1; st.draft = 7; st.n_out = 0; st.target = 1 << 30;
   CK(hipMemcpy(ws, &st, sizeof st, hipMemcpyHostToDevice));

@@ -37,9 +37,12 @@ inline int gemv_grid_for(int n_tasks, int n_cu, int wgs_per_cu) {
 template <typename WT>
 __device__ __forceinline__ WT *kv_row(const Common &c, const int32_t *ptab, int layer, int pos, int kvh, int which) {
   const Dims &m = c.dm;
-  const int page = ptab[pos / m.page_tokens];
-  const int slot = pos % m.page_tokens;
-  size_t idx = ((((size_t)layer * m.n_pages + page) * m.n_kv + kvh) * 2 + which) * m.page_tokens + slot;
+  // page sizes are powers of two: shifts instead of a division per row; the block index fits 32 bits
+  // (layers x pages x KV heads x 2 < 2^31 at any supported size)
+  const int page = ptab[pos >> m.page_shift];
+  const int slot = pos & (m.page_tokens - 1);
+  const uint32_t block = (((uint32_t)layer * m.n_pages + page) * m.n_kv + kvh) * 2 + which;
+  const size_t idx = ((size_t)block << m.page_shift) + slot;
   return (WT *)c.kv_pool + idx * m.hd;
 }
 

@@ -97,7 +97,7 @@ int main(int argc, char **argv) {
   c.kv_pool = kv;
   c.dm = Dims{};
   c.dm.d = d; c.dm.n_h = n_h; c.dm.n_kv = n_kv; c.dm.hd = hd; c.dm.f = f; c.dm.L = 1; c.dm.E = 1;
-  c.dm.max_seq = mpad; c.dm.page_tokens = pt; c.dm.n_pages = n_pages; c.dm.eps = 1e-5f; c.dm.qscale = 0.0883883f;
+  c.dm.max_seq = mpad; c.dm.page_tokens = pt; c.dm.page_shift = 4; c.dm.n_pages = n_pages; c.dm.eps = 1e-5f; c.dm.qscale = 0.0883883f;
 
   CK(pf_prepare());
   hipEvent_t e0, e1;
