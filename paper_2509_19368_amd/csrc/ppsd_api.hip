@@ -922,6 +922,14 @@ int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *b, ppsd_ctx **
       return cleanup(fail(PPSD_EHIP, "cannot query the device's compute-unit count"));
     x->n_cu = n_cu;
     m.head_blocks = x->gemv_grid((cfg->vocab + 1) / 2);
+    if (cfg->tune_attn_split == 0 && cfg->max_seq > kOneSplitUpTo) {
+      // long contexts: as many splits as fill the chip (one attention workgroup is resident per compute
+      // unit), a block of 128 positions per split at least
+      int fill = n_cu / cfg->n_kv_heads;
+      if (fill > cfg->max_seq / 128) fill = cfg->max_seq / 128;
+      if (fill > kMaxSplits) fill = kMaxSplits;
+      if (fill > x->lay.n_splits) { x->lay.n_splits = fill; m.n_splits = fill; }
+    }
   }
 #define HIP_TRY_X(expr)                                                                                   \
   do {                                                                                                    \

@@ -164,19 +164,27 @@ __device__ __forceinline__ void attn_unit(const Common &c, const int32_t *ptab, 
     }
   };
   auto process = [&](int p0, const uint4 (&kk)[U], const uint4 (&vv)[U]) {
+    // positions p0 + u * GPB; a whole u-slice of the split's last block may lie behind its end (the same for
+    // every group of the workgroup): its arithmetic is skipped, the result is the same
+    const int b0 = p0 - grp;
     float sc[G][U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float kf[N];
-      Pack<WT>::unpack(kk[u], kf);
-      const bool ok = p0 + u * GPB < end;
+      if (b0 + u * GPB < end) {
+        float kf[N];
+        Pack<WT>::unpack(kk[u], kf);
+        const bool ok = p0 + u * GPB < end;
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float sdot = 0.f;
+        for (int g = 0; g < G; ++g) {
+          float sdot = 0.f;
 #pragma unroll
-        for (int k = 0; k < N; ++k) sdot = fmaf(qr[g][k], kf[k], sdot);
-        sdot = group_sum<GS>(sdot);
-        sc[g][u] = ok ? sdot : kNegBig;
+          for (int k = 0; k < N; ++k) sdot = fmaf(qr[g][k], kf[k], sdot);
+          sdot = group_sum<GS>(sdot);
+          sc[g][u] = ok ? sdot : kNegBig;
+        }
+      } else {
+#pragma unroll
+        for (int g = 0; g < G; ++g) sc[g][u] = kNegBig;
       }
     }
 #pragma unroll
@@ -194,13 +202,15 @@ __device__ __forceinline__ void attn_unit(const Common &c, const int32_t *ptab, 
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      float vf[N];
-      Pack<WT>::unpack(vv[u], vf);
+      if (b0 + u * GPB < end) {
+        float vf[N];
+        Pack<WT>::unpack(vv[u], vf);
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        l[g] += sc[g][u];
+        for (int g = 0; g < G; ++g) {
+          l[g] += sc[g][u];
 #pragma unroll
-        for (int k = 0; k < N; ++k) acc[g][k] = fmaf(sc[g][u], vf[k], acc[g][k]);
+          for (int k = 0; k < N; ++k) acc[g][k] = fmaf(sc[g][u], vf[k], acc[g][k]);
+        }
       }
     }
   };
