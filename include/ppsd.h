@@ -112,7 +112,8 @@ typedef struct {
                               1..4; 0 = the library's defaults (3; 2 for gate/up) */
   int32_t tune_attn_split; /* launch tuning: positions of capacity (max_seq) per attention split, >= 64; the
                               number of splits is capped at 64.  0 = the library's default (one split up to
-                              512 positions, beyond that one per 512) */
+                              512 positions; beyond that one per 512 or, if that is more, one per compute unit
+                              and KV head, with at least 128 positions of capacity each) */
   int32_t eesd_gamma;      /* PPSD_MODE_EESD: drafts per round, 1..4; 0 = default (3).  (gamma + 1) * d_model
                               floats must fit the LDS of a compute unit (150 KiB) */
   int32_t exit_block;      /* 1: the early-exit head is one more transformer layer of the model's own structure
