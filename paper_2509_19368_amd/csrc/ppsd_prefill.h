@@ -16,7 +16,8 @@
 // (A high, A low, W) tiles; a row is 64 bytes and its four 16-byte vectors are stored at position
 // v ^ ((row / 4) % 4), which makes both the staging stores (4 rows x 4 vectors per 16 lanes) and the
 // MFMA operand loads (16 rows, one vector) hit every bank once.  The next tiles travel in registers
-// while the current one is multiplied, one barrier per K step.  Few output tiles
+// while the current one is multiplied; one barrier per K step in the small tile, one per half step in
+// the big one, whose two halves run half a step apart (see the kernel).  Few output tiles
 // (short prompts) are split along K over several workgroups, whose partial tiles a second kernel
 // adds in a fixed order before the epilogue, so results do not depend on timing.
 // Workgroup ids map to tiles so that all tiles of one weight row block run on one XCD (ids go
