@@ -228,10 +228,10 @@ struct ppsd_ctx {
   // persistent engine
   int n_cu = 0;                         // compute units of the device
   int n_wg = 0;
-  // grid of a weight-streaming kernel with n_tasks row-pair tasks: one wave per task up to a few
-  // workgroups per CU, then the waves loop
   // bytes of LDS a staged input vector of C elements takes (padded to whole column blocks)
   size_t xs_bytes(int C) const { return 4ull * xs_floats(cfg.dtype == PPSD_FP32 ? 4 : 2, C); }
+  // grid of a weight-streaming kernel with n_tasks row-pair tasks: one wave per task up to a few
+  // workgroups per CU, then the waves loop
   int gemv_grid(int n_tasks, int wgs_per_cu = kGemvWgsPerCu) const {
     return gemv_grid_for(n_tasks, n_cu, cfg.tune_wgs_per_cu > 0 ? cfg.tune_wgs_per_cu : wgs_per_cu);
   }
@@ -778,6 +778,7 @@ void pf_launch_attn(ppsd_ctx *x, int l, int c0, int nv, const float *Q, float *A
 
 int prefill_mfma(ppsd_ctx *x, int n_prompt) {
   const ppsd_config &c = x->cfg;
+  if (c.dtype != PPSD_BF16) return fail(PPSD_ESTATE, "matrix-core prefill is bf16 only");
   const int d = c.d_model, f = c.d_ffn, nq = c.n_heads * c.head_dim;
   const int qkv_cols = (c.n_heads + 2 * c.n_kv_heads) * c.head_dim, G = c.n_heads / c.n_kv_heads;
   float *X = at<float>(x, x->lay.pf_x), *Q = at<float>(x, x->lay.pf_q), *AO = at<float>(x, x->lay.pf_ao);
@@ -819,7 +820,6 @@ int prefill_mfma(ppsd_ctx *x, int n_prompt) {
   // the LM head and the commit run as for the last position of the looped prefill
   hipLaunchKernelGGL(k_begin_prefill, dim3(1), dim3(64), 0, x->sA, at<DevState>(x, x->lay.state), n_prompt, n_prompt - 1);
   Launcher A{x, x->sA, false};
-  if (c.dtype == PPSD_FP32) return fail(PPSD_ESTATE, "matrix-core prefill is bf16 only");
   launch_head<bf16_t>(A, kPrefill, kXDraft, true);
   launch_commit(A, 3);
   if (A.err != hipSuccess) return fail(PPSD_EHIP, "prefill head: %s", hipGetErrorString(A.err));
@@ -1217,18 +1217,21 @@ int ppsd_trace_read(ppsd_ctx *x, int32_t n_phases, uint64_t *out) {
 int ppsd_hbm_read_probe(const void *buf, size_t bytes, void *stream, int32_t iters, float *avg_ms) {
   if (!buf || !avg_ms || iters < 1 || bytes < 16 || (uintptr_t)buf % 16) return fail(PPSD_EARG, "bad probe argument");
   hipStream_t s = (hipStream_t)stream;
-  hipEvent_t e0, e1;
-  HIP_TRY(hipEventCreate(&e0));
-  HIP_TRY(hipEventCreate(&e1));
-  uint32_t *sink = nullptr;   // the probe never writes in practice, but needs a valid target
-  static uint32_t *s_sink = nullptr;
+  static uint32_t *s_sink = nullptr;   // the probe never writes in practice, but needs a valid target
   if (!s_sink) HIP_TRY(hipHostMalloc((void **)&s_sink, 64, hipHostMallocDefault));
-  sink = s_sink;
+  uint32_t *sink = s_sink;
   const size_t n_vec = bytes / 16;
   int dev = 0, n_cu = 0;
   HIP_TRY(hipGetDevice(&dev));
   HIP_TRY(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev));
   const int blocks = n_cu;                  // one resident workgroup per compute unit
+  struct Events {                           // destroyed on every return path
+    hipEvent_t a = nullptr, b = nullptr;
+    ~Events() { if (a) (void)hipEventDestroy(a); if (b) (void)hipEventDestroy(b); }
+  } ev;
+  HIP_TRY(hipEventCreate(&ev.a));
+  HIP_TRY(hipEventCreate(&ev.b));
+  hipEvent_t e0 = ev.a, e1 = ev.b;
   hipLaunchKernelGGL(k_read_probe, dim3(blocks), dim3(kGBlock), 0, s, (const uint4 *)buf, n_vec, sink);   // warm-up
   HIP_TRY(hipEventRecord(e0, s));
   for (int k = 0; k < iters; ++k) hipLaunchKernelGGL(k_read_probe, dim3(blocks), dim3(kGBlock), 0, s, (const uint4 *)buf, n_vec, sink);
@@ -1237,8 +1240,6 @@ int ppsd_hbm_read_probe(const void *buf, size_t bytes, void *stream, int32_t ite
   HIP_TRY(hipGetLastError());
   float ms = 0.f;
   HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
-  (void)hipEventDestroy(e0);
-  (void)hipEventDestroy(e1);
   *avg_ms = ms / iters;
   return PPSD_OK;
 }
