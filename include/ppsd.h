@@ -84,7 +84,7 @@ typedef struct {
   int32_t exit_layer;      /* E: the draft model is layers 1..E; 1 <= E < N */
   int32_t d_model;
   int32_t n_heads;         /* query heads */
-  int32_t n_kv_heads;      /* n_heads / n_kv_heads in {1,2,4,8} */
+  int32_t n_kv_heads;      /* n_heads / n_kv_heads in {1,2,4} */
   int32_t head_dim;        /* 64 or 128 */
   int32_t d_ffn;
   int32_t vocab;

@@ -16,6 +16,14 @@ namespace ppsd {
 constexpr int kMaxBatch = 5;          // gamma + 1
 constexpr int kMaxGamma = kMaxBatch - 1;
 
+// The staged vectors are written and read as whole float4 (the buffer is 16-byte aligned, a vector's
+// pitch ldx and every position a multiple of 4 floats): indexing in float4 units keeps every access one
+// 16-byte LDS instruction wherever the kernel is compiled.  Through a float pointer plus b * ldx the
+// compiler had split the reads of the slab-walking projection into 4-byte pairs in the library build
+// (38.5 us per launch at the 7B shape against 26.5 us with 16-byte reads).
+__device__ __forceinline__ float4 *xs_vec(float *xs) { return reinterpret_cast<float4 *>(xs); }
+__device__ __forceinline__ const float4 *xs_vec(const float *xs) { return reinterpret_cast<const float4 *>(xs); }
+
 // RMSNorm of B vectors (vector b at x0 + b * d) into LDS xs[b * ldx + i]; same arithmetic per vector
 // as NormStage.
 template <typename WT, int BLOCK, int B>
@@ -53,8 +61,8 @@ struct BatchNormStage {
       for (int e = 0; e < kNormPer; ++e) {
         const int i = 4 * (threadIdx.x + e * BLOCK);
         if (i < d)
-          *(float4 *)(xs + (size_t)b * ldx + xs_pos<WT>(i)) = make_float4(xv[b][e].x * rs * gv[e].x, xv[b][e].y * rs * gv[e].y,
-                                                              xv[b][e].z * rs * gv[e].z, xv[b][e].w * rs * gv[e].w);
+          xs_vec(xs)[b * (ldx >> 2) + (xs_pos<WT>(i) >> 2)] = make_float4(xv[b][e].x * rs * gv[e].x, xv[b][e].y * rs * gv[e].y,
+                                                                           xv[b][e].z * rs * gv[e].z, xv[b][e].w * rs * gv[e].w);
       }
     }
     __syncthreads();
@@ -81,7 +89,7 @@ __device__ __forceinline__ void trip_consume_b(const Trip<WT, kTripRows, kTripBl
         float x[N];
 #pragma unroll
         for (int q = 0; q < N / 4; ++q) {
-          const float4 v = *(const float4 *)(xs + (size_t)b * ldx + (cb + k) * kStride + q * (4 * kWave) + lane * 4);
+          const float4 v = xs_vec(xs)[b * (ldx >> 2) + (cb + k) * (kStride >> 2) + q * kWave + lane];
           x[4 * q] = v.x; x[4 * q + 1] = v.y; x[4 * q + 2] = v.z; x[4 * q + 3] = v.w;
         }
 #pragma unroll
@@ -233,7 +241,7 @@ __global__ __launch_bounds__(kGBlock) void k_proj_resid_b(Common c, const float 
 #pragma unroll
   for (int b = 0; b < B; ++b)
     for (int i = 4 * threadIdx.x; i < Cs; i += 4 * kGBlock)
-      *(float4 *)(xs + (size_t)b * ldx + xs_pos<WT>(i)) = *(const float4 *)(vin + (size_t)b * C_total + c0 + i);
+      xs_vec(xs)[b * (ldx >> 2) + (xs_pos<WT>(i) >> 2)] = *(const float4 *)(vin + (size_t)b * C_total + c0 + i);
   __syncthreads();
   const int d = c.dm.d;
   const float *resid = c.xbuf + (size_t)resid_slot0 * d;
@@ -279,7 +287,7 @@ __global__ __launch_bounds__(kGBlock) void k_proj_resid_bs(Common c, const float
 #pragma unroll
     for (int b = 0; b < B; ++b)
       for (int i = 4 * threadIdx.x; i < w; i += 4 * kGBlock)
-        *(float4 *)(xs + (size_t)b * ldx + xs_pos<WT>(i)) = *(const float4 *)(vin + (size_t)b * C + c0 + i);
+        xs_vec(xs)[b * (ldx >> 2) + (xs_pos<WT>(i) >> 2)] = *(const float4 *)(vin + (size_t)b * C + c0 + i);
     __syncthreads();
     if (mine) {
       for (int cb = 0; cb < nblk; cb += KB) {
@@ -293,7 +301,7 @@ __global__ __launch_bounds__(kGBlock) void k_proj_resid_bs(Common c, const float
               float x[N];
 #pragma unroll
               for (int q = 0; q < N / 4; ++q) {
-                const float4 v = *(const float4 *)(xs + (size_t)b * ldx + (cb + k) * kStride + q * (4 * kWave) + lane * 4);
+                const float4 v = xs_vec(xs)[b * (ldx >> 2) + (cb + k) * (kStride >> 2) + q * kWave + lane];
                 x[4 * q] = v.x; x[4 * q + 1] = v.y; x[4 * q + 2] = v.z; x[4 * q + 3] = v.w;
               }
 #pragma unroll

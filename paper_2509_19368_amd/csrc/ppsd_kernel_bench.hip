@@ -5,9 +5,11 @@
 // Also the reference dispatches for scaling rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings:
 // k_read_probe over 1 GiB and a 1 GiB device-to-device copy.
 //
-// usage: ppsd_kernel_bench [d_model d_ffn vocab n_heads n_kv_heads head_dim [iters [context [splits]]]]   (bf16 storage)
-// With a context length, the decode attention kernel is timed too: one query over `context` cached positions,
+// usage: ppsd_kernel_bench [d_model d_ffn vocab n_heads n_kv_heads head_dim [iters [context [splits [passes]]]]]   (bf16 storage)
+// With a context length > 0, the decode attention kernel is timed too: one query over `context` cached positions,
 // 32 layers' worth of K/V pages visited in turn (so no launch finds its rows in a cache), head_dim 128 only.
+// With passes > 0, the four batched projections are also launched in the order of the verify pass (24 layers per
+// pass), so that a kernel trace of this program shows each kernel between its real neighbours.
 #include <cstdio>
 #include <cstdlib>
 
@@ -27,12 +29,33 @@ __global__ void k_copy16(const uint4 *src, uint4 *dst, size_t n) {
   for (; i < n; i += stride) dst[i] = src[i];
 }
 
+// bf16 values spread over (-0.04, 0.04) from a hash of the index: weights whose bits vary like a model's
+__global__ void k_fill_bf16(bf16_t *w, size_t n, unsigned seed) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    unsigned long long z = (i + seed) * 0x9E3779B97F4A7C15ull;
+    z ^= z >> 29; z *= 0xBF58476D1CE4E5B9ull; z ^= z >> 32;
+    w[i] = float_to_bf16_rne(((int)(z & 0xffff) - 32768) * (0.04f / 32768.f));
+  }
+}
+__global__ void k_fill_f32(float *p, size_t n, unsigned seed) {
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (; i < n; i += stride) {
+    unsigned long long z = (i + seed) * 0x9E3779B97F4A7C15ull;
+    z ^= z >> 29; z *= 0xBF58476D1CE4E5B9ull; z ^= z >> 32;
+    p[i] = ((int)(z & 0xffff) - 32768) * (1.0f / 32768.f);
+  }
+}
+
 int main(int argc, char **argv) {
   int d = 4096, f = 11008, V = 32000, n_h = 32, n_kv = 32, hd = 128, iters = 30;
   if (argc >= 7) { d = atoi(argv[1]); f = atoi(argv[2]); V = atoi(argv[3]); n_h = atoi(argv[4]); n_kv = atoi(argv[5]); hd = atoi(argv[6]); }
   if (argc >= 8) iters = atoi(argv[7]);
   const int ctx = argc >= 9 ? atoi(argv[8]) : 0;
   const int ctx_splits = argc >= 10 ? atoi(argv[9]) : 0;
+  const int seq_reps = argc >= 11 ? atoi(argv[10]) : 0;
   const int nq = n_h * hd;
   if (d % 8 || f % 8 || d > 8192 || f > 16384 || nq > 16384 || (hd != 64 && hd != 128)) { printf("unsupported shape\n"); return 2; }
   int dev = 0, n_cu = 0;
@@ -41,9 +64,17 @@ int main(int argc, char **argv) {
   const size_t bytes = (size_t)6 << 30;
   char *W, *ws;
   CK(hipMalloc(&W, bytes));
-  CK(hipMemset(W, 0x3c, bytes));            // bf16 0x3c3c = 0.0115: finite products
+  const bool varied = getenv("PPSD_BENCH_CONSTANT_DATA") == nullptr;
+  if (varied) hipLaunchKernelGGL(k_fill_bf16, dim3(8192), dim3(256), 0, 0, (bf16_t *)W, bytes / 2, 11u);
+  else CK(hipMemset(W, 0x3c, bytes));      // bf16 0x3c3c = 0.0115: finite products
   CK(hipMalloc(&ws, (size_t)64 << 20));
   CK(hipMemset(ws, 0, (size_t)64 << 20));
+  if (varied) {                             // activations, gains and staged inputs: values in (-1, 1)
+    hipLaunchKernelGGL(k_fill_f32, dim3(1024), dim3(256), 0, 0, (float *)(ws + (1 << 20)), (size_t)(1 << 20) / 4, 3u);
+    hipLaunchKernelGGL(k_fill_f32, dim3(1024), dim3(256), 0, 0, (float *)(ws + (5 << 20)), (size_t)(3 << 20) / 4, 5u);
+    hipLaunchKernelGGL(k_fill_f32, dim3(1024), dim3(256), 0, 0, (float *)(ws + (44 << 20)), (size_t)(4 << 20) / 4, 7u);
+  }
+  CK(hipDeviceSynchronize());
   Common c{};
   c.st = (DevState *)ws;
   c.prompt = (int32_t *)(ws + 4096);
@@ -194,5 +225,43 @@ int main(int argc, char **argv) {
                        candb, (float *)nullptr, (float *)nullptr);
   });
   CK(hipGetLastError());
+
+  // the batched kernels in the order of the verify pass (QKV, o_proj, gate/up, down per layer), every launch
+  // on fresh weights: what a kernel costs between its real neighbours, for a kernel trace of this program
+  if (seq_reps > 0) {
+    const size_t per_layer = ((size_t)qkv_rows * d + (size_t)d * nq + (size_t)2 * f * d + (size_t)d * f) * 2;
+    const int seq_layers = 24, parts = (int)(bytes / per_layer);
+    const size_t lds_o = (size_t)B * xs_floats(2, nq) * 4;
+    const int n_slabs = (int)(((size_t)B * f * 4 + 65535) / 65536);
+    const int Cs = ((f + n_slabs - 1) / n_slabs + 511) / 512 * 512;
+    if (Cs >= f || lds_o > 65536) { printf("sequence skipped: it covers shapes whose down-projection is walked in slabs\n"); return 0; }
+    int turn = 0;
+    auto layer = [&]() {
+      const bf16_t *w = (const bf16_t *)(W + (size_t)(turn++ % parts) * per_layer);
+      hipLaunchKernelGGL((k_qkv_b<bf16_t, B>), dim3(bgrid(qkv_rows / 2, lds_d, kGemvWgsPerCu)), dim3(kGBlock), lds_d, 0, c, 3,
+                         (int)kXBatchInSlot0, gain, w, vb);
+      w += (size_t)qkv_rows * d;
+      hipLaunchKernelGGL((k_proj_resid_b<bf16_t, B>), dim3(bgrid((d + 1) / 2, lds_o, kGemvWgsPerCu)), dim3(kGBlock), lds_o, 0, c,
+                         (const float *)vb, nq, 0, nq, w, d, (int)kXBatchWorkSlot0, (int)kXBatchWorkSlot0);
+      w += (size_t)d * nq;
+      hipLaunchKernelGGL((k_gate_up_b<bf16_t, B>), dim3(bgrid(f, lds_d, kGateUpWgsPerCu)), dim3(kGBlock), lds_d, 0, c,
+                         (int)kXBatchWorkSlot0, gain, w, mb);
+      w += (size_t)2 * f * d;
+      hipLaunchKernelGGL((k_proj_resid_bs<bf16_t, B>), dim3((d + kGWaves - 1) / kGWaves), dim3(kGBlock), (size_t)B * xs_floats(2, Cs) * 4, 0, c,
+                         (const float *)mb, f, Cs, w, d, (int)kXBatchWorkSlot0, (int)kXBatchWorkSlot0);
+    };
+    for (int l = 0; l < seq_layers; ++l) layer();
+    CK(hipDeviceSynchronize());
+    CK(hipEventRecord(e0));
+    for (int r = 0; r < seq_reps; ++r)
+      for (int l = 0; l < seq_layers; ++l) layer();
+    CK(hipEventRecord(e1));
+    CK(hipEventSynchronize(e1));
+    float ms = 0.f;
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    printf("verify-pass sequence (4 launches per layer, %d layers, %d passes): %.2f us per layer\n", seq_layers, seq_reps,
+           ms * 1e3 / seq_reps / seq_layers);
+    CK(hipGetLastError());
+  }
   return 0;
 }
