@@ -15,6 +15,7 @@ namespace ppsd {
 
 constexpr int kMaxBatch = 5;          // gamma + 1
 constexpr int kMaxGamma = kMaxBatch - 1;
+constexpr int kBatchTripBlocks = kTripBlocks;   // column blocks per trip, as in the single-token kernels (4 per trip: 10-20 % slower)
 
 // The staged vectors are written and read as whole float4 (the buffer is 16-byte aligned, a vector's
 // pitch ldx and every position a multiple of 4 floats): indexing in float4 units keeps every access one
@@ -43,20 +44,36 @@ struct BatchNormStage {
       }
     }
   }
+  // red: B * BLOCK / 64 floats of LDS.  The B sums of squares are reduced together (one pair of barriers for
+  // all of them), each in the order wg_sum takes: wave butterfly, then the waves' sums added in wave order.
   __device__ __forceinline__ void finish(int d, float eps, float *xs, int ldx, float *red) {
+    constexpr int W = BLOCK / kWave;
+    float ss[B];
 #pragma unroll
     for (int b = 0; b < B; ++b) {
-      float ss = 0.f;
+      ss[b] = 0.f;
 #pragma unroll
       for (int e = 0; e < kNormPer; ++e) {
         const int i = 4 * (threadIdx.x + e * BLOCK);
         if (i < d) {
-          ss = fmaf(xv[b][e].x, xv[b][e].x, ss); ss = fmaf(xv[b][e].y, xv[b][e].y, ss);
-          ss = fmaf(xv[b][e].z, xv[b][e].z, ss); ss = fmaf(xv[b][e].w, xv[b][e].w, ss);
+          ss[b] = fmaf(xv[b][e].x, xv[b][e].x, ss[b]); ss[b] = fmaf(xv[b][e].y, xv[b][e].y, ss[b]);
+          ss[b] = fmaf(xv[b][e].z, xv[b][e].z, ss[b]); ss[b] = fmaf(xv[b][e].w, xv[b][e].w, ss[b]);
         }
       }
-      ss = wg_sum<BLOCK>(ss, red);
-      const float rs = 1.0f / sqrtf(ss / (float)d + eps);
+      ss[b] = wave_sum(ss[b]);
+    }
+    __syncthreads();   // red may still be read from a previous use
+    if ((threadIdx.x & 63) == 0) {
+#pragma unroll
+      for (int b = 0; b < B; ++b) red[b * W + (threadIdx.x >> 6)] = ss[b];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+      float tot = 0.f;
+#pragma unroll
+      for (int w = 0; w < W; ++w) tot += red[b * W + w];
+      const float rs = 1.0f / sqrtf(tot / (float)d + eps);
 #pragma unroll
       for (int e = 0; e < kNormPer; ++e) {
         const int i = 4 * (threadIdx.x + e * BLOCK);
@@ -72,18 +89,18 @@ struct BatchNormStage {
 // One trip of weights against B staged vectors.  Per (row, vector) the products are added in the
 // same order as in trip_consume.
 template <typename WT, int B>
-__device__ __forceinline__ void trip_consume_b(const Trip<WT, kTripRows, kTripBlocks> &t, const float *xs, int ldx,
+__device__ __forceinline__ void trip_consume_b(const Trip<WT, kTripRows, kBatchTripBlocks> &t, const float *xs, int ldx,
                                                int cb, int C, float (&acc)[kTripRows][B]) {
   constexpr int N = Pack<WT>::N;
   constexpr int kStride = kWave * N;
   const int lane = threadIdx.x & 63;
 #pragma unroll
-  for (int k = 0; k < kTripBlocks; ++k) {
+  for (int k = 0; k < kBatchTripBlocks; ++k) {
     const int c = (cb + k) * kStride + lane * N;
     if (c < C) {
       float w0[N], w1[N];
-      Pack<WT>::unpack(t.u[0 * kTripBlocks + k], w0);
-      Pack<WT>::unpack(t.u[1 * kTripBlocks + k], w1);
+      Pack<WT>::unpack(t.u[0 * kBatchTripBlocks + k], w0);
+      Pack<WT>::unpack(t.u[1 * kBatchTripBlocks + k], w1);
 #pragma unroll
       for (int b = 0; b < B; ++b) {
         float x[N];
@@ -103,7 +120,7 @@ __device__ __forceinline__ void trip_consume_b(const Trip<WT, kTripRows, kTripBl
 
 // gemv_tasks with B right-hand sides: epi(task, s) with s[row][vector].
 template <typename WT, int B, typename RowsFn, typename EpiFn>
-__device__ __forceinline__ void gemv_tasks_b(Trip<WT, kTripRows, kTripBlocks> &trip, const WT *(&rows)[kTripRows],
+__device__ __forceinline__ void gemv_tasks_b(Trip<WT, kTripRows, kBatchTripBlocks> &trip, const WT *(&rows)[kTripRows],
                                              int task, int n_tasks, int tw, int C, const float *xs, int ldx,
                                              RowsFn &&set_rows, EpiFn &&epi) {
   const int nblk = col_blocks<WT>(C);
@@ -114,13 +131,13 @@ __device__ __forceinline__ void gemv_tasks_b(Trip<WT, kTripRows, kTripBlocks> &t
 #pragma unroll
       for (int b = 0; b < B; ++b) acc[r][b] = 0.f;
     const int next = task + tw;
-    for (int cb = 0; cb < nblk; cb += kTripBlocks) {
+    for (int cb = 0; cb < nblk; cb += kBatchTripBlocks) {
       trip_consume_b<WT, B>(trip, xs, ldx, cb, C, acc);
-      if (cb + kTripBlocks < nblk) {
-        trip_load<WT, kTripRows, kTripBlocks>(trip, rows, cb + kTripBlocks, nblk, C);
+      if (cb + kBatchTripBlocks < nblk) {
+        trip_load<WT, kTripRows, kBatchTripBlocks>(trip, rows, cb + kBatchTripBlocks, nblk, C);
       } else if (next < n_tasks) {
         set_rows(next);
-        trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, nblk, C);
+        trip_load<WT, kTripRows, kBatchTripBlocks>(trip, rows, 0, nblk, C);
       }
     }
     float s[kTripRows][B];
@@ -140,7 +157,7 @@ template <typename WT, int B>
 __global__ __launch_bounds__(kGBlock) void k_qkv_b(Common c, int layer, int x_slot0, const float *gain, const WT *wqkv,
                                                    float *qout) {
   extern __shared__ __align__(16) float xs[];
-  __shared__ float red[kGWaves];
+  __shared__ float red[kGWaves * B];
   const Dims &m = c.dm;
   const int d = m.d;
   BatchNormStage<WT, kGBlock, B> in;
@@ -158,8 +175,8 @@ __global__ __launch_bounds__(kGBlock) void k_qkv_b(Common c, int layer, int x_sl
     rows[0] = wqkv + (size_t)(head * m.hd + i) * d;
     rows[1] = rows[0] + (size_t)half * d;
   };
-  Trip<WT, kTripRows, kTripBlocks> trip;
-  if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
+  Trip<WT, kTripRows, kBatchTripBlocks> trip;
+  if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kBatchTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
   const int ldx = xs_floats((int)sizeof(WT), d);
   in.finish(d, m.eps, xs, ldx, red);
   gemv_tasks_b<WT, B>(trip, rows, gw, n_tasks, tw, d, xs, ldx, set_rows, [&](int task, float (&s)[kTripRows][B]) {
@@ -235,8 +252,8 @@ __global__ __launch_bounds__(kGBlock) void k_proj_resid_b(Common c, const float 
     rows[0] = W + (size_t)(2 * task) * C_total + c0;
     rows[1] = W + (size_t)min(2 * task + 1, n_rows - 1) * C_total + c0;
   };
-  Trip<WT, kTripRows, kTripBlocks> trip;
-  if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(Cs), Cs); }
+  Trip<WT, kTripRows, kBatchTripBlocks> trip;
+  if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kBatchTripBlocks>(trip, rows, 0, col_blocks<WT>(Cs), Cs); }
   const int ldx = xs_floats((int)sizeof(WT), Cs);
 #pragma unroll
   for (int b = 0; b < B; ++b)
@@ -335,7 +352,7 @@ template <typename WT, int B>
 __global__ __launch_bounds__(kGBlock) void k_gate_up_b(Common c, int x_slot0, const float *gain, const WT *wgu,
                                                        float *mout) {
   extern __shared__ __align__(16) float xs[];
-  __shared__ float red[kGWaves];
+  __shared__ float red[kGWaves * B];
   const Dims &m = c.dm;
   const int d = m.d, f = m.f;
   BatchNormStage<WT, kGBlock, B> in;
@@ -349,8 +366,8 @@ __global__ __launch_bounds__(kGBlock) void k_gate_up_b(Common c, int x_slot0, co
     rows[0] = wgu + (size_t)task * d;
     rows[1] = wgu + (size_t)(f + task) * d;
   };
-  Trip<WT, kTripRows, kTripBlocks> trip;
-  if (gw < f) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
+  Trip<WT, kTripRows, kBatchTripBlocks> trip;
+  if (gw < f) { set_rows(gw); trip_load<WT, kTripRows, kBatchTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
   const int ldx = xs_floats((int)sizeof(WT), d);
   in.finish(d, m.eps, xs, ldx, red);
   gemv_tasks_b<WT, B>(trip, rows, gw, f, tw, d, xs, ldx, set_rows, [&](int task, float (&s)[kTripRows][B]) {
@@ -370,7 +387,7 @@ template <typename WT, int B>
 __global__ __launch_bounds__(kGBlock) void k_head_b(Common c, int x_slot0, const float *gain, const WT *W, float2 *cand,
                                                     float *logits_log, float *logits_out) {
   extern __shared__ __align__(16) float xs[];
-  __shared__ float red[kGWaves];
+  __shared__ float red[kGWaves * B];
   __shared__ float bv[kGWaves][B];
   __shared__ int bi[kGWaves][B];
   const Dims &m = c.dm;
@@ -387,8 +404,8 @@ __global__ __launch_bounds__(kGBlock) void k_head_b(Common c, int x_slot0, const
     rows[0] = W + (size_t)(2 * task) * d;
     rows[1] = W + (size_t)min(2 * task + 1, V - 1) * d;
   };
-  Trip<WT, kTripRows, kTripBlocks> trip;
-  if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
+  Trip<WT, kTripRows, kBatchTripBlocks> trip;
+  if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kBatchTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
   const int ldx = xs_floats((int)sizeof(WT), d);
   in.finish(d, m.eps, xs, ldx, red);
   const int row0 = c.st->gen_count;
