@@ -151,7 +151,7 @@ __device__ __forceinline__ void attn_unit(const Common &c, const int32_t *ptab, 
   // A block = U positions per group (U * GPB per workgroup).  The next block's K/V rows are loaded
   // before the current block is used, so a wave's arithmetic runs under its own loads; within a
   // block the running maximum is raised once and the accumulators rescaled once.
-  constexpr int U = 4;
+  constexpr int U = 2;   // (4: a split of 272 positions pads to 384 instead of 320, and four query heads per KV head need 158 VGPRs instead of 124)
   uint4 ku[U], vu[U], kn[U], vn[U];
   auto load_block = [&](int p0, uint4 (&kk)[U], uint4 (&vv)[U]) {
 #pragma unroll
