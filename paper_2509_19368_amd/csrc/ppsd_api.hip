@@ -43,8 +43,9 @@ constexpr size_t kAlign = 256;
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
 constexpr int kOneSplitUpTo = 512;     // attention: a single split up to this capacity (max_seq)
-constexpr int kSplitPositions = 512;   // beyond it, one split per this many positions of capacity (measured at
-                                       // 8192 positions, 8 KV heads: 512 -> 25 us, 256 -> 26 us, 128 -> 28.5 us)
+constexpr int kSplitPositions = 512;   // beyond it, one split per this many positions of capacity at least; at load
+                                       // the count is raised until the attention workgroups fill the chip once
+                                       // (8704 positions, 8 KV heads: 24 / 32 / 40 / 56 splits -> 19.0 / 18.3 / 24.1 / 21.2 us)
 constexpr int kMaxSplits = kMaxAttnSplits;   // attention splits along the sequence (both engines)
 constexpr int kDefaultGamma = 3;       // drafts per round of PPSD_MODE_EESD
 constexpr size_t kBatchLdsMax = 150 * 1024;   // staged input vectors of a batched kernel: at most this much LDS
