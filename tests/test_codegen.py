@@ -92,3 +92,17 @@ def test_prefill_kernels_run_on_the_matrix_cores_from_16_byte_lds_reads(kernels)
             assert c["v_mfma_f32_32x32x16_bf16"] >= 16, (name, dict(c))
             assert c["ds_read_b128"] >= 32, (name, dict(c))
             assert c["ds_read2_b32"] + c["ds_read2_b64"] + c["ds_read_b32"] == 0, (name, dict(c))
+
+
+def test_register_budgets_keep_the_intended_number_of_workgroups_resident(kernels):
+    """A CU holds 512 VGPRs per SIMD lane: a 512-thread workgroup puts two waves on every SIMD, so three
+    resident workgroups need at most 84 registers per wave, two need at most 128, one at most 256."""
+    budgets = (("k_qkvI", 84), ("k_proj_residI", 84), ("k_gate_upI", 84), ("k_headI", 84),      # three per CU
+               ("k_qkv_bI", 128), ("k_gate_up_bI", 128), ("k_head_bI", 128), ("k_proj_resid_bI", 128),
+               ("k_proj_resid_bsI", 128), ("k_attnI", 128), ("k_attn_bI", 128),                  # two per CU
+               ("k_pf_gemmI", 256), ("k_pf_flashI", 256))
+    for frag, limit in budgets:
+        for name, c in _pick(kernels, frag).items():
+            # five staged vectors leave room for one workgroup per CU only (LDS), whatever the registers
+            lim = 256 if ("_bI" in frag or "_bsI" in frag) and "Li5E" in name and "k_attn" not in frag else limit
+            assert 0 < c["meta_next_free_vgpr"] <= lim, (name, c["meta_next_free_vgpr"], lim)
