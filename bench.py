@@ -185,6 +185,7 @@ def main():
     ap.add_argument("--engine", default="streams", choices=["streams", "persistent"])
     ap.add_argument("--pipeline-streams", type=int, default=0, help="streams of the pipeline mode (0 = library default)")
     ap.add_argument("--wgs-per-cu", type=int, default=0, help="launch tuning of the weight-streaming kernels (0 = defaults)")
+    ap.add_argument("--draft-share", type=int, default=0, help="launch tuning of the overlap mode: percent of its workgroups the draft stage works with beside the verify stage (0 = default)")
     ap.add_argument("--attn-split", type=int, default=0, help="launch tuning: positions of capacity per attention split (0 = default)")
     ap.add_argument("--prefill-loop", action="store_true", help="prefill with the decode kernels, one position at a time")
     ap.add_argument("--prompt-len", type=int, default=None, help="override the workload's prompt length")
@@ -253,7 +254,7 @@ def main():
             continue
         ss = P.Session(w, W, max_seq=max_seq, mode=mode, engine=engine, prefill_loop=args.prefill_loop,
                        pipeline_streams=args.pipeline_streams if mode == P.MODE_PIPELINE else 0,
-                       tune_wgs_per_cu=args.wgs_per_cu, tune_attn_split=args.attn_split,
+                       tune_wgs_per_cu=args.wgs_per_cu, tune_attn_split=args.attn_split, tune_draft_share=args.draft_share,
                        eesd_gamma=args.gamma if mode == P.MODE_EESD else 0,
                        temperature=args.temperature, sample_seed=args.sample_seed)
         times, st, toks = run_generations(ss, prompt, n, args.steps, args.warmup, torch)

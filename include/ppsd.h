@@ -139,6 +139,13 @@ typedef struct {
   int32_t tune_prefill_tile; /* launch tuning of the matrix-core prefill GEMMs: 0 = choose per projection (256 x 256
                               output tiles when they still fill the chip, else 128 x 128 with K split over
                               several workgroups), 1 = always 128 x 128, 2 = always 256 x 256 */
+  int32_t tune_draft_share;/* launch tuning of PPSD_MODE_OVERLAP: percent of their workgroups the draft stage's
+                              weight-streaming kernels work with while the verify stage runs beside them (the
+                              others return at once), 1..100; 0 = the library's default.  The draft stage has
+                              E layers + a head to stream against N-E layers + a head: with a matching share
+                              of the bandwidth it stays beside the verify chain for the whole step instead of
+                              finishing early.  Draft-only steps use every workgroup.  Results do not depend
+                              on it */
 } ppsd_config;
 
 /* DEVICE pointers, BORROWED.  Per-layer entries are HOST arrays of n_layers DEVICE pointers

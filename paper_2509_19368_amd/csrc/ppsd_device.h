@@ -73,6 +73,7 @@ struct Dims {
   int32_t max_seq, page_tokens, n_pages, n_splits;
   int32_t debug_rows, head_blocks;
   int32_t n_stages, page_shift;   // ceil(L / E); log2(page_tokens) (pages hold 8, 16, 32 or 64 positions)
+  int32_t draft_share;            // of 256: workgroups of a draft-stage kernel that work while the verify stage runs beside it
   float eps, qscale;     // qscale = 1/sqrt(hd)
 };
 
@@ -432,6 +433,22 @@ struct CopyStage {
     __syncthreads();
   }
 };
+
+// Workgroups of a weight-streaming kernel that take part (the others return at once).  In a full
+// two-stage step the draft stage (E layers + exit head) runs beside the verify stage (N-E layers +
+// LM head) and has a fraction of its bytes to move: with equal grids it would finish early and leave
+// the verify chain alone with its launch gaps for the rest of the step.  Working with a share of its
+// grid, it streams at a matching share of the bandwidth and stays beside the verify chain for the
+// whole step.  A draft-only step (nothing runs beside it) uses the whole grid.  Row sums do not
+// depend on which wave computes them, so results are the same bit for bit.
+__device__ __forceinline__ int active_workgroups(const Common &c, int role) {
+  int n = gridDim.x;
+  if (role == kDraft && c.dm.draft_share < 256 && c.st->full) {
+    n = (n * c.dm.draft_share + 255) >> 8;
+    if (n < 1) n = 1;
+  }
+  return n;
+}
 
 // A residual selector whose address does not depend on the device state.
 __device__ __forceinline__ bool static_slot(int sel) {

@@ -65,7 +65,9 @@ __global__ __launch_bounds__(kGBlock) void k_qkv(Common c, int role, int layer, 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int half = m.hd >> 1;
   const int n_tasks = (m.n_h + 2 * m.n_kv) * half;
-  const int gw = blockIdx.x * kGWaves + wave, tw = gridDim.x * kGWaves;
+  const int nwg = active_workgroups(c, role);
+  if ((int)blockIdx.x >= nwg) return;
+  const int gw = blockIdx.x * kGWaves + wave, tw = nwg * kGWaves;
 
   const WT *rows[kTripRows];
   auto set_rows = [&](int task) {
@@ -401,7 +403,9 @@ __global__ __launch_bounds__(kGBlock) void k_proj_resid(Common c, int role, cons
   if (!si.active) return;
   constexpr int KB = kProjTripBlocks;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int gw = blockIdx.x * kGWaves + wave, tw = gridDim.x * kGWaves;
+  const int nwg = active_workgroups(c, role);
+  if ((int)blockIdx.x >= nwg) return;
+  const int gw = blockIdx.x * kGWaves + wave, tw = nwg * kGWaves;
   const int nblk = col_blocks<WT>(C);
   const WT *rows[1];
   Trip<WT, 1, KB> trip;
@@ -443,7 +447,9 @@ __global__ __launch_bounds__(kGBlock) void k_gate_up(Common c, int role, int xin
   const StageIn si = stage_in(c, role);
   if (!si.active) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int gw = blockIdx.x * kGWaves + wave, tw = gridDim.x * kGWaves;
+  const int nwg = active_workgroups(c, role);
+  if ((int)blockIdx.x >= nwg) return;
+  const int gw = blockIdx.x * kGWaves + wave, tw = nwg * kGWaves;
   const WT *rows[kTripRows];
   auto set_rows = [&](int task) {
     rows[0] = wgu + (size_t)task * d;
@@ -481,7 +487,12 @@ __global__ __launch_bounds__(kGBlock) void k_head(Common c, int role, int xin_se
   if (!si.active) return;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int n_tasks = (V + 1) >> 1;
-  const int gw = blockIdx.x * kGWaves + wave, tw = gridDim.x * kGWaves;
+  const int nwg = active_workgroups(c, role);
+  if ((int)blockIdx.x >= nwg) {     // the commit kernel reads one candidate per launched workgroup
+    if (threadIdx.x == 0) cand[blockIdx.x] = make_float2(-INFINITY, __int_as_float(0x7fffffff));
+    return;
+  }
+  const int gw = blockIdx.x * kGWaves + wave, tw = nwg * kGWaves;
   const WT *rows[kTripRows];
   auto set_rows = [&](int task) {
     rows[0] = W + (size_t)(2 * task) * d;
