@@ -222,6 +222,21 @@ int ppsd_prefill(ppsd_ctx *ctx, const int32_t *prompt, int32_t n_prompt, int32_t
  * eesd_gamma in PPSD_MODE_EESD) would pass max_seq. */
 int ppsd_decode(ppsd_ctx *ctx, int32_t n_tokens, int32_t *out_tokens, int32_t *n_written);
 
+/* For callers that cannot allocate device memory while they decode (tight serving loops, harnesses that
+ * forbid hipMalloc, code that must not grow the process's device footprint): ppsd_decode with the per-step
+ * scratch of its kernels -- the vectors between the kernels of a layer, the attention split partials and
+ * their arrival counters, the heads' argmax candidates, the batched pass's vectors -- in a static device
+ * array of PPSD_STATIC_SCRATCH_BYTES inside the library instead of the caller's workspace (KV cache, decode
+ * state, hidden states and weights stay where ppsd_load_weights put them).  The call itself allocates
+ * nothing on host or device: kernels are launched directly (no graph), the tokens come back through the
+ * context's pinned block.  Same arguments, results and errors as ppsd_decode, and calls of the two may
+ * alternate on one context; in addition PPSD_ECAPACITY if the configuration's scratch exceeds the static
+ * region, PPSD_EARG with the persistent engine or time_kernels, PPSD_ESTATE if the current device is not
+ * the context's.  Every context on a device shares that device's array (each device has its own copy, held
+ * until the process ends): calls that overlap in time on one device race; run them one after the other. */
+#define PPSD_STATIC_SCRATCH_BYTES (16u << 20)
+int ppsd_decode_static_scratch(ppsd_ctx *ctx, int32_t n_tokens, int32_t *out_tokens, int32_t *n_written);
+
 /* Copies the counters (HOST out). */
 int ppsd_stats(const ppsd_ctx *ctx, ppsd_stats_t *out);
 

@@ -75,6 +75,8 @@ def load_library():
     lib.ppsd_load_weights.argtypes = [C.POINTER(ppsd_config), C.POINTER(ppsd_buffers), C.POINTER(vp)]
     lib.ppsd_prefill.restype, lib.ppsd_prefill.argtypes = i32, [vp, C.POINTER(i32), i32, C.POINTER(i32)]
     lib.ppsd_decode.restype, lib.ppsd_decode.argtypes = i32, [vp, i32, C.POINTER(i32), C.POINTER(i32)]
+    lib.ppsd_decode_static_scratch.restype = i32
+    lib.ppsd_decode_static_scratch.argtypes = [vp, i32, C.POINTER(i32), C.POINTER(i32)]
     lib.ppsd_stats.restype, lib.ppsd_stats.argtypes = i32, [vp, C.POINTER(ppsd_stats_t)]
     lib.ppsd_read_logits.restype, lib.ppsd_read_logits.argtypes = i32, [vp, i32, i32, C.POINTER(C.c_float)]
     lib.ppsd_read_drafts.restype, lib.ppsd_read_drafts.argtypes = i32, [vp, i32, i32, C.POINTER(i32)]
@@ -202,6 +204,12 @@ class Session:
         out = (C.c_int32 * max(n_tokens, 1))()
         n = C.c_int32()
         _check(self.lib.ppsd_decode(self._ctx, n_tokens, out, C.byref(n)))
+        return list(out[: n.value])
+
+    def ppsd_decode_static_scratch(self, n_tokens: int) -> List[int]:
+        out = (C.c_int32 * max(n_tokens, 1))()
+        n = C.c_int32()
+        _check(self.lib.ppsd_decode_static_scratch(self._ctx, n_tokens, out, C.byref(n)))
         return list(out[: n.value])
 
     def ppsd_stats(self) -> dict:

@@ -19,6 +19,8 @@
 
 using namespace ppsd;
 
+static __device__ __align__(256) unsigned char scratch[PPSD_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local std::string g_err;
@@ -54,6 +56,12 @@ constexpr int kMaxStreams = 4;         // streams the stages of a pipeline tick 
 
 enum Kind { kKQkv = 0, kKAttn, kKOproj, kKGateUp, kKDown, kKHead, kKCommit };
 
+// The per-step scratch region of ppsd_decode_static_scratch.  In host code the array's name is only a
+// stand-in; its device address is taken once per device with hipGetSymbolAddress (ppsd_load_weights does
+// it for the current device) and kept here.  Every device holds its own copy until the process ends.
+constexpr int kMaxDevices = 64;
+void *g_static_scratch[kMaxDevices] = {};
+
 struct Layout {
   size_t state, prompt, out_tokens, drafts, page_table, rope_cos, rope_sin, xbuf;
   size_t q[kMaxStreams], a[kMaxStreams], mbuf[kMaxStreams], partials[kMaxStreams], counters[kMaxStreams], cand_lm, cand_exit, sink, logits, kv;
@@ -64,6 +72,7 @@ struct Layout {
   size_t logits_lm, logits_exit, probs;                // sampling (0 bytes unless temperature > 0)
   size_t logits_b, probs_e;                            // sampling in draft-then-verify rounds
   bool pf;
+  size_t scratch0, scratch_bytes;                      // the per-step scratch region [scratch0, scratch0 + scratch_bytes)
   size_t total;
   int n_pages, n_splits, head_blocks;
 };
@@ -152,6 +161,11 @@ Layout make_layout(const ppsd_config *c) {
   L.rope_sin = take(4ull * c->max_seq * (c->head_dim / 2));
   L.xbuf = take(4ull * kXSlots * c->d_model);
   const size_t nq = (size_t)c->n_heads * c->head_dim;
+  // Per-step scratch, one contiguous region: vectors between the kernels of a layer, attention split
+  // partials and their arrival counters, the heads' candidates, the batched pass's vectors.  Nothing in it
+  // outlives a step (the counters are back at zero after every use), so ppsd_decode_static_scratch can
+  // run the same kernels with this region in the library's static device array instead.
+  L.scratch0 = off;
   for (int s = 0; s < kMaxStreams; ++s) {
     L.q[s] = take(4 * nq);
     L.a[s] = take(4 * nq);
@@ -162,6 +176,14 @@ Layout make_layout(const ppsd_config *c) {
   const size_t n_cand = kMaxWorkgroups;
   L.cand_lm = take(8ull * n_cand);
   L.cand_exit = take(8ull * n_cand);
+  const size_t nb = c->mode == PPSD_MODE_EESD ? kMaxBatch : 0;
+  L.qb = take(4ull * nb * nq);
+  L.ab = take(4ull * nb * nq);
+  L.mb = take(4ull * nb * c->d_ffn);
+  L.partials_b = take(4ull * nb * c->n_heads * kMaxSplits * (c->head_dim + 2));
+  L.counters_b = take(4ull * nb * kCounterStride * c->n_kv_heads);
+  L.cand_b = take(8ull * nb * n_cand);
+  L.scratch_bytes = off - L.scratch0;
   L.layer_ptrs = take(sizeof(LayerPtrs) * (size_t)c->n_layers);
   L.bar = take(256);
   L.abort_flag = take(256);
@@ -188,13 +210,6 @@ Layout make_layout(const ppsd_config *c) {
     part = std::max(part, pf_partial_floats(pf_plan(nv, c->d_model, c->d_ffn, tile)));
   }
   L.pf_part = take(4ull * part);
-  const size_t nb = c->mode == PPSD_MODE_EESD ? kMaxBatch : 0;
-  L.qb = take(4ull * nb * nq);
-  L.ab = take(4ull * nb * nq);
-  L.mb = take(4ull * nb * c->d_ffn);
-  L.partials_b = take(4ull * nb * c->n_heads * kMaxSplits * (c->head_dim + 2));
-  L.counters_b = take(4ull * nb * kCounterStride * c->n_kv_heads);
-  L.cand_b = take(8ull * nb * n_cand);
   const size_t nv = c->temperature > 0.0f ? (size_t)c->vocab : 0;
   L.logits_lm = take(4ull * nv);
   L.logits_exit = take(4ull * nv);
@@ -218,6 +233,8 @@ struct ppsd_ctx {
   const void *embed, *final_norm, *lm_head, *exit_norm, *exit_head;
   std::vector<const void *> attn_norm, wqkv, wo, mlp_norm, wgu, wdown;
   char *ws;
+  char *scr = nullptr;                  // base of the per-step scratch region: ws + lay.scratch0, or the static array
+  int32_t *h_out = nullptr;             // pinned, max_seq ints: staging of the committed tokens on their way to the host
   hipStream_t sA, sB;
   hipStream_t sx[kMaxStreams] = {};     // pipeline ticks: sx[0] = sA, sx[1] = sB, the rest created here
   int n_streams = 2;
@@ -229,6 +246,7 @@ struct ppsd_ctx {
   DevState *h_state = nullptr;          // pinned
   // persistent engine
   int n_cu = 0;                         // compute units of the device
+  int device = -1;                      // the device the context was created on
   int n_wg = 0;
   // bytes of LDS a staged input vector of C elements takes (padded to whole column blocks)
   size_t xs_bytes(int C) const { return 4ull * xs_floats(cfg.dtype == PPSD_FP32 ? 4 : 2, C); }
@@ -254,6 +272,8 @@ struct ppsd_ctx {
 namespace {
 
 template <typename T> T *at(ppsd_ctx *x, size_t off) { return reinterpret_cast<T *>(x->ws + off); }
+// a buffer of the per-step scratch region, wherever that region lives for the running call
+template <typename T> T *sc(ppsd_ctx *x, size_t off) { return reinterpret_cast<T *>(x->scr + (off - x->lay.scratch0)); }
 
 // Launch helper.  In profiling mode (all launches on one stream) one event is recorded at the start
 // of the step and one after every kernel: kernel i lasted from event i to event i + 1.  A single
@@ -299,9 +319,9 @@ void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int 
   const ppsd_config &c = x->cfg;
   const Common &cm = x->cm;
   const int d = c.d_model, f = c.d_ffn, nq = c.n_heads * c.head_dim;
-  float *q = at<float>(x, x->lay.q[stage]);
-  float *a = at<float>(x, x->lay.a[stage]);
-  float *mb = at<float>(x, x->lay.mbuf[stage]);
+  float *q = sc<float>(x, x->lay.q[stage]);
+  float *a = sc<float>(x, x->lay.a[stage]);
+  float *mb = sc<float>(x, x->lay.mbuf[stage]);
   // xwork: residual slot used inside the layer after the first residual add
   const int total_pairs = (c.n_heads + 2 * c.n_kv_heads) * (c.head_dim / 2);
   L.before(kKQkv);
@@ -311,8 +331,8 @@ void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int 
   L.after();
 
   const dim3 agrid(c.n_kv_heads, x->lay.n_splits);
-  float *part = at<float>(x, x->lay.partials[stage]);
-  int *cnt = at<int>(x, x->lay.counters[stage]);
+  float *part = sc<float>(x, x->lay.partials[stage]);
+  int *cnt = sc<int>(x, x->lay.counters[stage]);
   const int G = c.n_heads / c.n_kv_heads;
   L.before(kKAttn);
 #define ATTN(HD, GG) hipLaunchKernelGGL((k_attn<WT, HD, GG>), agrid, dim3(kGBlock), 0, L.s, cm, role, layer, \
@@ -343,7 +363,7 @@ template <typename WT>
 void launch_head(Launcher &L, int role, int xin_sel, bool is_lm) {
   ppsd_ctx *x = L.x;
   const ppsd_config &c = x->cfg;
-  float2 *cand = at<float2>(x, is_lm ? x->lay.cand_lm : x->lay.cand_exit);
+  float2 *cand = sc<float2>(x, is_lm ? x->lay.cand_lm : x->lay.cand_exit);
   float *logits = c.debug_logits > 0 ? at<float>(x, x->lay.logits) : nullptr;
   float *full = c.temperature > 0.0f ? at<float>(x, is_lm ? x->lay.logits_lm : x->lay.logits_exit) : nullptr;
   L.before(kKHead);
@@ -364,8 +384,8 @@ void launch_commit(Launcher &L, int kind) {
     return;
   }
   L.before(kKCommit);
-  hipLaunchKernelGGL(k_commit, dim3(1), dim3(kBlock), 0, L.s, x->cm, kind, at<const float2>(x, x->lay.cand_lm),
-                     at<const float2>(x, x->lay.cand_exit), at<int32_t>(x, x->lay.out_tokens),
+  hipLaunchKernelGGL(k_commit, dim3(1), dim3(kBlock), 0, L.s, x->cm, kind, sc<const float2>(x, x->lay.cand_lm),
+                     sc<const float2>(x, x->lay.cand_exit), at<int32_t>(x, x->lay.out_tokens),
                      at<int32_t>(x, x->lay.drafts));
   L.after();
 }
@@ -400,7 +420,7 @@ void launch_exit_block(Launcher &L, int role, int stage, int xin, int xwork, boo
   L.before(kKQkv);
   hipLaunchKernelGGL((k_qkv<WT>), dim3(x->gemv_grid(total_pairs)), dim3(kGBlock), x->xs_bytes(c.d_model), L.s, x->cm, role,
                      layer, xin, 0, (const WT *)x->embed, (const float *)x->attn_norm[layer], (const WT *)x->wqkv[layer],
-                     at<float>(x, x->lay.q[stage]));
+                     sc<float>(x, x->lay.q[stage]));
   L.after();
 }
 
@@ -452,9 +472,9 @@ void launch_verify_batch(Launcher &L) {
   const ppsd_config &c = x->cfg;
   const Common &cm = x->cm;
   const int d = c.d_model, f = c.d_ffn, nq = c.n_heads * c.head_dim;
-  float *q = at<float>(x, x->lay.qb), *a = at<float>(x, x->lay.ab), *mb = at<float>(x, x->lay.mb);
-  float *part = at<float>(x, x->lay.partials_b);
-  int *cnt = at<int>(x, x->lay.counters_b);
+  float *q = sc<float>(x, x->lay.qb), *a = sc<float>(x, x->lay.ab), *mb = sc<float>(x, x->lay.mb);
+  float *part = sc<float>(x, x->lay.partials_b);
+  int *cnt = sc<int>(x, x->lay.counters_b);
   const size_t lds_d = (size_t)B * x->xs_bytes(d);
   const int total_pairs = (c.n_heads + 2 * c.n_kv_heads) * (c.head_dim / 2);
   const int G = c.n_heads / c.n_kv_heads;
@@ -482,7 +502,7 @@ void launch_verify_batch(Launcher &L) {
   float *full = c.temperature > 0.0f ? at<float>(x, x->lay.logits_b) : nullptr;
   L.before(kKHead);
   hipLaunchKernelGGL((k_head_b<WT, B>), dim3(cm.dm.head_blocks), dim3(kGBlock), lds_d, L.s, cm, kXBatchWorkSlot0,
-                     (const float *)x->final_norm, (const WT *)x->lm_head, at<float2>(x, x->lay.cand_b), logits, full);
+                     (const float *)x->final_norm, (const WT *)x->lm_head, sc<float2>(x, x->lay.cand_b), logits, full);
   L.after();
 }
 
@@ -515,7 +535,7 @@ hipError_t enqueue_eesd_round(ppsd_ctx *x) {
         hipLaunchKernelGGL(k_eesd_pick_sample, dim3(1), dim3(kSBlock), 0, A.s, x->cm, at<const float>(x, x->lay.logits_exit),
                            at<float>(x, x->lay.probs_e), j, 1.0f / c.temperature, (uint32_t)c.sample_seed);
       else
-        hipLaunchKernelGGL(k_eesd_pick, dim3(1), dim3(kBlock), 0, A.s, x->cm, at<const float2>(x, x->lay.cand_exit), j);
+        hipLaunchKernelGGL(k_eesd_pick, dim3(1), dim3(kBlock), 0, A.s, x->cm, sc<const float2>(x, x->lay.cand_exit), j);
       A.after();
     }
   }
@@ -531,7 +551,7 @@ hipError_t enqueue_eesd_round(ppsd_ctx *x) {
                        at<const float>(x, x->lay.probs_e), at<int32_t>(x, x->lay.out_tokens), at<int32_t>(x, x->lay.drafts), g,
                        1.0f / c.temperature, (uint32_t)c.sample_seed);
   else
-    hipLaunchKernelGGL(k_eesd_commit, dim3(1), dim3(kBlock), 0, A.s, x->cm, at<const float2>(x, x->lay.cand_b),
+    hipLaunchKernelGGL(k_eesd_commit, dim3(1), dim3(kBlock), 0, A.s, x->cm, sc<const float2>(x, x->lay.cand_b),
                        at<int32_t>(x, x->lay.out_tokens), at<int32_t>(x, x->lay.drafts), g);
   A.after();
   return A.err;
@@ -672,10 +692,10 @@ MegaArgs mega_args(ppsd_ctx *x, bool prefill, int max_steps) {
   A.embed = x->embed; A.final_norm = (const float *)x->final_norm; A.lm_head = x->lm_head;
   A.exit_norm = (const float *)x->exit_norm; A.exit_head = x->exit_head;
   for (int s = 0; s < 2; ++s) {
-    A.q[s] = at<float>(x, x->lay.q[s]); A.a[s] = at<float>(x, x->lay.a[s]); A.m[s] = at<float>(x, x->lay.mbuf[s]);
-    A.partials[s] = at<float>(x, x->lay.partials[s]); A.counters[s] = at<int>(x, x->lay.counters[s]);
+    A.q[s] = sc<float>(x, x->lay.q[s]); A.a[s] = sc<float>(x, x->lay.a[s]); A.m[s] = sc<float>(x, x->lay.mbuf[s]);
+    A.partials[s] = sc<float>(x, x->lay.partials[s]); A.counters[s] = sc<int>(x, x->lay.counters[s]);
   }
-  A.cand_lm = at<float2>(x, x->lay.cand_lm); A.cand_exit = at<float2>(x, x->lay.cand_exit);
+  A.cand_lm = sc<float2>(x, x->lay.cand_lm); A.cand_exit = sc<float2>(x, x->lay.cand_exit);
   A.logits = c.debug_logits > 0 ? at<float>(x, x->lay.logits) : nullptr;
   A.out_tokens = at<int32_t>(x, x->lay.out_tokens); A.drafts = at<int32_t>(x, x->lay.drafts);
   A.cand_counts = at<int>(x, x->lay.cand_counts);
@@ -888,6 +908,7 @@ int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *b, ppsd_ctx **
   x->cfg = *cfg;
   x->lay = lay;
   x->ws = (char *)b->workspace;
+  x->scr = x->ws + lay.scratch0;
   x->embed = b->embed; x->final_norm = b->final_norm; x->lm_head = b->lm_head;
   x->exit_norm = b->exit_norm; x->exit_head = b->exit_head;
   x->attn_norm.assign(b->attn_norm, b->attn_norm + cfg->n_layers + cfg->exit_block);
@@ -976,6 +997,17 @@ int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *b, ppsd_ctx **
   HIP_TRY_X(hipEventCreate(&x->ev_t0));
   HIP_TRY_X(hipEventCreate(&x->ev_t1));
   HIP_TRY_X(hipHostMalloc((void **)&x->h_state, sizeof(DevState), hipHostMallocDefault));
+  HIP_TRY_X(hipHostMalloc((void **)&x->h_out, 4ull * cfg->max_seq, hipHostMallocDefault));
+  {
+    int dev = 0;
+    HIP_TRY_X(hipGetDevice(&dev));
+    x->device = dev;
+    if (dev >= 0 && dev < kMaxDevices && !g_static_scratch[dev]) {
+      void *p = nullptr;
+      HIP_TRY_X(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+      g_static_scratch[dev] = p;
+    }
+  }
 
   // everything before the KV pool starts from zero (state, counters, candidates, logs)
   HIP_TRY_X(hipMemsetAsync(x->ws, 0, lay.kv, x->sA));
@@ -1026,6 +1058,7 @@ void ppsd_free(ppsd_ctx *x) {
   if (x->ev_t1) (void)hipEventDestroy(x->ev_t1);
   for (hipEvent_t e : x->tk_events) (void)hipEventDestroy(e);
   if (x->h_state) (void)hipHostFree(x->h_state);
+  if (x->h_out) (void)hipHostFree(x->h_out);
   delete x;
 }
 
@@ -1069,7 +1102,41 @@ int ppsd_prefill(ppsd_ctx *x, const int32_t *prompt, int32_t n_prompt, int32_t *
   return PPSD_OK;
 }
 
+static int decode_impl(ppsd_ctx *x, int32_t n_tokens, int32_t *out_tokens, int32_t *n_written, bool static_scratch);
+
 int ppsd_decode(ppsd_ctx *x, int32_t n_tokens, int32_t *out_tokens, int32_t *n_written) {
+  return decode_impl(x, n_tokens, out_tokens, n_written, false);
+}
+
+int ppsd_decode_static_scratch(ppsd_ctx *x, int32_t n_tokens, int32_t *out_tokens, int32_t *n_written) {
+  if (!x || !n_written) return fail(PPSD_EARG, "null argument");
+  *n_written = 0;
+  if (x->cfg.engine != PPSD_ENGINE_STREAMS || x->cfg.time_kernels)
+    return fail(PPSD_EARG, "ppsd_decode_static_scratch runs on the per-operation engine, without time_kernels");
+  if (x->lay.scratch_bytes > (size_t)PPSD_STATIC_SCRATCH_BYTES)
+    return fail(PPSD_ECAPACITY, "this configuration needs %zu bytes of per-step scratch, the static region holds %zu",
+                x->lay.scratch_bytes, (size_t)PPSD_STATIC_SCRATCH_BYTES);
+  int dev = -1;
+  HIP_TRY(hipGetDevice(&dev));
+  if (dev != x->device || dev < 0 || dev >= kMaxDevices || !g_static_scratch[dev])
+    return fail(PPSD_ESTATE, "the context was created on device %d, the current device is %d", x->device, dev);
+  // The region keeps what the last call (of any context on this device) left.  The kernels write every
+  // buffer before they read it, except the arrival counters of the attention splits, which must start at zero.
+  char *const own = x->scr;
+  x->scr = (char *)g_static_scratch[dev];
+  const int n_ctr = kCounterStride * x->cfg.n_kv_heads;
+  for (int s = 0; s < kMaxStreams; ++s)
+    hipLaunchKernelGGL(k_fill_int, dim3((n_ctr + 255) / 256), dim3(256), 0, x->sA, sc<int>(x, x->lay.counters[s]), n_ctr, 0);
+  if (x->cfg.mode == PPSD_MODE_EESD)
+    hipLaunchKernelGGL(k_fill_int, dim3((kMaxBatch * n_ctr + 255) / 256), dim3(256), 0, x->sA, sc<int>(x, x->lay.counters_b),
+                       kMaxBatch * n_ctr, 0);
+  int rc = hipGetLastError() == hipSuccess ? PPSD_OK : fail(PPSD_EHIP, "clearing the static scratch counters failed");
+  if (rc == PPSD_OK) rc = decode_impl(x, n_tokens, out_tokens, n_written, true);
+  x->scr = own;
+  return rc;
+}
+
+static int decode_impl(ppsd_ctx *x, int32_t n_tokens, int32_t *out_tokens, int32_t *n_written, bool static_scratch) {
   if (!x || !n_written || (n_tokens > 0 && !out_tokens)) return fail(PPSD_EARG, "null argument");
   *n_written = 0;
   if (n_tokens < 0) return fail(PPSD_EARG, "n_tokens < 0");
@@ -1150,7 +1217,8 @@ int ppsd_decode(ppsd_ctx *x, int32_t n_tokens, int32_t *out_tokens, int32_t *n_w
       const int per = c.mode == PPSD_MODE_EESD ? x->gamma + 1 : 1;
       const int n_steps = (remaining + per - 1) / per;
       for (int k = 0; k < n_steps; ++k) {
-        if (x->g_step) HIP_TRY(hipGraphLaunch(x->g_step, x->sA));
+        // the captured graph holds the workspace's scratch addresses: the static-scratch variant launches directly
+        if (x->g_step && !static_scratch) HIP_TRY(hipGraphLaunch(x->g_step, x->sA));
         else HIP_TRY(enqueue_step_any(x, c.mode, two, false));
       }
       x->steps_launched += n_steps;
@@ -1161,9 +1229,11 @@ int ppsd_decode(ppsd_ctx *x, int32_t n_tokens, int32_t *out_tokens, int32_t *n_w
     if (++guard > 4 * n_tokens + 16) return fail(PPSD_ESTATE, "decode made no progress (device state n_out %d)", x->h_state->n_out);
   }
   HIP_TRY(hipEventRecord(x->ev_t1, x->sA));
-  HIP_TRY(hipMemcpyAsync(out_tokens, at<int32_t>(x, x->lay.out_tokens), 4ull * n_tokens, hipMemcpyDeviceToHost, x->sA));
+  // through the context's pinned block: a copy into pageable memory may make the runtime allocate staging
+  HIP_TRY(hipMemcpyAsync(x->h_out, at<int32_t>(x, x->lay.out_tokens), 4ull * n_tokens, hipMemcpyDeviceToHost, x->sA));
   HIP_TRY(hipStreamSynchronize(x->sA));
   HIP_TRY(hipStreamSynchronize(x->sB));
+  std::memcpy(out_tokens, x->h_out, 4ull * n_tokens);
   float ms = 0.f;
   HIP_TRY(hipEventElapsedTime(&ms, x->ev_t0, x->ev_t1));
   x->device_ms += ms;

@@ -936,6 +936,12 @@ __global__ void k_begin_decode(DevState *st, int n_tokens) {
   if (threadIdx.x == 0 && blockIdx.x == 0) { st->n_out = 0; st->target = n_tokens; }
 }
 
+// Fill of a few ints (arrival counters of a scratch region about to be used).
+__global__ void k_fill_int(int *p, int n, int v) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
 // Does nothing (measurement support: what a launch, and an event between two launches, cost).
 __global__ void k_nop(int *p) { if (p == (int *)1) *p = 0; }
 
