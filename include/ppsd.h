@@ -248,6 +248,21 @@ int ppsd_read_logits(ppsd_ctx *ctx, int32_t first, int32_t count, float *out);
  * or -1 if the token was committed without a draft (token #0, vanilla mode). HOST out. */
 int ppsd_read_drafts(ppsd_ctx *ctx, int32_t first, int32_t count, int32_t *out);
 
+/* What the context launches, as decided at ppsd_load_weights from the configuration and the device
+ * (parity tests and benchmark reports state the launch configuration they ran in). */
+typedef struct {
+  int32_t compute_units;        /* of the device */
+  int32_t attn_splits;          /* splits along the sequence of the decode attention (grid = n_kv_heads x splits) */
+  int32_t prefill_matrix_core;  /* 1: ppsd_prefill runs the MFMA path, 0: the looped decode kernels */
+  int32_t prefill_chunk;        /* positions per chunk of the MFMA prefill (0 when it is not used) */
+  int32_t grid_qkv, grid_proj, grid_gate_up, grid_head;   /* workgroups of the weight-streaming kernels */
+  int32_t draft_share_of_256;   /* PPSD_MODE_OVERLAP: share of its workgroups the draft stage works with beside the verify stage */
+  int32_t streams;              /* streams a step is spread over */
+  int32_t pipeline_stages;      /* ceil(n_layers / exit_layer) */
+  int32_t eesd_gamma;           /* drafts per round in PPSD_MODE_EESD, else 0 */
+} ppsd_launch_info_t;
+int ppsd_launch_info(const ppsd_ctx *ctx, ppsd_launch_info_t *out);
+
 /* Profiling mode only (time_kernels = 1): accumulated per-kind kernel durations. */
 int ppsd_kernel_times(const ppsd_ctx *ctx, ppsd_kernel_times_t *out);
 

@@ -53,6 +53,12 @@ class ppsd_kernel_times_t(C.Structure):
     _fields_ = [("total_us", C.c_double * 7), ("launches", C.c_int64 * 7), ("event_overhead_us", C.c_double)]
 
 
+class ppsd_launch_info_t(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("compute_units", "attn_splits", "prefill_matrix_core", "prefill_chunk", "grid_qkv",
+                                          "grid_proj", "grid_gate_up", "grid_head", "draft_share_of_256", "streams",
+                                          "pipeline_stages", "eesd_gamma")]
+
+
 _lib = None
 
 
@@ -81,6 +87,7 @@ def load_library():
     lib.ppsd_read_logits.restype, lib.ppsd_read_logits.argtypes = i32, [vp, i32, i32, C.POINTER(C.c_float)]
     lib.ppsd_read_drafts.restype, lib.ppsd_read_drafts.argtypes = i32, [vp, i32, i32, C.POINTER(i32)]
     lib.ppsd_kernel_times.restype, lib.ppsd_kernel_times.argtypes = i32, [vp, C.POINTER(ppsd_kernel_times_t)]
+    lib.ppsd_launch_info.restype, lib.ppsd_launch_info.argtypes = i32, [vp, C.POINTER(ppsd_launch_info_t)]
     lib.ppsd_trace_request.restype, lib.ppsd_trace_request.argtypes = i32, [vp, i32, i32]
     lib.ppsd_trace_read.restype, lib.ppsd_trace_read.argtypes = i32, [vp, i32, C.POINTER(C.c_uint64)]
     lib.ppsd_hbm_read_probe.restype = i32
@@ -227,6 +234,11 @@ class Session:
         out = (C.c_int32 * max(count, 1))()
         _check(self.lib.ppsd_read_drafts(self._ctx, first, count, out))
         return list(out[:count])
+
+    def launch_info(self) -> dict:
+        li = ppsd_launch_info_t()
+        _check(self.lib.ppsd_launch_info(self._ctx, C.byref(li)))
+        return {n: getattr(li, n) for n, _ in ppsd_launch_info_t._fields_}
 
     def kernel_times(self) -> dict:
         kt = ppsd_kernel_times_t()

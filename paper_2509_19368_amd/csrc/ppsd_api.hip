@@ -1275,6 +1275,24 @@ int ppsd_read_drafts(ppsd_ctx *x, int32_t first, int32_t count, int32_t *out) {
   return PPSD_OK;
 }
 
+int ppsd_launch_info(const ppsd_ctx *x, ppsd_launch_info_t *out) {
+  if (!x || !out) return fail(PPSD_EARG, "null argument");
+  const ppsd_config &c = x->cfg;
+  out->compute_units = x->n_cu;
+  out->attn_splits = x->lay.n_splits;
+  out->prefill_matrix_core = x->lay.pf ? 1 : 0;
+  out->prefill_chunk = x->lay.pf ? x->lay.pf_chunk : 0;
+  out->grid_qkv = x->gemv_grid((c.n_heads + 2 * c.n_kv_heads) * (c.head_dim / 2));
+  out->grid_proj = x->gemv_grid(c.d_model);
+  out->grid_gate_up = x->gemv_grid(c.d_ffn, kGateUpWgsPerCu);
+  out->grid_head = x->cm.dm.head_blocks;
+  out->draft_share_of_256 = x->cm.dm.draft_share;
+  out->streams = c.mode == PPSD_MODE_PIPELINE ? x->n_streams : c.mode == PPSD_MODE_OVERLAP ? 2 : 1;
+  out->pipeline_stages = x->cm.dm.n_stages;
+  out->eesd_gamma = x->gamma;
+  return PPSD_OK;
+}
+
 int ppsd_kernel_times(const ppsd_ctx *x, ppsd_kernel_times_t *out) {
   if (!x || !out) return fail(PPSD_EARG, "null argument");
   if (!x->cfg.time_kernels) return fail(PPSD_ESTATE, "context was not created with time_kernels = 1");
