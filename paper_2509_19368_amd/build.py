@@ -1,4 +1,4 @@
-"""Compiles the HIP library for gfx950 in-tree (paper_2509_19368_amd/libppsd.so)."""
+"""Compiles the HIP library (paper_2509_19368_amd/libppsd.so) and the ppsd_cli driver program for gfx950, in-tree."""
 from __future__ import annotations
 
 import os
@@ -28,34 +28,22 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
-BENCH_PATH = os.path.join(HERE, "ppsd_kernel_bench")
-BENCH_SOURCE = os.path.join(HERE, "csrc", "ppsd_kernel_bench.hip")
+CLI_PATH = os.path.join(HERE, "ppsd_cli")
+CLI_SOURCE = os.path.join(HERE, "csrc", "ppsd_cli.hip")
 
 
-PREFILL_BENCH_PATH = os.path.join(HERE, "ppsd_prefill_bench")
-PREFILL_BENCH_SOURCE = os.path.join(HERE, "csrc", "ppsd_prefill_bench.hip")
-
-
-def _build_program(path: str, source: str, verbose: bool) -> str:
+def build_cli(verbose: bool = False) -> str:
+    """ppsd_cli: a plain C++ program that drives libppsd.so through include/ppsd.h only (no Python at run
+    time): the program to run under rocprofv3, and a C-side exercise of the ABI."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     flags = [f for f in HIPCC_FLAGS if f not in ("-shared", "-fPIC")]
-    cmd = [hipcc, *flags, "-o", path, source]
+    cmd = [hipcc, *flags, "-o", CLI_PATH, CLI_SOURCE, "-L" + HERE, "-lppsd", "-Wl,-rpath,$ORIGIN"]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + res.stdout + res.stderr)
     if verbose:
         print(" ".join(cmd))
-    return path
-
-
-def build_kernel_bench(verbose: bool = False) -> str:
-    """The standalone kernel-level benchmark of the decode kernels (no Python at run time; used under rocprofv3 --pmc)."""
-    return _build_program(BENCH_PATH, BENCH_SOURCE, verbose)
-
-
-def build_prefill_bench(verbose: bool = False) -> str:
-    """The standalone kernel-level benchmark of the matrix-core prefill kernels."""
-    return _build_program(PREFILL_BENCH_PATH, PREFILL_BENCH_SOURCE, verbose)
+    return CLI_PATH
 
 
 def is_stale() -> bool:
@@ -67,5 +55,4 @@ def is_stale() -> bool:
 
 if __name__ == "__main__":
     print(build_library(verbose=True))
-    print(build_kernel_bench(verbose=True))
-    print(build_prefill_bench(verbose=True))
+    print(build_cli(verbose=True))
