@@ -146,6 +146,12 @@ typedef struct {
                               of the bandwidth it stays beside the verify chain for the whole step instead of
                               finishing early.  Draft-only steps use every workgroup.  Results do not depend
                               on it */
+  int32_t pipeline_stage_layers; /* PPSD_MODE_PIPELINE: layers per stage behind the draft stage; 0 = exit_layer, the paper's
+                              balanced partition into ceil(N/E) stages (one GPU each, Sec. 4.1).  On one GPU the
+                              stages share the memory system and need not be equal: fewer, longer stages behind the
+                              draft stage keep fewer speculative tokens in flight, so a rejection drops less work
+                              (S - 1 tokens, S = 1 + ceil((N - E) / pipeline_stage_layers)), at the price of fewer
+                              kernel chains running side by side.  N - E gives the two-stage schedule */
 } ppsd_config;
 
 /* DEVICE pointers, BORROWED.  Per-layer entries are HOST arrays of n_layers DEVICE pointers

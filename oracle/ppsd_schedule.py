@@ -31,7 +31,7 @@ produces; the tests hold this simulator to that.
 from __future__ import annotations
 
 from dataclasses import dataclass, field
-from typing import List, Sequence
+from typing import List, Optional, Sequence
 
 import torch
 
@@ -156,9 +156,18 @@ class PipelineStats:
         return self.accepted / self.drafts_compared if self.drafts_compared else 0.0
 
 
-def stage_ranges(n_layers: int, exit_layer: int) -> List[range]:
-    """Layers of each pipeline stage: E per stage, the remainder forms a last, shorter stage."""
-    return [range(lo, min(lo + exit_layer, n_layers)) for lo in range(0, n_layers, exit_layer)]
+def stage_ranges(n_layers: int, exit_layer: int, later_stage_layers: Optional[int] = None) -> List[range]:
+    """Layers of each pipeline stage: E per stage, the remainder forms a last, shorter stage (Sec. 4.1).
+
+    The first stage is always the draft model, layers 1..E, because the early-exit head reads the state
+    behind layer E.  later_stage_layers = w cuts the N - E layers behind it into stages of w layers instead
+    of E (the last takes what remains): a partition the paper does not use (its stages are one GPU each and
+    must be equal), but the schedule of Alg. 1 is defined for any partition whose first stage ends at the
+    exit layer; w = N - E is the two-stage schedule.
+    """
+    w = exit_layer if later_stage_layers is None else later_stage_layers
+    assert w >= 1
+    return [range(0, exit_layer)] + [range(lo, min(lo + w, n_layers)) for lo in range(exit_layer, n_layers, w)]
 
 
 @dataclass
@@ -177,11 +186,12 @@ class PipelineSession:
     stats: PipelineStats = field(default_factory=PipelineStats)
 
 
-def pipeline_prefill(dec: Decoder, prompt: Sequence[int], max_seq: int) -> PipelineSession:
+def pipeline_prefill(dec: Decoder, prompt: Sequence[int], max_seq: int,
+                     later_stage_layers: Optional[int] = None) -> PipelineSession:
     base = prefill(dec, prompt, max_seq)
-    S = len(stage_ranges(dec.s.n_layers, dec.s.exit_layer))
-    ss = PipelineSession(dec=dec, kv=base.kv, t=base.t, last_token=base.last_token,
-                         stages=stage_ranges(dec.s.n_layers, dec.s.exit_layer))
+    stages = stage_ranges(dec.s.n_layers, dec.s.exit_layer, later_stage_layers)
+    S = len(stages)
+    ss = PipelineSession(dec=dec, kv=base.kv, t=base.t, last_token=base.last_token, stages=stages)
     ss.valid = [True] + [False] * (S - 1)
     ss.pos = [base.t] + [0] * (S - 1)
     ss.hidden = [None] * S

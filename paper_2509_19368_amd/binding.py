@@ -32,7 +32,7 @@ class ppsd_config(C.Structure):
                 ("prefill_loop", C.c_int32), ("pipeline_streams", C.c_int32), ("tune_wgs_per_cu", C.c_int32),
                 ("tune_attn_split", C.c_int32), ("eesd_gamma", C.c_int32), ("exit_block", C.c_int32), ("temperature", C.c_float),
                 ("sample_seed", C.c_uint32), ("prefill_chunk", C.c_int32), ("tune_prefill_tile", C.c_int32),
-                ("tune_draft_share", C.c_int32)]
+                ("tune_draft_share", C.c_int32), ("pipeline_stage_layers", C.c_int32)]
 
 
 class ppsd_buffers(C.Structure):
@@ -108,7 +108,7 @@ def make_config(shape, max_seq: int, mode: int, kv_page_tokens: int = 16, debug_
                 prefill_loop: bool = False, pipeline_streams: int = 0, tune_wgs_per_cu: int = 0,
                 tune_attn_split: int = 0, eesd_gamma: int = 0, temperature: float = 0.0,
                 sample_seed: int = 0, prefill_chunk: int = 0, tune_prefill_tile: int = 0,
-                tune_draft_share: int = 0) -> ppsd_config:
+                tune_draft_share: int = 0, pipeline_stage_layers: int = 0) -> ppsd_config:
     cfg = ppsd_config()
     for n in ("n_layers", "exit_layer", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab"):
         setattr(cfg, n, int(getattr(shape, n)))
@@ -127,6 +127,7 @@ def make_config(shape, max_seq: int, mode: int, kv_page_tokens: int = 16, debug_
     cfg.prefill_chunk = int(prefill_chunk)
     cfg.tune_prefill_tile = int(tune_prefill_tile)
     cfg.tune_draft_share = int(tune_draft_share)
+    cfg.pipeline_stage_layers = int(pipeline_stage_layers)
     return cfg
 
 
@@ -158,13 +159,14 @@ class Session:
                  page_table: Optional[Sequence[int]] = None, engine: int = ENGINE_STREAMS,
                  prefill_loop: bool = False, pipeline_streams: int = 0, tune_wgs_per_cu: int = 0,
                  tune_attn_split: int = 0, eesd_gamma: int = 0, temperature: float = 0.0, sample_seed: int = 0,
-                 prefill_chunk: int = 0, tune_prefill_tile: int = 0, tune_draft_share: int = 0):
+                 prefill_chunk: int = 0, tune_prefill_tile: int = 0, tune_draft_share: int = 0,
+                 pipeline_stage_layers: int = 0):
         self.lib = load_library()
         self.shape = shape
         self.weights = weights
         self.cfg = make_config(shape, max_seq, mode, kv_page_tokens, debug_logits, use_graph, time_kernels, engine,
                                prefill_loop, pipeline_streams, tune_wgs_per_cu, tune_attn_split, eesd_gamma, temperature,
-                               sample_seed, prefill_chunk, tune_prefill_tile, tune_draft_share)
+                               sample_seed, prefill_chunk, tune_prefill_tile, tune_draft_share, pipeline_stage_layers)
         nbytes = ppsd_workspace_bytes(self.cfg)
         dev = weights["embed"].device
         if dev.type != "cuda":

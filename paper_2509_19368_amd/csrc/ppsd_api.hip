@@ -77,6 +77,15 @@ struct Layout {
   int n_pages, n_splits, head_blocks;
 };
 
+// Stages of the full pipeline schedule: stage 0 is the draft model (layers 1..E); the layers behind it are cut
+// into stages of pipeline_stage_layers layers each (0 = E, the balanced partition of Sec. 4.1), the last taking
+// what remains.
+int later_stage_layers(const ppsd_config *c) { return c->pipeline_stage_layers > 0 ? c->pipeline_stage_layers : c->exit_layer; }
+int pipeline_stages(const ppsd_config *c) {
+  const int w = later_stage_layers(c);
+  return 1 + (c->n_layers - c->exit_layer + w - 1) / w;
+}
+
 bool valid_config(const ppsd_config *c, const char **why) {
 #define REJECT(cond, msg) if (cond) { *why = msg; return false; }
   REJECT(!c, "null config");
@@ -112,7 +121,8 @@ bool valid_config(const ppsd_config *c, const char **why) {
   if (c->mode == PPSD_MODE_PIPELINE) {
     REJECT(c->engine != PPSD_ENGINE_STREAMS, "the full pipeline schedule runs on the per-operation engine only");
     REJECT(c->time_kernels, "time_kernels is not available with the full pipeline schedule");
-    REJECT((c->n_layers + c->exit_layer - 1) / c->exit_layer > kMaxStages, "more than 16 pipeline stages (n_layers / exit_layer)");
+    REJECT(c->pipeline_stage_layers < 0 || c->pipeline_stage_layers > c->n_layers, "pipeline_stage_layers must be 0 (= exit_layer) or 1..n_layers");
+    REJECT(pipeline_stages(c) > kMaxStages, "more than 16 pipeline stages (n_layers / exit_layer)");
   }
   REJECT(c->pipeline_streams < 0 || c->pipeline_streams == 1 || c->pipeline_streams > kMaxStreams, "pipeline_streams must be 0 (default) or 2..4");
   REJECT(c->tune_wgs_per_cu < 0 || c->tune_wgs_per_cu > 4, "tune_wgs_per_cu must be 0..4");
@@ -584,7 +594,9 @@ hipError_t enqueue_step(ppsd_ctx *x, int mode, bool two_streams, bool timed) {
     for (int k = 0; k < S; ++k) {
       const int si = k % ns;
       Launcher Lk{x, x->sx[si], false};
-      const int lo = k * c.exit_layer, hi = (k + 1) * c.exit_layer < c.n_layers ? (k + 1) * c.exit_layer : c.n_layers;
+      const int wl = later_stage_layers(&c);
+      const int lo = k == 0 ? 0 : c.exit_layer + (k - 1) * wl;
+      const int hi = k == 0 ? c.exit_layer : (lo + wl < c.n_layers ? lo + wl : c.n_layers);
       const int work = kXStageWork0 + k;
       const int xin = k == 0 ? work : kXBoundRead0 + k;
       const int xout = k == S - 1 ? work : kXBoundWrite0 + k + 1;
@@ -933,7 +945,7 @@ int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *b, ppsd_ctx **
   m.V = cfg->vocab; m.L = cfg->n_layers; m.E = cfg->exit_layer; m.max_seq = cfg->max_seq;
   m.page_tokens = cfg->kv_page_tokens; m.n_pages = lay.n_pages; m.n_splits = lay.n_splits;
   m.debug_rows = cfg->debug_logits; m.head_blocks = 0;   // set below, once the device is known
-  m.n_stages = (cfg->n_layers + cfg->exit_layer - 1) / cfg->exit_layer;
+  m.n_stages = pipeline_stages(cfg);
   m.page_shift = 0;
   while ((1 << m.page_shift) < cfg->kv_page_tokens) ++m.page_shift;
   m.eps = cfg->rms_eps; m.qscale = (float)(1.0 / std::sqrt((double)cfg->head_dim));

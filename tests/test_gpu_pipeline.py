@@ -36,8 +36,8 @@ PIPE = [
 ]
 
 
-def _n_stages(w):
-    return -(-w.n_layers // w.exit_layer)
+def _n_stages(w, later=0):
+    return 1 + -(-(w.n_layers - w.exit_layer) // (later or w.exit_layer))
 
 
 def _run(P, w, Wg, prompt, calls, mode, **kw):
@@ -54,9 +54,9 @@ def _run(P, w, Wg, prompt, calls, mode, **kw):
     return out
 
 
-def _oracle(w, W, prompt, calls):
+def _oracle(w, W, prompt, calls, later=None):
     dec = O.Decoder(w, W)
-    ss = SCH.pipeline_prefill(dec, prompt, len(prompt) + sum(calls) + 2 * _n_stages(w) + 2)
+    ss = SCH.pipeline_prefill(dec, prompt, len(prompt) + sum(calls) + 2 * _n_stages(w) + 2, later)
     toks = [ss.last_token]
     snaps = []
     for c in calls:
@@ -93,6 +93,34 @@ def test_pipeline_schedule_equals_the_simulator(P, w):
     n = w.decode_len
     rej_before_last = sum(1 for k in range(1, n) if r["drafts"][k] != r["tokens"][k])
     assert r["stats"][-1]["pipeline_ticks"] == (S_ - 1) + n + (S_ - 1) * rej_before_last
+
+
+@pytest.mark.parametrize("later", [3, 2, 5, 1])
+def test_pipeline_with_later_stages_of_another_size_equals_the_simulator(P, later):
+    """pipeline_stage_layers: the layers behind the draft stage cut into stages of `later` layers (7 layers, exit
+    layer 2: S = 3, 4, 2, 6).  Tokens, compared drafts and every counter equal the simulator's for that partition,
+    logits bitwise equal to vanilla mode, ticks = Eq. (7)'s cost model with the partition's S."""
+    w = S.Workload("pl7", n_layers=7, exit_layer=2, d_model=128, n_heads=2, n_kv_heads=2, head_dim=64, d_ffn=264,
+                   vocab=515, dtype="fp32", damp=0.25, seed=61, prompt_len=7, decode_len=30)
+    W = S.make_weights(w)
+    prompt = S.make_prompt(w)
+    calls = [11, 19]
+    n = sum(calls)
+    S_ = _n_stages(w, later)
+    dec, want, compared, snaps = _oracle(w, W, prompt, calls, later)
+    Wg = to_device(W, "cuda")
+    max_seq = len(prompt) + 1 + n + S_ - 1
+    g = _run(P, w, Wg, prompt, calls, P.MODE_PIPELINE, max_seq=max_seq, pipeline_stage_layers=later)
+    v = _run(P, w, Wg, prompt, calls, P.MODE_VANILLA, max_seq=max_seq)
+    assert g["tokens"] == want == v["tokens"] and torch.equal(g["logits"], v["logits"])
+    assert g["drafts"][1:] == compared
+    for got, ref in zip(g["stats"], snaps):
+        for k, val in ref.items():
+            assert got[k] == val, (k, got[k], val)
+    rej_before_last = sum(1 for k in range(1, n) if g["drafts"][k] != g["tokens"][k])
+    assert g["stats"][-1]["pipeline_ticks"] == (S_ - 1) + n + (S_ - 1) * rej_before_last
+    with pytest.raises(P.PpsdError):       # capacity: S - 1 speculative positions beyond the last committed token
+        _run(P, w, Wg, prompt, calls, P.MODE_PIPELINE, max_seq=max_seq - 1, pipeline_stage_layers=later)
 
 
 def test_pipeline_is_resumable_and_graph_replay_equals_direct_launch(P):

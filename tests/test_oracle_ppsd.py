@@ -105,12 +105,12 @@ def test_rollback_is_needed_for_losslessness(tiny_shape):
 
 
 # ------------------------------------------------------------------ full ceil(N/E)-stage schedule
-def _pipeline(w, W=None, n=None):
+def _pipeline(w, W=None, n=None, later=None):
     W = S.make_weights(w) if W is None else W
     dec = O.Decoder(w, W)
     prompt = S.make_prompt(w)
     n = w.decode_len if n is None else n
-    ss = P.pipeline_prefill(dec, prompt, len(prompt) + n + 8)
+    ss = P.pipeline_prefill(dec, prompt, len(prompt) + n + 8, later)
     committed = []
     reject_at = []
     while len(committed) < n:
@@ -129,6 +129,45 @@ def test_stage_partition_follows_the_paper():
     assert [list(r) for r in P.stage_ranges(8, 3)] == [[0, 1, 2], [3, 4, 5], [6, 7]]     # remainder = own stage
     assert len(P.stage_ranges(32, 8)) == 4 and len(P.stage_ranges(32, 12)) == 3
     assert [len(r) for r in P.stage_ranges(40, 10)] == [10, 10, 10, 10]
+
+
+def test_later_stages_of_another_size_keep_the_draft_stage_at_the_exit_layer():
+    assert [list(r) for r in P.stage_ranges(8, 2, 3)] == [[0, 1], [2, 3, 4], [5, 6, 7]]
+    assert [len(r) for r in P.stage_ranges(32, 8, 12)] == [8, 12, 12]
+    assert [len(r) for r in P.stage_ranges(32, 8, 24)] == [8, 24]                    # the two-stage schedule
+    assert [len(r) for r in P.stage_ranges(40, 10, 16)] == [10, 16, 14]              # the last takes what remains
+    assert [list(r) for r in P.stage_ranges(8, 3, 3)] == [list(r) for r in P.stage_ranges(8, 3)]
+    for n, e, w in ((32, 8, 12), (7, 2, 4), (9, 1, 3)):
+        flat = [l for r in P.stage_ranges(n, e, w) for l in r]
+        assert flat == list(range(n))                                                # every layer once, in order
+
+
+def test_unequal_partitions_are_lossless_and_cost_one_tick_per_stage_on_a_rejection(tiny_shape):
+    """Any partition whose first stage is the draft model commits the full model's greedy stream; the drafts
+    that meet their check token and the acceptances are those of every other schedule (they depend on the exit
+    head and the gold prefix only); ticks follow Eq. (7)'s cost model with S = the partition's stage count."""
+    base = tiny_shape.replace(n_layers=7, decode_len=22, damp=0.2)
+    for E, later in ((2, 3), (2, 5), (1, 2), (3, 2), (1, 6)):
+        w = base.replace(exit_layer=E)
+        dec, prompt, toks, ss, reject_at = _pipeline(w, later=later)
+        Sg = len(P.stage_ranges(w.n_layers, E, later))
+        assert Sg == 1 + -(-(w.n_layers - E) // later)
+        assert toks == O.greedy_decode_no_cache(dec, prompt, w.decode_len + 1), (E, later)
+        paid = sum(1 for k in reject_at if k < w.decode_len - 1)
+        assert ss.stats.ticks == (Sg - 1) + w.decode_len + (Sg - 1) * paid
+        assert ss.stats.flushed_tokens == (Sg - 1) * ss.stats.rejected
+        _, _, toks_e, se, _ = _pipeline(w)                       # the paper's partition: E layers per stage
+        assert toks_e == toks and se.compared == ss.compared
+        assert (se.stats.accepted, se.stats.rejected) == (ss.stats.accepted, ss.stats.rejected)
+    # later stage = everything behind the exit layer: the two-stage schedule, step for step
+    w = base.replace(exit_layer=3)
+    dec = O.Decoder(w, S.make_weights(w))
+    prompt = S.make_prompt(w)
+    a = P.prefill(dec, prompt, 60)
+    ta = P.decode(a, 22)
+    b = P.pipeline_prefill(dec, prompt, 60, w.n_layers - 3)
+    assert P.pipeline_decode(b, 22) == ta
+    assert b.stats.ticks == a.stats.steps_overlapped + a.stats.steps_draft_only
 
 
 def test_pipeline_schedule_is_lossless_for_every_granularity(tiny_shape):
