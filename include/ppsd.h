@@ -210,11 +210,17 @@ typedef struct {
 /* Bytes of workspace a context with this configuration needs.  0 if cfg is invalid. */
 size_t ppsd_workspace_bytes(const ppsd_config *cfg);
 
-/* Validates cfg, records the borrowed pointers, builds the rotary table (computed in double on
- * the host) and the KV page table, zeroes the device state.  *out receives the context. */
+/* The stage layout of Sec. 4.1 on one GPU: the model's N layers with the early-exit head behind layer E
+ * (the draft model = layers 1..E + that head, Sec. 3.1) and the LM head behind layer N, all stages sharing
+ * one KV cache (the verifier reuses the draft pass's rows, Sec. 3.1).
+ * Validates cfg, records the borrowed pointers, builds the rotary table (computed in double on
+ * the host) and the KV page table, zeroes the device state.  *out receives the context.
+ * PPSD_EARG for a null / misaligned pointer or an unsupported configuration, PPSD_ECAPACITY if the workspace is
+ * smaller than ppsd_workspace_bytes(cfg), PPSD_EHIP if a HIP call fails; on any error *out is NULL. */
 int ppsd_load_weights(const ppsd_config *cfg, const ppsd_buffers *bufs, ppsd_ctx **out);
 
-/* Resets the sequence, runs the full model over prompt (HOST, n_prompt >= 1 ids in [0, vocab)),
+/* The pipeline's warm-up (Sec. 4.1: after it all stages can work in parallel; Alg. 1 starts from the prompt
+ * x_1..x_n): resets the sequence, runs the full model over prompt (HOST, n_prompt >= 1 ids in [0, vocab)),
  * fills the KV cache of all layers for positions 0..n_prompt-1 and writes generated token #0 (the
  * full model's greedy token after the prompt) to *first_token (HOST).  The pipeline is left empty:
  * the first decode step is a draft-only step.  PPSD_ECAPACITY if n_prompt + 2 > max_seq. */

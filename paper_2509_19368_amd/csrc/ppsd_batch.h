@@ -412,7 +412,7 @@ __global__ __launch_bounds__(kGBlock) void k_head_b(Common c, int x_slot0, const
   float best[B];
   int besti[B];
 #pragma unroll
-  for (int b = 0; b < B; ++b) { best[b] = -INFINITY; besti[b] = 0x7fffffff; }
+  for (int b = 0; b < B; ++b) { best[b] = -INFINITY; besti[b] = kNoIndex; }
   gemv_tasks_b<WT, B>(trip, rows, gw, n_tasks, tw, d, xs, ldx, set_rows, [&](int task, float (&s)[kTripRows][B]) {
     const int r = 2 * task;
 #pragma unroll
@@ -451,7 +451,7 @@ __global__ __launch_bounds__(kBlock) void k_eesd_pick(Common c, const float2 *ca
   __shared__ int si_[kWavesPerBlock];
   DevState *st = c.st;
   if (!(st->n_out < st->target)) return;
-  const int tok = reduce_candidates<kBlock>(cand_exit, c.dm.head_blocks, sv, si_);
+  const int tok = reduce_candidates<kBlock>(cand_exit, c.dm.head_blocks, c.dm.V, sv, si_);
   if (threadIdx.x == 0) st->ee_draft[j + 1] = tok;
 }
 
@@ -558,7 +558,7 @@ __global__ __launch_bounds__(kBlock) void k_eesd_commit(Common c, const float2 *
   DevState *st = c.st;
   if (!(st->n_out < st->target)) return;
   int v[kMaxBatch];
-  for (int b = 0; b <= gamma; ++b) v[b] = reduce_candidates<kBlock>(cand_b + (size_t)b * kMaxWorkgroups, c.dm.head_blocks, sv, si_);
+  for (int b = 0; b <= gamma; ++b) v[b] = reduce_candidates<kBlock>(cand_b + (size_t)b * kMaxWorkgroups, c.dm.head_blocks, c.dm.V, sv, si_);
   if (threadIdx.x == 0) {
     int n = 0;
     while (n < gamma && st->ee_draft[n + 1] == v[n]) ++n;

@@ -250,8 +250,15 @@ __device__ __forceinline__ float block_sum(float v, float *red) {
 }
 
 // (value, index) ordering for argmax: larger value wins, equal values -> lower index wins.
-__device__ __forceinline__ bool better(float v, int i, float bv, int bi) {
+__host__ __device__ __forceinline__ bool better(float v, int i, float bv, int bi) {
   return (v > bv) || (v == bv && i < bi);
+}
+// The reduction starts from (-inf, kNoIndex); a NaN never wins a comparison, so a row of NaN logits (NaN or Inf
+// weights, an overflow) leaves kNoIndex standing.  The token that leaves the reduction is then token 0: an id
+// inside the vocabulary, so the next step's embedding read stays inside the table.
+constexpr int kNoIndex = 0x7fffffff;
+__host__ __device__ __forceinline__ int argmax_token(int best_index, int vocab) {
+  return (unsigned)best_index < (unsigned)vocab ? best_index : 0;
 }
 
 __device__ __forceinline__ void wave_argmax(float &v, int &i) {

@@ -489,7 +489,7 @@ __global__ __launch_bounds__(kGBlock) void k_head(Common c, int role, int xin_se
   const int n_tasks = (V + 1) >> 1;
   const int nwg = active_workgroups(c, role);
   if ((int)blockIdx.x >= nwg) {     // the commit kernel reads one candidate per launched workgroup
-    if (threadIdx.x == 0) cand[blockIdx.x] = make_float2(-INFINITY, __int_as_float(0x7fffffff));
+    if (threadIdx.x == 0) cand[blockIdx.x] = make_float2(-INFINITY, __int_as_float(kNoIndex));
     return;
   }
   const int gw = blockIdx.x * kGWaves + wave, tw = nwg * kGWaves;
@@ -509,7 +509,7 @@ __global__ __launch_bounds__(kGBlock) void k_head(Common c, int role, int xin_se
     if (row < m.debug_rows) lrow = logits_log + (size_t)row * V;
   }
   float best = -INFINITY;
-  int besti = 0x7fffffff;
+  int besti = kNoIndex;
   gemv_tasks<WT>(trip, rows, gw, n_tasks, tw, d, xs, set_rows, [&](int task, float s0, float s1) {
     const int r = 2 * task;
     if (better(s0, r, best, besti)) { best = s0; besti = r; }
@@ -532,10 +532,10 @@ __global__ __launch_bounds__(kGBlock) void k_head(Common c, int role, int xin_se
 // One workgroup.  kind: 0 vanilla step, 1 PPSD step, 2 prefill position (no head), 3 last prefill
 // position (LM head ran), 4 one tick of the full pipeline schedule.
 template <int BLOCK>
-__device__ __forceinline__ int reduce_candidates(const float2 *cand, int n, float *sv, int *si_) {
+__device__ __forceinline__ int reduce_candidates(const float2 *cand, int n, int vocab, float *sv, int *si_) {
   constexpr int NW = BLOCK / kWave;
   float best = -INFINITY;
-  int besti = 0x7fffffff;
+  int besti = kNoIndex;
   for (int k = threadIdx.x; k < n; k += BLOCK) {
     const float2 cnd = cand[k];
     const int idx = __float_as_int(cnd.y);
@@ -549,7 +549,7 @@ __device__ __forceinline__ int reduce_candidates(const float2 *cand, int n, floa
 #pragma unroll
   for (int w = 1; w < NW; ++w)
     if (better(sv[w], si_[w], best, besti)) { best = sv[w]; besti = si_[w]; }
-  return besti;
+  return argmax_token(besti, vocab);
 }
 
 // Called by all BLOCK threads of ONE workgroup.  sv / si_: BLOCK/64 entries of LDS each.
@@ -562,7 +562,7 @@ __device__ __forceinline__ void commit_step(const Common &c, int kind, const flo
   if (kind == 2 || kind == 3) {   // prefill
     if (!(st->prefill_pos < st->prefill_len)) return;
     int tok = -1;
-    if (kind == 3) tok = reduce_candidates<BLOCK>(cand_lm, nb, sv, si_);
+    if (kind == 3) tok = reduce_candidates<BLOCK>(cand_lm, nb, c.dm.V, sv, si_);
     if (threadIdx.x == 0) {
       st->prefill_pos += 1;
       if (kind == 3) {
@@ -589,9 +589,9 @@ __device__ __forceinline__ void commit_step(const Common &c, int kind, const flo
     // from the verified token.
     const int S = c.dm.n_stages;
     const int ran_last = st->pl_valid[S - 1];
-    const int d_next = reduce_candidates<BLOCK>(cand_exit, n_cand_exit, sv, si_);
+    const int d_next = reduce_candidates<BLOCK>(cand_exit, n_cand_exit, c.dm.V, sv, si_);
     int v = -1;
-    if (ran_last) v = reduce_candidates<BLOCK>(cand_lm, nb, sv, si_);
+    if (ran_last) v = reduce_candidates<BLOCK>(cand_lm, nb, c.dm.V, sv, si_);
     if (threadIdx.x == 0) {
       int n_ran = 0;
       for (int k = 0; k < S; ++k) n_ran += st->pl_valid[k] ? 1 : 0;
@@ -632,7 +632,7 @@ __device__ __forceinline__ void commit_step(const Common &c, int kind, const flo
   }
   const int full = st->full;
   if (kind == 0) {   // vanilla: the LM head's token is the next token
-    const int v = reduce_candidates<BLOCK>(cand_lm, nb, sv, si_);
+    const int v = reduce_candidates<BLOCK>(cand_lm, nb, c.dm.V, sv, si_);
     if (threadIdx.x == 0) {
       out_tokens[st->n_out] = v;
       drafts_log[st->gen_count] = -1;
@@ -642,9 +642,9 @@ __device__ __forceinline__ void commit_step(const Common &c, int kind, const flo
     return;
   }
   // PPSD step
-  const int d_next = reduce_candidates<BLOCK>(cand_exit, n_cand_exit, sv, si_);   // draft stage always ran
+  const int d_next = reduce_candidates<BLOCK>(cand_exit, n_cand_exit, c.dm.V, sv, si_);   // draft stage always ran
   int v = -1;
-  if (full) v = reduce_candidates<BLOCK>(cand_lm, nb, sv, si_);
+  if (full) v = reduce_candidates<BLOCK>(cand_lm, nb, c.dm.V, sv, si_);
   if (threadIdx.x == 0) {
     if (!full) {                 // pipeline refill: nothing to commit yet
       st->draft = d_next;

@@ -330,7 +330,7 @@ __global__ __launch_bounds__(kMBlock, kMegaWgsPerCu) void k_mega(MegaArgs A) {
           if (row < m.debug_rows) lrow = A.logits + (size_t)row * V;
         }
         float best = -INFINITY;
-        int besti = 0x7fffffff;
+        int besti = kNoIndex;
         gemv_tasks<WT>(trip, rows, gw, g.units, tw, d, xs, set_rows, [&](int task, float s0, float s1) {
           const int r = 2 * task;
           if (better(s0, r, best, besti)) { best = s0; besti = r; }
