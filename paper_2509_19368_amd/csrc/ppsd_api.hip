@@ -323,6 +323,11 @@ struct Launcher {
   }
 };
 
+// Trips a wave of a weight-streaming kernel keeps in flight: two where several kernel chains share the chip
+// (the stages of the pipeline schedule), one for a single chain or two chains.
+inline bool deep_role(int role) { return role >= kPipeStage0 && role < kEesdDraft0; }
+constexpr int kDeepWgsPerCu = 2;      // what stays resident at the deeper variant's register count
+
 template <typename WT>
 void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int xout_last_sel, bool from_embed, int xwork) {
   ppsd_ctx *x = L.x;
@@ -334,10 +339,16 @@ void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int 
   float *mb = sc<float>(x, x->lay.mbuf[stage]);
   // xwork: residual slot used inside the layer after the first residual add
   const int total_pairs = (c.n_heads + 2 * c.n_kv_heads) * (c.head_dim / 2);
+  const bool deep = deep_role(role);
   L.before(kKQkv);
-  hipLaunchKernelGGL((k_qkv<WT>), dim3(x->gemv_grid(total_pairs)), dim3(kGBlock), x->xs_bytes(d), L.s, cm, role, layer,
-                     xin_sel, from_embed ? 1 : 0, (const WT *)x->embed, (const float *)x->attn_norm[layer],
-                     (const WT *)x->wqkv[layer], q);
+  if (deep)
+    hipLaunchKernelGGL((k_qkv<WT, 2>), dim3(x->gemv_grid(total_pairs, kDeepWgsPerCu)), dim3(kGBlock), x->xs_bytes(d), L.s, cm, role, layer,
+                       xin_sel, from_embed ? 1 : 0, (const WT *)x->embed, (const float *)x->attn_norm[layer],
+                       (const WT *)x->wqkv[layer], q);
+  else
+    hipLaunchKernelGGL((k_qkv<WT, 1>), dim3(x->gemv_grid(total_pairs)), dim3(kGBlock), x->xs_bytes(d), L.s, cm, role, layer,
+                       xin_sel, from_embed ? 1 : 0, (const WT *)x->embed, (const float *)x->attn_norm[layer],
+                       (const WT *)x->wqkv[layer], q);
   L.after();
 
   const dim3 agrid(c.n_kv_heads, x->lay.n_splits);
@@ -352,20 +363,32 @@ void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int 
 #undef ATTN
   L.after();
 
-  const int proj_grid = x->gemv_grid(d);   // one row per task
+  const int proj_grid = x->gemv_grid(d, deep ? kDeepWgsPerCu : kGemvWgsPerCu);   // one row per task
   L.before(kKOproj);
-  hipLaunchKernelGGL((k_proj_resid<WT>), dim3(proj_grid), dim3(kGBlock), x->xs_bytes(nq), L.s, cm, role,
-                     (const float *)a, nq, (const WT *)x->wo[layer], d, xin_sel, xwork);
+  if (deep)
+    hipLaunchKernelGGL((k_proj_resid<WT, 2>), dim3(proj_grid), dim3(kGBlock), x->xs_bytes(nq), L.s, cm, role,
+                       (const float *)a, nq, (const WT *)x->wo[layer], d, xin_sel, xwork);
+  else
+    hipLaunchKernelGGL((k_proj_resid<WT, 1>), dim3(proj_grid), dim3(kGBlock), x->xs_bytes(nq), L.s, cm, role,
+                       (const float *)a, nq, (const WT *)x->wo[layer], d, xin_sel, xwork);
   L.after();
 
   L.before(kKGateUp);
-  hipLaunchKernelGGL((k_gate_up<WT>), dim3(x->gemv_grid(f, kGateUpWgsPerCu)), dim3(kGBlock), x->xs_bytes(d), L.s, cm, role, xwork,
-                     (const float *)x->mlp_norm[layer], (const WT *)x->wgu[layer], mb);
+  if (deep)
+    hipLaunchKernelGGL((k_gate_up<WT, 2>), dim3(x->gemv_grid(f, kGateUpWgsPerCu)), dim3(kGBlock), x->xs_bytes(d), L.s, cm, role, xwork,
+                       (const float *)x->mlp_norm[layer], (const WT *)x->wgu[layer], mb);
+  else
+    hipLaunchKernelGGL((k_gate_up<WT, 1>), dim3(x->gemv_grid(f, kGateUpWgsPerCu)), dim3(kGBlock), x->xs_bytes(d), L.s, cm, role, xwork,
+                       (const float *)x->mlp_norm[layer], (const WT *)x->wgu[layer], mb);
   L.after();
 
   L.before(kKDown);
-  hipLaunchKernelGGL((k_proj_resid<WT>), dim3(proj_grid), dim3(kGBlock), x->xs_bytes(f), L.s, cm, role,
-                     (const float *)mb, f, (const WT *)x->wdown[layer], d, xwork, xout_last_sel);
+  if (deep)
+    hipLaunchKernelGGL((k_proj_resid<WT, 2>), dim3(proj_grid), dim3(kGBlock), x->xs_bytes(f), L.s, cm, role,
+                       (const float *)mb, f, (const WT *)x->wdown[layer], d, xwork, xout_last_sel);
+  else
+    hipLaunchKernelGGL((k_proj_resid<WT, 1>), dim3(proj_grid), dim3(kGBlock), x->xs_bytes(f), L.s, cm, role,
+                       (const float *)mb, f, (const WT *)x->wdown[layer], d, xwork, xout_last_sel);
   L.after();
 }
 
@@ -377,9 +400,16 @@ void launch_head(Launcher &L, int role, int xin_sel, bool is_lm) {
   float *logits = c.debug_logits > 0 ? at<float>(x, x->lay.logits) : nullptr;
   float *full = c.temperature > 0.0f ? at<float>(x, is_lm ? x->lay.logits_lm : x->lay.logits_exit) : nullptr;
   L.before(kKHead);
-  hipLaunchKernelGGL((k_head<WT>), dim3(x->cm.dm.head_blocks), dim3(kGBlock), x->xs_bytes(c.d_model), L.s,
-                     x->cm, role, xin_sel, (const float *)(is_lm ? x->final_norm : x->exit_norm),
-                     (const WT *)(is_lm ? x->lm_head : x->exit_head), cand, logits, is_lm ? 1 : 0, full);
+  // the commit kernels read head_blocks candidates: both variants launch that many workgroups (the deeper one
+  // keeps two of them resident per compute unit and runs the rest behind them)
+  if (deep_role(role))
+    hipLaunchKernelGGL((k_head<WT, 2>), dim3(x->cm.dm.head_blocks), dim3(kGBlock), x->xs_bytes(c.d_model), L.s,
+                       x->cm, role, xin_sel, (const float *)(is_lm ? x->final_norm : x->exit_norm),
+                       (const WT *)(is_lm ? x->lm_head : x->exit_head), cand, logits, is_lm ? 1 : 0, full);
+  else
+    hipLaunchKernelGGL((k_head<WT, 1>), dim3(x->cm.dm.head_blocks), dim3(kGBlock), x->xs_bytes(c.d_model), L.s,
+                       x->cm, role, xin_sel, (const float *)(is_lm ? x->final_norm : x->exit_norm),
+                       (const WT *)(is_lm ? x->lm_head : x->exit_head), cand, logits, is_lm ? 1 : 0, full);
   L.after();
 }
 
@@ -428,7 +458,7 @@ void launch_exit_block(Launcher &L, int role, int stage, int xin, int xwork, boo
   }
   const int total_pairs = (c.n_heads + 2 * c.n_kv_heads) * (c.head_dim / 2);
   L.before(kKQkv);
-  hipLaunchKernelGGL((k_qkv<WT>), dim3(x->gemv_grid(total_pairs)), dim3(kGBlock), x->xs_bytes(c.d_model), L.s, x->cm, role,
+  hipLaunchKernelGGL((k_qkv<WT, 1>), dim3(x->gemv_grid(total_pairs)), dim3(kGBlock), x->xs_bytes(c.d_model), L.s, x->cm, role,
                      layer, xin, 0, (const WT *)x->embed, (const float *)x->attn_norm[layer], (const WT *)x->wqkv[layer],
                      sc<float>(x, x->lay.q[stage]));
   L.after();

@@ -49,7 +49,7 @@ __device__ __forceinline__ WT *kv_row(const Common &c, const int32_t *ptab, int 
 // ------------------------------------------------------------------------------------------
 // a1-a3: (embedding) + RMSNorm + QKV GEMV + rotary + KV append.
 // A task is the row pair (i, i + hd/2) of one head, so the rotation partner is local to the wave.
-template <typename WT>
+template <typename WT, int DEPTH>
 __global__ __launch_bounds__(kGBlock) void k_qkv(Common c, int role, int layer, int xin_sel, int from_embed,
                                                  const WT *embed, const float *gain, const WT *wqkv,
                                                  float *qout) {
@@ -75,15 +75,16 @@ __global__ __launch_bounds__(kGBlock) void k_qkv(Common c, int role, int layer, 
     rows[0] = wqkv + (size_t)(head * m.hd + i) * d;
     rows[1] = rows[0] + (size_t)half * d;
   };
-  Trip<WT, kTripRows, kTripBlocks> trip;
+  Trips<WT, kTripRows, kTripBlocks, DEPTH> trips;
   if (!early) {
     const WT *xrow = from_embed ? embed + (size_t)si.tok * d : nullptr;
     in.issue(from_embed ? nullptr : xslot(c, xin_sel), xrow, gain, d);
   }
-  if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
+  trips.start(rows, gw, n_tasks, tw, d, set_rows);
   in.finish(d, m.eps, xs, red, (from_embed && blockIdx.x == 0) ? xslot(c, xin_sel) : nullptr);
-  gemv_tasks<WT>(trip, rows, gw, n_tasks, tw, d, xs, set_rows, [&](int task, float lo, float hi) {
+  trips.run(rows, gw, n_tasks, tw, d, xs, set_rows, [&](int task, const float (&sum)[kTripRows]) {
     if (lane != 0) return;
+    float lo = sum[0], hi = sum[1];
     const int h = task / half, i = task - h * half;
     if (h < m.n_h + m.n_kv) {   // q or k head: rotate the pair by the position angle
       const float cs = c.rope_cos[(size_t)si.pos * half + i];
@@ -393,7 +394,7 @@ __global__ __launch_bounds__(kGBlock) void k_attn(Common c, int role, int layer,
 // 7B shapes: o_proj 10.3 -> 8.7 us, down 21.1 -> 18.7 us).  Per row the products are added in the same
 // order as in the two-row form.  Dynamic LDS = C floats, padded to whole column blocks.
 constexpr int kProjTripBlocks = 4;
-template <typename WT>
+template <typename WT, int DEPTH>
 __global__ __launch_bounds__(kGBlock) void k_proj_resid(Common c, int role, const float *vin, int C,
                                                         const WT *W, int n_rows, int resid_sel, int out_sel) {
   extern __shared__ __align__(16) float xs[];
@@ -406,35 +407,22 @@ __global__ __launch_bounds__(kGBlock) void k_proj_resid(Common c, int role, cons
   const int nwg = active_workgroups(c, role);
   if ((int)blockIdx.x >= nwg) return;
   const int gw = blockIdx.x * kGWaves + wave, tw = nwg * kGWaves;
-  const int nblk = col_blocks<WT>(C);
   const WT *rows[1];
-  Trip<WT, 1, KB> trip;
-  if (gw < n_rows) { rows[0] = W + (size_t)gw * C; trip_load<WT, 1, KB>(trip, rows, 0, nblk, C); }
+  auto set_rows = [&](int task) { rows[0] = W + (size_t)task * C; };
+  Trips<WT, 1, KB, DEPTH> trips;
+  trips.start(rows, gw, n_rows, tw, C, set_rows);
   in.template finish<WT>(C, xs);
   const float *resid = xslot(c, resid_sel);
   float *out = xslot(c, out_sel);
-  for (int task = gw; task < n_rows;) {
-    float acc[1] = {0.f};
-    const int next = task + tw;
-    for (int cb = 0; cb < nblk; cb += KB) {
-      trip_consume<WT, 1, KB>(trip, xs, cb, C, acc);
-      if (cb + KB < nblk) {
-        trip_load<WT, 1, KB>(trip, rows, cb + KB, nblk, C);
-      } else if (next < n_rows) {
-        rows[0] = W + (size_t)next * C;
-        trip_load<WT, 1, KB>(trip, rows, 0, nblk, C);
-      }
-    }
-    const float s0 = wave_sum(acc[0]);
-    if (lane == 0) out[task] = resid[task] + s0;
-    task = next;
-  }
+  trips.run(rows, gw, n_rows, tw, C, xs, set_rows, [&](int task, const float (&sum)[1]) {
+    if (lane == 0) out[task] = resid[task] + sum[0];
+  });
 }
 
 // ------------------------------------------------------------------------------------------
 // a2 + a6: RMSNorm + gate/up GEMV + SwiGLU: mout[i] = silu(Wg[i,:].xn) * (Wu[i,:].xn).
 // A task is the pair (gate row i, up row i).
-template <typename WT>
+template <typename WT, int DEPTH>
 __global__ __launch_bounds__(kGBlock) void k_gate_up(Common c, int role, int xin_sel, const float *gain,
                                                      const WT *wgu, float *mout) {
   extern __shared__ __align__(16) float xs[];
@@ -455,11 +443,12 @@ __global__ __launch_bounds__(kGBlock) void k_gate_up(Common c, int role, int xin
     rows[0] = wgu + (size_t)task * d;
     rows[1] = wgu + (size_t)(f + task) * d;
   };
-  Trip<WT, kTripRows, kTripBlocks> trip;
+  Trips<WT, kTripRows, kTripBlocks, DEPTH> trips;
   if (!early) in.issue(xslot(c, xin_sel), (const WT *)nullptr, gain, d);
-  if (gw < f) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
+  trips.start(rows, gw, f, tw, d, set_rows);
   in.finish(d, m.eps, xs, red, nullptr);
-  gemv_tasks<WT>(trip, rows, gw, f, tw, d, xs, set_rows, [&](int task, float g, float u) {
+  trips.run(rows, gw, f, tw, d, xs, set_rows, [&](int task, const float (&sum)[kTripRows]) {
+    const float g = sum[0], u = sum[1];
     if (lane == 0) mout[task] = g / (1.0f + __expf(-g)) * u;
   });
 }
@@ -470,7 +459,7 @@ __global__ __launch_bounds__(kGBlock) void k_gate_up(Common c, int role, int xin
 // (value, index) candidate in cand[blockIdx.x]; the commit kernel finishes the reduction over
 // gridDim.x candidates.  logits_log != nullptr additionally stores the logits (parity harness);
 // logits_out != nullptr receives all V logits of this head (sampling needs the distribution).
-template <typename WT>
+template <typename WT, int DEPTH>
 __global__ __launch_bounds__(kGBlock) void k_head(Common c, int role, int xin_sel, const float *gain,
                                                   const WT *W, float2 *cand, float *logits_log, int is_lm,
                                                   float *logits_out) {
@@ -498,9 +487,9 @@ __global__ __launch_bounds__(kGBlock) void k_head(Common c, int role, int xin_se
     rows[0] = W + (size_t)(2 * task) * d;
     rows[1] = W + (size_t)min(2 * task + 1, V - 1) * d;
   };
-  Trip<WT, kTripRows, kTripBlocks> trip;
+  Trips<WT, kTripRows, kTripBlocks, DEPTH> trips;
   if (!early) in.issue(xslot(c, xin_sel), (const WT *)nullptr, gain, d);
-  if (gw < n_tasks) { set_rows(gw); trip_load<WT, kTripRows, kTripBlocks>(trip, rows, 0, col_blocks<WT>(d), d); }
+  trips.start(rows, gw, n_tasks, tw, d, set_rows);
   in.finish(d, m.eps, xs, red, nullptr);
   // logits row for the parity harness: row index = number of tokens committed so far
   float *lrow = nullptr;
@@ -510,7 +499,8 @@ __global__ __launch_bounds__(kGBlock) void k_head(Common c, int role, int xin_se
   }
   float best = -INFINITY;
   int besti = kNoIndex;
-  gemv_tasks<WT>(trip, rows, gw, n_tasks, tw, d, xs, set_rows, [&](int task, float s0, float s1) {
+  trips.run(rows, gw, n_tasks, tw, d, xs, set_rows, [&](int task, const float (&sum)[kTripRows]) {
+    const float s0 = sum[0], s1 = sum[1];
     const int r = 2 * task;
     if (better(s0, r, best, besti)) { best = s0; besti = r; }
     if (r + 1 < V && better(s1, r + 1, best, besti)) { best = s1; besti = r + 1; }
