@@ -213,7 +213,10 @@ template <typename WT, int HD, int G>
 __global__ __launch_bounds__(kGBlock) void k_attn_b(Common c, int layer, const float *q, float *aout, float *partials,
                                                     int *counters) {
   constexpr int GPB = kGBlock / (HD / Pack<WT>::N);
-  __shared__ float merge[GPB * G * (HD + 2)];
+  // one record per wave and query head (the groups of a wave are merged through shuffles first); the merge of
+  // the splits reuses it for 3 * G * kMaxAttnSplits floats
+  __shared__ float merge[(kGBlock / kWave) * G * (HD + 2)];
+  static_assert((kGBlock / kWave) * (HD + 2) >= 3 * kMaxAttnSplits, "the split merge's arrays fit the records");
   __shared__ int s_last;
   __shared__ int32_t s_ptab[kAttnLdsPages];
   const bool lds_pt = c.dm.n_pages <= kAttnLdsPages;

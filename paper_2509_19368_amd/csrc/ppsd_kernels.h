@@ -370,8 +370,10 @@ constexpr int kAttnLdsPages = 2048;   // page-table entries the attention kernel
 template <typename WT, int HD, int G>
 __global__ __launch_bounds__(kGBlock) void k_attn(Common c, int role, int layer, const float *q, float *aout,
                                                   float *partials, int *counters) {
-  constexpr int GPB = kGBlock / (HD / Pack<WT>::N);
-  __shared__ float merge[GPB * G * (HD + 2)];
+  // one record per wave and query head (the groups of a wave are merged through shuffles first); the merge of
+  // the splits reuses it for 3 * G * kMaxAttnSplits floats
+  __shared__ float merge[(kGBlock / kWave) * G * (HD + 2)];
+  static_assert((kGBlock / kWave) * (HD + 2) >= 3 * kMaxAttnSplits, "the split merge's arrays fit the records");
   __shared__ int s_last;
   __shared__ int32_t s_ptab[kAttnLdsPages];
   // the page table does not depend on the state: copy it to LDS while the state is being read
