@@ -9,7 +9,11 @@
 // decodes in every schedule and requires one token stream: the method is lossless, Sec. 5.1).
 //
 //   ppsd_cli <C1|C2|C4|C5|7B_E4|7B_E16> [--mode vanilla|serial|overlap|pipeline|eesd] [--prompt N] [--decode N]
-//            [--gens K] [--damp X] [--exit-layer E] [--check] [--calibrate] [--static-scratch] [--no-graph]
+//            [--gens K] [--damp X] [--exit-layer E] [--later-stage W] [--capacity-for-decode N] [--check] [--calibrate]
+//            [--static-scratch] [--no-graph]
+//   --later-stage W: PPSD_MODE_PIPELINE with the layers behind the draft stage in stages of W layers.
+//   --capacity-for-decode N: size max_seq as if N tokens were decoded (a short counter run then keeps the
+//   attention split count of the full workload).
 #include <hip/hip_runtime.h>
 
 #include <chrono>
@@ -154,6 +158,8 @@ int mode_of(const std::string &m) {
   exit(2);
 }
 
+int g_later_stage = 0, g_capacity_decode = 0;
+
 RunResult run(const Model &m, int mode, int n_prompt, int n_decode, int gens, bool graph, bool static_scratch,
               hipStream_t sA, hipStream_t sB) {
   const Shape &s = m.s;
@@ -162,7 +168,8 @@ RunResult run(const Model &m, int mode, int n_prompt, int n_decode, int gens, bo
   c.n_layers = s.L; c.exit_layer = s.E; c.d_model = s.d; c.n_heads = s.n_h; c.n_kv_heads = s.n_kv; c.head_dim = s.hd;
   c.d_ffn = s.f; c.vocab = s.V; c.dtype = s.dtype; c.kv_page_tokens = 16; c.mode = mode;
   const int stages = (s.L + s.E - 1) / s.E;
-  c.max_seq = n_prompt + 1 + n_decode + (stages - 1 > 4 ? stages - 1 : 4);
+  c.max_seq = n_prompt + 1 + (g_capacity_decode > n_decode ? g_capacity_decode : n_decode) + (stages - 1 > 4 ? stages - 1 : 4);
+  c.pipeline_stage_layers = g_later_stage;
   c.rope_base = s.rope_base; c.rms_eps = 1e-5f; c.use_graph = graph ? 1 : 0;
   const size_t ws_bytes = ppsd_workspace_bytes(&c);
   if (!ws_bytes) { fprintf(stderr, "ppsd_workspace_bytes: %s\n", ppsd_last_error()); exit(4); }
@@ -207,7 +214,8 @@ RunResult run(const Model &m, int mode, int n_prompt, int n_decode, int gens, bo
 int main(int argc, char **argv) {
   if (argc < 2) {
     fprintf(stderr, "usage: %s <C1|C2|C4|C5|7B_E4|7B_E16> [--mode M] [--prompt N] [--decode N] [--gens K] [--damp X] "
-                    "[--exit-layer E] [--check] [--calibrate] [--static-scratch] [--no-graph]\n", argv[0]);
+                    "[--exit-layer E] [--later-stage W] [--capacity-for-decode N] [--check] [--calibrate] [--static-scratch] "
+                    "[--no-graph]\n", argv[0]);
     return 2;
   }
   const Shape *found = nullptr;
@@ -227,6 +235,8 @@ int main(int argc, char **argv) {
     else if (a == "--gens") gens = atoi(val());
     else if (a == "--damp") s.damp = (float)atof(val());
     else if (a == "--exit-layer") s.E = atoi(val());
+    else if (a == "--later-stage") g_later_stage = atoi(val());
+    else if (a == "--capacity-for-decode") g_capacity_decode = atoi(val());
     else if (a == "--check") check = true;
     else if (a == "--calibrate") calibrate = true;
     else if (a == "--static-scratch") static_scratch = true;
