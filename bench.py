@@ -31,14 +31,15 @@ TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic_per_kernel.txt")
 # Which PPSD schedule to run, decided before anything is measured.  Rows: the draft stage's share of the model,
 # E / N; columns: acceptance below 0.6, 0.6 to 0.8, 0.8 and above.  Measured on the 7B exit-layer x acceptance
 # grid (tokens/s relative to vanilla decode, two-stage / paper's ceil(N/E) stages / three stages):
-#   E/N = 1/8:  0.88 / 0.46 / 0.85    0.91 / 0.59 / 0.94    0.96 / 0.93 / 1.10
-#   E/N = 1/4:  0.91 / 0.71 / 0.82    0.96 / 0.85 / 0.94    1.02 / 1.13 / 1.14
-#   E/N = 1/2:  0.91 / 0.91 / 0.70    1.01 / 1.01 / 0.83    1.10 / 1.10 / 0.98
-# "three_stage" = the pipeline schedule with the layers behind the draft stage cut into two halves.
+#   E/N = 1/8:  0.87 / 0.47 / 0.86    0.91 / 0.60 / 0.95    0.96 / 0.95 / 1.12
+#   E/N = 1/4:  0.91 / 0.72 / 0.83    0.96 / 0.87 / 0.95    1.02 / 1.16 / 1.15
+#   E/N = 1/2:  0.91 / 0.93 / 0.70    1.01 / 1.02 / 0.84    1.09 / 1.11 / 0.99
+# "three_stage" = the pipeline schedule with the layers behind the draft stage cut into two halves; at E/N = 1/2
+# the paper's partition has two stages and differs from "overlap" in the kernels' prefetch depth only.
 SCHEDULE_TABLE = (
     (0.1875, ("overlap", "three_stage", "three_stage")),
     (0.375, ("overlap", "overlap", "three_stage")),
-    (1.0, ("overlap", "overlap", "overlap")),
+    (1.0, ("pipeline", "pipeline", "pipeline")),
 )
 
 
@@ -116,6 +117,11 @@ def offline_traffic():
     return {(wl, k): f * fu + wr * wu for wl, k, f, wr in rows}, dict(fetch_unit_bytes=fu, write_unit_bytes=wu)
 
 
+def progress(msg):
+    """Progress lines on stderr (stdout carries the one JSON line)."""
+    print("bench.py: " + msg, file=sys.stderr, flush=True)
+
+
 def run_generations(ss, prompt, n_decode, steps, warmup, torch):
     times = []
     stats = None
@@ -187,6 +193,7 @@ def measure(w, W, prompt, plan, args, torch, P, engine=None):
         ss.close()
         total = sum(times)
         ts = sorted(times)
+        progress(f"{w.name} {name}: {steps * n / total:.1f} tokens/s over {steps} generation(s) of {n} tokens")
         res[name] = dict(tokens_per_s=steps * n / total, ms_per_generation=1e3 * total / steps,
                          ms_per_token=1e3 * total / (steps * n), stats=st, prefill_ms=prefill_ms, steps=steps, warmup=warmup,
                          ms_per_generation_min=1e3 * ts[0], ms_per_generation_median=1e3 * ts[len(ts) // 2], launch=info)
@@ -411,6 +418,7 @@ def main():
     engine = P.ENGINE_PERSISTENT if args.engine == "persistent" else P.ENGINE_STREAMS
 
     def one_workload(w, steps, warmup, headline):
+        progress(f"{w.name}: generating weights")
         t0 = time.perf_counter()
         W = S.make_weights(w, device="cuda")
         torch.cuda.synchronize()
@@ -439,6 +447,7 @@ def main():
                                        f"{alpha_expected}" if not (headline and args.schedule) else "--schedule")
         ktimes = roofline = None
         if not args.no_kernel_timing and engine == P.ENGINE_STREAMS:
+            progress(f"{w.name}: per-kernel timing pass")
             ktimes, roofline = kernel_timing(w, W, prompt, max_seq, args, P, traffic)
             roofline["frac_per_committed_token"] = rec["hbm_frac_per_committed_token"]
         elif not args.no_kernel_timing:
@@ -461,7 +470,9 @@ def main():
     del probe
     cpu = None
     if not args.no_cpu_baseline:
+        progress(f"{w.name}: CPU oracle baseline (about half a minute)")
         cpu = cpu_oracle_baseline(w, W, prompt, torch)
+        progress(f"{w.name}: CPU oracle {cpu['value']:.3f} tokens/s on {cpu['cores']} threads")
     del W
     torch.cuda.empty_cache()
 
