@@ -84,6 +84,28 @@ def test_both_engines_give_bitwise_equal_logits(P):
         assert torch.equal(a["logits"], b["logits"])
 
 
+def test_launch_tuning_does_not_change_results(P):
+    """Workgroup share of the draft stage, workgroups per compute unit, trips in flight per wave (the pipeline
+    schedule's stages use two, everything else one): per row the products are added in one order whatever wave
+    computes them, so tokens and logits are the same bit for bit."""
+    w = SMALL[1]
+    W = to_device(S.make_weights(w), "cuda")
+    prompt = S.make_prompt(w)
+    ref = _gpu_run(P, w, W, prompt, 30, P.MODE_VANILLA)
+    for kw in (dict(mode=P.MODE_OVERLAP, tune_draft_share=100), dict(mode=P.MODE_OVERLAP, tune_draft_share=30),
+               dict(mode=P.MODE_OVERLAP, tune_draft_share=1), dict(mode=P.MODE_OVERLAP, tune_wgs_per_cu=1),
+               dict(mode=P.MODE_VANILLA, tune_wgs_per_cu=4), dict(mode=P.MODE_PIPELINE),
+               dict(mode=P.MODE_PIPELINE, pipeline_stage_layers=1), dict(mode=P.MODE_PIPELINE, tune_wgs_per_cu=3)):
+        mode = kw.pop("mode")
+        r = _gpu_run(P, w, W, prompt, 30, mode, max_seq=len(prompt) + 30 + 6, **kw)
+        assert r["tokens"] == ref["tokens"] and torch.equal(r["logits"], ref["logits"]), kw
+    ss = P.Session(w, W, max_seq=64, mode=P.MODE_OVERLAP, tune_draft_share=30)
+    assert ss.launch_info()["draft_share_of_256"] == 77 and ss.launch_info()["streams"] == 2
+    ss.close()
+    with pytest.raises(P.PpsdError):
+        P.Session(w, W, max_seq=64, mode=P.MODE_OVERLAP, tune_draft_share=101)
+
+
 def test_drafts_equal_the_exit_heads_greedy_token(P):
     """Every compared draft is the exit head's argmax on the true prefix (oracle, fp64)."""
     w = S.WORKLOADS["C1"]
