@@ -383,7 +383,20 @@ void launch_layer(Launcher &L, int role, int layer, int stage, int xin_sel, int 
   L.after();
 
   L.before(kKDown);
-  if (deep)
+  // An input vector of which three workgroups per compute unit cannot each stage a whole copy, under a grid that
+  // then no longer fits the chip in one round (13B: 640 workgroups, two per compute unit): two column slabs.
+  // Where the grid fits anyway (8B: 512 workgroups) the whole vector is staged: one barrier less.
+  const int fit_whole = (int)((160 * 1024) / (x->xs_bytes(f) + 1024));
+  if (f > kSlabAbove && proj_grid > fit_whole * x->n_cu) {
+    const int blk = kWave * (16 / (int)sizeof(WT));
+    const int Cs = ((f + 1) / 2 + blk - 1) / blk * blk;
+    if (deep)
+      hipLaunchKernelGGL((k_proj_resid_slabs<WT, 2>), dim3(proj_grid), dim3(kGBlock), x->xs_bytes(Cs), L.s, cm, role,
+                         (const float *)mb, f, Cs, (const WT *)x->wdown[layer], d, xwork, xout_last_sel);
+    else
+      hipLaunchKernelGGL((k_proj_resid_slabs<WT, 1>), dim3(proj_grid), dim3(kGBlock), x->xs_bytes(Cs), L.s, cm, role,
+                         (const float *)mb, f, Cs, (const WT *)x->wdown[layer], d, xwork, xout_last_sel);
+  } else if (deep)
     hipLaunchKernelGGL((k_proj_resid<WT, 2>), dim3(proj_grid), dim3(kGBlock), x->xs_bytes(f), L.s, cm, role,
                        (const float *)mb, f, (const WT *)x->wdown[layer], d, xwork, xout_last_sel);
   else

@@ -420,12 +420,12 @@ struct NormStage {
   }
 };
 
-template <int BLOCK>
+template <int BLOCK, int PER = kCopyPer>
 struct CopyStage {
-  float4 xv[kCopyPer];
-  __device__ __forceinline__ void issue(const float *vin, int C) {   // C % 4 == 0
+  float4 xv[PER];
+  __device__ __forceinline__ void issue(const float *vin, int C) {   // C % 4 == 0, C <= 4 * PER * BLOCK
 #pragma unroll
-    for (int e = 0; e < kCopyPer; ++e) {
+    for (int e = 0; e < PER; ++e) {
       const int i = 4 * (threadIdx.x + e * BLOCK);
       xv[e] = i < C ? *(const float4 *)(vin + i) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
@@ -433,7 +433,7 @@ struct CopyStage {
   template <typename WT>
   __device__ __forceinline__ void finish(int C, float *xs) {
 #pragma unroll
-    for (int e = 0; e < kCopyPer; ++e) {
+    for (int e = 0; e < PER; ++e) {
       const int i = 4 * (threadIdx.x + e * BLOCK);
       if (i < C) *(float4 *)(xs + xs_pos<WT>(i)) = xv[e];
     }
@@ -539,6 +539,35 @@ struct Trips {
 #pragma unroll
         for (int r = 0; r < R; ++r) { s[r] = wave_sum(acc[r]); acc[r] = 0.f; }
         epi(ct, s);
+        ccb = 0;
+        ct += tw;
+      }
+    };
+    while (ct < n_tasks) {
+      step(a);
+      if (DEPTH == 2) {
+        if (!(ct < n_tasks)) break;
+        step(b);
+      }
+    }
+  }
+  // The same walk for ONE row per task (R = 1) whose FMA chain is handed in and out per lane instead of being
+  // reduced: begin(task) gives the lane's running sum so far (0, or what an earlier column slab left), end(task,
+  // sum) takes it back.  Used by the projection that walks its columns in slabs.
+  template <typename RowsFn, typename BeginFn, typename EndFn>
+  __device__ __forceinline__ void run_chained(const WT *(&rows)[R], int task, int n_tasks, int tw, int C, const float *xs,
+                                              RowsFn &&set_rows, BeginFn &&begin, EndFn &&end) {
+    static_assert(R == 1, "one row per task");
+    const int nblk = col_blocks<WT>(C);
+    int ct = task, ccb = 0;
+    float acc[1] = {0.f};
+    auto step = [&](Trip<WT, R, KB> &t) {
+      if (ccb == 0) acc[0] = begin(ct);
+      trip_consume<WT, R, KB>(t, xs, ccb, C, acc);
+      next(t, rows, n_tasks, tw, nblk, C, set_rows);
+      ccb += KB;
+      if (ccb >= nblk) {
+        end(ct, acc[0]);
         ccb = 0;
         ct += tw;
       }

@@ -421,6 +421,69 @@ __global__ __launch_bounds__(kGBlock) void k_proj_resid(Common c, int role, cons
   });
 }
 
+// The same projection for input vectors too long for three workgroups per compute unit to stage whole (more than
+// 13312 floats: the down projection of the 13B and 8B shapes, 55-57 KB): the columns are walked in slabs of Cs
+// (a multiple of a column block), one slab staged at a time, so a workgroup needs half the LDS and all of them are
+// resident at once.  With the whole vector staged, 640 workgroups of 55 KB ran two per compute unit in 1.25
+// rounds (13B: 29.2 us for 141.6 MB).  Every lane's FMA chain over its columns runs on from slab to slab (the
+// running sums of up to kSlabRows rows per wave wait in LDS while the next slab is staged) and is reduced once at
+// the end: per row the products are added in the single-slab order, the results are the same bit for bit.
+// Dynamic LDS = Cs floats padded to whole column blocks.
+constexpr int kSlabRows = 4;          // rows per wave whose running sums are kept across slabs; more rows: another round
+constexpr int kSlabAbove = 13312;     // input lengths above this are walked in slabs
+template <typename WT, int DEPTH>
+__global__ __launch_bounds__(kGBlock) void k_proj_resid_slabs(Common c, int role, const float *vin, int C, int Cs,
+                                                              const WT *W, int n_rows, int resid_sel, int out_sel) {
+  extern __shared__ __align__(16) float xs[];
+  __shared__ float carry[kSlabRows * kGBlock];
+  CopyStage<kGBlock, kCopyPer / 2> in;    // a slab is at most half of the longest vector
+  in.issue(vin, C < Cs ? C : Cs);         // the first slab; the input buffer's address never depends on the state
+  const StageIn si = stage_in(c, role);
+  if (!si.active) return;
+  constexpr int KB = kProjTripBlocks;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int nwg = active_workgroups(c, role);
+  if ((int)blockIdx.x >= nwg) return;
+  const int tw = nwg * kGWaves;
+  const float *resid = xslot(c, resid_sel);
+  float *out = xslot(c, out_sel);
+  // every wave of the workgroup goes through the same rounds and slabs (barriers); wave 0 has the most rows
+  const int first = blockIdx.x * kGWaves;
+  const int rows_wave0 = first < n_rows ? (n_rows - first + tw - 1) / tw : 0;
+  const int rounds = (rows_wave0 + kSlabRows - 1) / kSlabRows;
+  bool staged_first = false;
+  for (int r = 0; r < rounds; ++r) {
+    const int base = first + wave + r * kSlabRows * tw;            // this wave's first row of the round
+    const int limit = min(n_rows, base + kSlabRows * tw);          // its rows: base, base + tw, ... below limit
+    for (int c0 = 0; c0 < C; c0 += Cs) {
+      const int w = C - c0 < Cs ? C - c0 : Cs;
+      const WT *rows[1];
+      auto set_rows = [&](int task) { rows[0] = W + (size_t)task * C + c0; };
+      Trips<WT, 1, KB, DEPTH> trips;
+      trips.start(rows, base, limit, tw, w, set_rows);             // weights do not wait for the staging
+      if (staged_first) {
+        __syncthreads();                                           // the slab before has been read by every wave
+        in.issue(vin + c0, w);
+      }
+      in.template finish<WT>(w, xs);
+      staged_first = true;
+      int tb = 0, te = 0;                                          // index of the row inside the round
+      const bool last = c0 + Cs >= C;
+      trips.run_chained(rows, base, limit, tw, w, xs, set_rows,
+                        [&](int) { const float v = c0 == 0 ? 0.f : carry[tb * kGBlock + threadIdx.x]; ++tb; return v; },
+                        [&](int task, float sum) {
+                          if (!last) {
+                            carry[te * kGBlock + threadIdx.x] = sum;
+                          } else {
+                            const float s0 = wave_sum(sum);
+                            if (lane == 0) out[task] = resid[task] + s0;
+                          }
+                          ++te;
+                        });
+    }
+  }
+}
+
 // ------------------------------------------------------------------------------------------
 // a2 + a6: RMSNorm + gate/up GEMV + SwiGLU: mout[i] = silu(Wg[i,:].xn) * (Wu[i,:].xn).
 // A task is the pair (gate row i, up row i).
